@@ -1,0 +1,85 @@
+"""Pins for the DBuffer oracle: per-element brute force for pack / unpack, exact
+arithmetic (fractions / fsum) and special cases for shard_reduce."""
+import math
+
+import numpy as np
+
+from oracle import dbuffer as D
+from oracle import plan as P
+from workloads import WORKLOADS, gen_params, gen_partial
+
+
+def toy():
+    wl = WORKLOADS[1]
+    specs = [P.TensorSpec(t.rows, t.cols, t.mode) for t in wl.tensors]
+    return wl, P.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize)
+
+
+def test_pack_per_element_scatter_and_zero_padding():
+    wl, pl = toy()
+    params = gen_params(wl, seed=1)
+    db = D.ragged_pack(params, pl.offsets, pl.total)
+    want = [0] * pl.total
+    for src, l in zip(params, pl.offsets):
+        for i, v in enumerate(src.tolist()):
+            want[l + i] = v
+    assert db.tolist() == want
+    assert db.size == wl.world * pl.S
+    inside = np.zeros(pl.total, dtype=bool)
+    for s, l in zip(pl.specs, pl.offsets):
+        inside[l:l + s.e] = True
+    assert np.all(db[~inside] == 0)
+
+
+def test_unpack_inverts_pack():
+    wl, pl = toy()
+    params = gen_params(wl, seed=2)
+    db = D.ragged_pack(params, pl.offsets, pl.total)
+    outs = D.unpack_bf16(db, pl.offsets, [s.e for s in pl.specs])
+    for a, b in zip(params, outs):
+        assert np.array_equal(a, b)
+
+
+def test_bf16_widening_is_bit_placement():
+    bits = np.array([0x3F80, 0xBF80, 0x0001, 0x7F7F, 0x0000, 0x8000], dtype=np.uint16)
+    f = D.bf16_bits_to_f32(bits)
+    assert f[0] == 1.0 and f[1] == -1.0 and f[2] == 2.0 ** -133
+    assert f[3] == (2 - 2.0 ** -7) * 2.0 ** 127
+    assert f[4] == 0 and np.signbit(f[5])
+
+
+def test_reduce_exact_rational_on_sample():
+    wl, pl = toy()
+    k = 1
+    segs = pl.rank_segments(k)
+    parts = np.stack([gen_partial(wl, 3, w, pl.S) for w in range(wl.world)])
+    out = D.shard_reduce(parts, segs)
+    payload = np.zeros(pl.S, dtype=bool)
+    for _, _, d, n in segs:
+        payload[d:d + n] = True
+    assert np.all(out[~payload] == 0)
+    assert (~payload).any()
+    idx = np.flatnonzero(payload)[::97]
+    for i in idx.tolist():
+        vals = [float(D.bf16_bits_to_f32(parts[w, i:i + 1])[0]) for w in range(wl.world)]
+        exact = math.fsum(vals) / wl.world            # fsum is exact, one rounding in the division
+        assert out[i] == np.float32(exact)
+
+
+def test_reduce_special_cases():
+    S = 64
+    segs = [(0, 0, 0, 40), (1, 0, 48, 16)]
+    one = gen_partial(WORKLOADS[1], 4, 0, S).reshape(1, S)
+    out = D.shard_reduce(one, segs)
+    widened = D.bf16_bits_to_f32(one[0])
+    assert np.array_equal(out[:40], widened[:40]) and np.array_equal(out[48:], widened[48:])
+    assert np.all(out[40:48] == 0)                    # padding stays 0 whatever the partials hold
+    same = np.repeat(one, 8, axis=0)                  # equal partials, W a power of two
+    assert np.array_equal(D.shard_reduce(same, segs), out)
+    neg = same.copy()
+    neg[1::2] ^= 0x8000                               # alternate signs cancel exactly
+    assert np.all(D.shard_reduce(neg, segs) == 0)
+    # the mean, not the sum: W = 4 partials of 1.0, 2.0, 3.0, 6.0 -> 3.0
+    vals = np.array([[0x3F80], [0x4000], [0x4040], [0x40C0]], dtype=np.uint16)
+    assert D.shard_reduce(vals, [(0, 0, 0, 1)])[0] == 3.0
+    assert D.shard_reduce_abs_sum(vals)[0] == 12.0
