@@ -1,0 +1,168 @@
+/*
+ * raggedshard.h - C ABI of the MI355X (gfx950) RaggedShard / DBuffer hot path.
+ *
+ * One FSDP unit's tensors are laid out in a rank-major flat communication buffer
+ * ("DBuffer", paper Section 5) by the structure-aware planner (Section 5, problem
+ * statement and Algorithm 1) so that every sharding block stays whole on one rank
+ * (Section 4, block-wise RaggedShard).  Four HBM-bound kernels move data through it:
+ * ragged_pack, shard_reduce, FP8 block_quant and dequant_unpack.
+ *
+ * Conventions
+ *   - All sizes and offsets are in ELEMENTS unless a name says bytes.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP device
+ *     memory of the device the plan was uploaded to.  The library never takes
+ *     ownership of caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *     calls enqueue exactly one kernel, never synchronise and never allocate.
+ *   - Every function returning int returns RS_OK (0) or a negative RS_E* code and
+ *     never aborts; rs_strerror() names the code.
+ *   - bf16 = 2-byte bfloat16, codes = 1-byte OCP FP8 E4M3 ("fn": bias 7, no inf,
+ *     max 448), scales = fp32.
+ */
+#ifndef RAGGEDSHARD_H
+#define RAGGEDSHARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RS_OK = 0,
+  RS_EINVAL = -1,        /* bad argument (null, non-positive size, unknown mode, rank out of range) */
+  RS_EOVERFLOW = -2,     /* world * S does not fit in 62 bits */
+  RS_ENOMEM = -3,        /* host or device allocation failed */
+  RS_EALIGN = -4,        /* a device pointer or stride misses its required alignment */
+  RS_EUNSUPPORTED = -5,  /* operation undefined for this plan (e.g. FP8 on whole-matrix blocks) */
+  RS_EHIP = -6,          /* a HIP runtime call failed (no device, launch error) */
+  RS_ENOTUPLOADED = -7   /* device call before rs_plan_upload */
+};
+
+/* Sharding granularity of one tensor (Section 4: the atomic non-shardable block).
+ * Row-wise RaggedShard makes 2-D tiles contiguous: 128 whole rows hold a row of 128x128 tiles
+ * (Section 6.4, "128-row setting"). */
+enum {
+  RS_BLOCK_1x128 = 0,    /* 1-D: g = 128 elements; 2-D: g = one row; FP8 blocks are 1x128 runs per row */
+  RS_BLOCK_128x128 = 1,  /* 2-D only: g = 128 rows; FP8 blocks are 128x128 tiles, edge tiles partial */
+  RS_BLOCK_WHOLE = 2,    /* g = e: the whole tensor on one rank (matrix optimisers, Section 6.3); no FP8 */
+  RS_BLOCK_EXPLICIT = 3  /* g = g_explicit elements; no FP8 */
+};
+
+typedef struct rs_tensor_desc {
+  int64_t rows;        /* R, or the length n of a 1-D tensor */
+  int64_t cols;        /* C; 0 marks a 1-D tensor */
+  int32_t block_mode;  /* RS_BLOCK_* */
+  int32_t reserved;    /* must be 0 */
+  int64_t g_explicit;  /* used by RS_BLOCK_EXPLICIT only */
+} rs_tensor_desc;
+
+/* n elements of tensor `tensor`, starting at its element src_off, live at element dst_off
+ * of one rank's region [rank*S, (rank+1)*S). */
+typedef struct rs_segment {
+  int32_t tensor;
+  int32_t reserved;
+  int64_t src_off;
+  int64_t dst_off;
+  int64_t n;
+} rs_segment;
+
+typedef struct rs_plan rs_plan;                  /* layout plan + device tables, library-owned */
+typedef struct rs_tensor_table rs_tensor_table;  /* device copy of n tensor base pointers */
+
+int rs_version(void);
+const char* rs_strerror(int code);
+
+/* ---- plan (host only; needs no GPU) ------------------------------------------------------
+ * Solves  min S  s.t. each tensor is one contiguous interval [l_t, l_t + e_t) of the
+ * world*S-element buffer, intervals are disjoint, and every interior rank boundary k*S
+ * that falls inside a tensor falls on a multiple of g_t from l_t  (Section 5, the
+ * minimisation problem), by Algorithm 1 for the tensor order given: candidate units are
+ * g_coll and the running LCM of the ascending distinct block sizes; for each unit the
+ * smallest feasible multiple is found by bisection with CheckValidShard, which places each
+ * tensor at its earliest feasible start.
+ *   g_coll = align_bytes / min_itemsize elements (S is a multiple of it, so every rank
+ *   region starts align_bytes-aligned for every dtype that shares the plan);
+ *   tensor_align_elems = alignment of every l_t, must divide g_coll; 0 selects g_coll.
+ * descs: host array of n descriptors, copied.  *out is owned by the library until
+ * rs_plan_destroy.  Errors: RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM. */
+int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                   int min_itemsize, int tensor_align_elems, rs_plan** out);
+void rs_plan_destroy(rs_plan* plan);
+
+/* CheckValidShard(S) of Algorithm 1 on its own: 1 feasible, 0 infeasible, <0 error.
+ * S must be a positive multiple of tensor_align_elems (0 = g_coll). */
+int rs_check_valid_shard(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                         int min_itemsize, int tensor_align_elems, int64_t S);
+
+/* Queries (pure).  Output arrays are caller-owned host memory. */
+int rs_plan_num_tensors(const rs_plan* plan);
+int rs_plan_world(const rs_plan* plan);
+int64_t rs_plan_shard_elems(const rs_plan* plan);    /* S */
+int64_t rs_plan_total_elems(const rs_plan* plan);    /* world * S */
+int64_t rs_plan_payload_elems(const rs_plan* plan);  /* sum of e_t */
+int64_t rs_plan_padding_elems(const rs_plan* plan);  /* world * S - payload */
+int64_t rs_plan_num_scales(const rs_plan* plan);     /* FP8 blocks of the whole unit */
+/* l_t for every tensor; cap must be >= n. */
+int rs_plan_offsets(const rs_plan* plan, int64_t* out, int cap);
+/* first scale index of every tensor plus the total (n + 1 values; cap >= n + 1).  Scales form
+ * one flat fp32 array in buffer order: tensor-major, then block row, then block column. */
+int rs_plan_scale_bases(const rs_plan* plan, int64_t* out, int cap);
+/* [lo, hi): the scales rank owns; contiguous because blocks are whole on a rank. */
+int rs_plan_scale_range(const rs_plan* plan, int rank, int64_t* lo, int64_t* hi);
+/* Writes up to cap segments of the rank and returns how many the rank has (may exceed cap). */
+int rs_plan_rank_segments(const rs_plan* plan, int rank, rs_segment* out, int cap);
+
+/* ---- device set-up -------------------------------------------------------------------------
+ * Builds the plan's device tables on HIP device `device` (hipMalloc + copy, synchronous).
+ * Call once before any device call; freed by rs_plan_destroy.  RS_EHIP without a GPU. */
+int rs_plan_upload(rs_plan* plan, int device);
+
+/* The DBuffer's persistent tensor -> address mapping (Section 5): uploads n device base
+ * pointers (host array `ptrs`, one per tensor, each tensor contiguous row-major) to the
+ * plan's device.  The table may be reused by any number of calls. */
+int rs_tensor_table_create(const rs_plan* plan, const void* const* ptrs, rs_tensor_table** out);
+void rs_tensor_table_destroy(rs_tensor_table* table);
+
+/* ---- ragged_pack: the fused group copy + zero of the DBuffer (Section 5) ---------------------
+ * dbuf[l_t + i] = src_t[i] for every tensor, every other element of dbuf[0, world*S) = +0.
+ * src: table of bf16 device tensors; dbuf: device, world*S bf16, 16-byte aligned (RS_EALIGN). */
+int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* stream);
+
+/* Inverse group copy: dst_t[i] = dbuf[l_t + i] (bf16 DBuffer -> per-tensor bf16). */
+int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream);
+
+/* ---- shard_reduce: the arithmetic of the gradient ReduceScatter as one rank sees it --------
+ * (Section 2.3).  out[i] = (1/world) * sum_w partials[w*row_stride + i] for i in the
+ * payload of rank's region, 0 on its padding; fp32 accumulation in a fixed order.
+ * partials: device, `world` rows of S bf16, row_stride elements apart (multiple of 8,
+ * base 16-byte aligned); out: device, S fp32, 16-byte aligned. */
+int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride,
+              float* out, void* stream);
+
+/* ---- block_quant: communication-free block-wise FP8 of the local shard (Sections 2.1, 4) ----
+ * Per block: amax = max|x|, scale = amax/448 (fp32), code = E4M3 RNE of clamp(x/scale, +-448);
+ * an all-zero block gives scale 0 and codes 0x00.  Padding codes are 0x00.
+ * rank >= 0: shard/codes point at that rank's region (S elements), scales at its slice
+ * [lo, hi) of the scale array.  rank == -1: all ranks at once (world*S elements, all scales).
+ * shard: device bf16, codes: device uint8, both 16-byte aligned.  RS_EUNSUPPORTED if the plan
+ * holds a tensor without FP8 blocks. */
+int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes, float* scales,
+                void* stream);
+
+/* ---- dequant_unpack: gathered FP8 unit -> per-parameter bf16 --------------------------------
+ * dst_t[i] = bf16_rne( value(codes[l_t + i]) * scales[block of i] ).
+ * codes: device, world*S uint8, 16-byte aligned; scales: device, all of the unit's scales. */
+int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
+              const rs_tensor_table* dst, void* stream);
+
+/* ---- bandwidth probe: plain 16-byte-vector device copy of `bytes` (multiple of 16) ---------
+ * Not part of the method: the measured ceiling the four kernels are held against, and the
+ * known-size launch that calibrates HBM byte counters. */
+int rs_copy_probe(void* dst, const void* src, int64_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAGGEDSHARD_H */

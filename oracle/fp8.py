@@ -120,10 +120,18 @@ def dequantise_tensor(codes: np.ndarray, scales: np.ndarray, spec: TensorSpec) -
     """Step 4 for one tensor: bf16 bits (flat) from its codes and its scales."""
     R, C, bh, bw = _as_2d(spec)
     nbr, nbc = -(-R // bh), -(-C // bw)
-    vals = decode_table()[np.asarray(codes, dtype=np.uint8).reshape(R, C)]
+    tab = decode_table()
+    cod = np.asarray(codes, dtype=np.uint8).reshape(R, C)
     sc = np.asarray(scales, dtype=np.float32).reshape(nbr, nbc)
-    per_elem = np.repeat(np.repeat(sc, bh, axis=0)[:R], bw, axis=1)[:, :C]
-    return f32_to_bf16_bits(vals * per_elem).reshape(-1)
+    out = np.empty((R, C), dtype=np.uint16)
+    for br in range(nbr):
+        rows = cod[br * bh:(br + 1) * bh]
+        h = rows.shape[0]
+        wide = np.zeros((h, nbc * bw), dtype=np.uint8)
+        wide[:, :C] = rows
+        v = tab[wide].reshape(h, nbc, bw) * sc[br][None, :, None]      # fp32 * fp32
+        out[br * bh:(br + 1) * bh] = f32_to_bf16_bits(v).reshape(h, nbc * bw)[:, :C]
+    return out.reshape(-1)
 
 
 def block_quant_all(plan: Plan, db: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

@@ -1,0 +1,244 @@
+"""ctypes binding of libraggedshard.so: the same entry points as include/raggedshard.h, with
+Python argument marshalling and nothing else.  torch tensors are used for device memory and
+streams only; every step of the path runs in the library's kernels.  There is no fallback:
+a missing library or a failing call raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Sequence, Tuple
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libraggedshard.so")
+
+RS_BLOCK_1x128, RS_BLOCK_128x128, RS_BLOCK_WHOLE, RS_BLOCK_EXPLICIT = 0, 1, 2, 3
+RS_OK, RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM, RS_EALIGN, RS_EUNSUPPORTED, RS_EHIP, RS_ENOTUPLOADED = (
+    0, -1, -2, -3, -4, -5, -6, -7)
+
+EXPORTS = [
+    "rs_version", "rs_strerror", "rs_plan_create", "rs_plan_destroy", "rs_check_valid_shard",
+    "rs_plan_num_tensors", "rs_plan_world", "rs_plan_shard_elems", "rs_plan_total_elems",
+    "rs_plan_payload_elems", "rs_plan_padding_elems", "rs_plan_num_scales", "rs_plan_offsets",
+    "rs_plan_scale_bases", "rs_plan_scale_range", "rs_plan_rank_segments", "rs_plan_upload",
+    "rs_tensor_table_create", "rs_tensor_table_destroy", "rs_pack", "rs_unpack_bf16", "rs_reduce",
+    "rs_quantize", "rs_unpack", "rs_copy_probe",
+]
+
+
+class rs_tensor_desc(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("block_mode", C.c_int32),
+                ("reserved", C.c_int32), ("g_explicit", C.c_int64)]
+
+
+class rs_segment(C.Structure):
+    _fields_ = [("tensor", C.c_int32), ("reserved", C.c_int32), ("src_off", C.c_int64),
+                ("dst_off", C.c_int64), ("n", C.c_int64)]
+
+
+class RaggedShardError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {rs_strerror(code)} ({code})")
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_22437_amd.build`; "
+                      "there is no fallback path")
+_lib = C.CDLL(LIB_PATH)
+
+_P = C.c_void_p
+_lib.rs_version.restype = C.c_int
+_lib.rs_strerror.restype = C.c_char_p
+_lib.rs_strerror.argtypes = [C.c_int]
+_lib.rs_plan_create.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                C.POINTER(_P)]
+_lib.rs_plan_destroy.argtypes = [_P]
+_lib.rs_plan_destroy.restype = None
+_lib.rs_check_valid_shard.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int,
+                                      C.c_int, C.c_int64]
+for _name in ("rs_plan_num_tensors", "rs_plan_world"):
+    getattr(_lib, _name).argtypes = [_P]
+    getattr(_lib, _name).restype = C.c_int
+for _name in ("rs_plan_shard_elems", "rs_plan_total_elems", "rs_plan_payload_elems",
+              "rs_plan_padding_elems", "rs_plan_num_scales"):
+    getattr(_lib, _name).argtypes = [_P]
+    getattr(_lib, _name).restype = C.c_int64
+_lib.rs_plan_offsets.argtypes = [_P, C.POINTER(C.c_int64), C.c_int]
+_lib.rs_plan_scale_bases.argtypes = [_P, C.POINTER(C.c_int64), C.c_int]
+_lib.rs_plan_scale_range.argtypes = [_P, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+_lib.rs_plan_rank_segments.argtypes = [_P, C.c_int, C.POINTER(rs_segment), C.c_int]
+_lib.rs_plan_upload.argtypes = [_P, C.c_int]
+_lib.rs_tensor_table_create.argtypes = [_P, C.POINTER(_P), C.POINTER(_P)]
+_lib.rs_tensor_table_destroy.argtypes = [_P]
+_lib.rs_tensor_table_destroy.restype = None
+_lib.rs_pack.argtypes = [_P, _P, _P, _P]
+_lib.rs_unpack_bf16.argtypes = [_P, _P, _P, _P]
+_lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
+_lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
+_lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
+_lib.rs_copy_probe.argtypes = [_P, _P, C.c_int64, _P]
+
+
+def _check(code: int, where: str) -> int:
+    if code < 0:
+        raise RaggedShardError(code, where)
+    return code
+
+
+def _descs(tensors: Sequence[Tuple]) -> "C.Array":
+    arr = (rs_tensor_desc * max(1, len(tensors)))()
+    for i, t in enumerate(tensors):
+        rows, cols, mode = t[0], t[1], t[2]
+        arr[i] = rs_tensor_desc(int(rows), int(cols), int(mode), 0, int(t[3]) if len(t) > 3 else 0)
+    return arr
+
+
+def _ptr(x) -> int:
+    """Device (or host) address of a torch tensor, or a raw integer address."""
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+# ---- same names as the C ABI ---------------------------------------------------------------
+
+def rs_version() -> int:
+    return _lib.rs_version()
+
+
+def rs_strerror(code: int) -> str:
+    return _lib.rs_strerror(int(code)).decode()
+
+
+def rs_plan_create(tensors: Sequence[Tuple], world: int, align_bytes: int = 16, min_itemsize: int = 1,
+                   tensor_align_elems: int = 0) -> int:
+    """tensors: (rows, cols, block_mode[, g_explicit]) per tensor.  Returns the plan handle."""
+    out = _P()
+    _check(_lib.rs_plan_create(_descs(tensors), len(tensors), int(world), int(align_bytes),
+                               int(min_itemsize), int(tensor_align_elems), C.byref(out)),
+           "rs_plan_create")
+    return out.value
+
+
+def rs_plan_destroy(plan: int) -> None:
+    _lib.rs_plan_destroy(plan)
+
+
+def rs_check_valid_shard(tensors, world, align_bytes, min_itemsize, tensor_align_elems, S) -> bool:
+    return bool(_check(_lib.rs_check_valid_shard(_descs(tensors), len(tensors), int(world),
+                                                 int(align_bytes), int(min_itemsize),
+                                                 int(tensor_align_elems), int(S)),
+                       "rs_check_valid_shard"))
+
+
+def rs_plan_num_tensors(plan) -> int:
+    return _check(_lib.rs_plan_num_tensors(plan), "rs_plan_num_tensors")
+
+
+def rs_plan_world(plan) -> int:
+    return _check(_lib.rs_plan_world(plan), "rs_plan_world")
+
+
+def rs_plan_shard_elems(plan) -> int:
+    return _check(_lib.rs_plan_shard_elems(plan), "rs_plan_shard_elems")
+
+
+def rs_plan_total_elems(plan) -> int:
+    return _check(_lib.rs_plan_total_elems(plan), "rs_plan_total_elems")
+
+
+def rs_plan_payload_elems(plan) -> int:
+    return _check(_lib.rs_plan_payload_elems(plan), "rs_plan_payload_elems")
+
+
+def rs_plan_padding_elems(plan) -> int:
+    return _check(_lib.rs_plan_padding_elems(plan), "rs_plan_padding_elems")
+
+
+def rs_plan_num_scales(plan) -> int:
+    return _check(_lib.rs_plan_num_scales(plan), "rs_plan_num_scales")
+
+
+def rs_plan_offsets(plan) -> List[int]:
+    n = rs_plan_num_tensors(plan)
+    out = (C.c_int64 * n)()
+    _check(_lib.rs_plan_offsets(plan, out, n), "rs_plan_offsets")
+    return list(out)
+
+
+def rs_plan_scale_bases(plan) -> List[int]:
+    n = rs_plan_num_tensors(plan)
+    out = (C.c_int64 * (n + 1))()
+    _check(_lib.rs_plan_scale_bases(plan, out, n + 1), "rs_plan_scale_bases")
+    return list(out)
+
+
+def rs_plan_scale_range(plan, rank: int) -> Tuple[int, int]:
+    lo, hi = C.c_int64(), C.c_int64()
+    _check(_lib.rs_plan_scale_range(plan, int(rank), C.byref(lo), C.byref(hi)), "rs_plan_scale_range")
+    return lo.value, hi.value
+
+
+def rs_plan_rank_segments(plan, rank: int) -> List[Tuple[int, int, int, int]]:
+    cnt = _check(_lib.rs_plan_rank_segments(plan, int(rank), None, 0), "rs_plan_rank_segments")
+    buf = (rs_segment * max(1, cnt))()
+    _check(_lib.rs_plan_rank_segments(plan, int(rank), buf, cnt), "rs_plan_rank_segments")
+    return [(s.tensor, s.src_off, s.dst_off, s.n) for s in buf[:cnt]]
+
+
+def rs_plan_upload(plan, device: int = 0) -> None:
+    _check(_lib.rs_plan_upload(plan, int(device)), "rs_plan_upload")
+
+
+def rs_tensor_table_create(plan, tensors: Sequence) -> int:
+    """tensors: torch device tensors (contiguous) or raw device addresses, one per plan tensor."""
+    n = len(tensors)
+    arr = (_P * max(1, n))()
+    for i, t in enumerate(tensors):
+        if hasattr(t, "is_contiguous") and not t.is_contiguous():
+            raise ValueError("tensor table entries must be contiguous")
+        arr[i] = _ptr(t)
+    if n != rs_plan_num_tensors(plan):
+        raise ValueError("one pointer per plan tensor is required")
+    out = _P()
+    _check(_lib.rs_tensor_table_create(plan, arr, C.byref(out)), "rs_tensor_table_create")
+    return out.value
+
+
+def rs_tensor_table_destroy(table) -> None:
+    _lib.rs_tensor_table_destroy(table)
+
+
+def rs_pack(plan, src_table, dbuf, stream=None) -> None:
+    _check(_lib.rs_pack(plan, src_table, _ptr(dbuf), _stream(stream)), "rs_pack")
+
+
+def rs_unpack_bf16(plan, dbuf, dst_table, stream=None) -> None:
+    _check(_lib.rs_unpack_bf16(plan, _ptr(dbuf), dst_table, _stream(stream)), "rs_unpack_bf16")
+
+
+def rs_reduce(plan, rank: int, partials, row_stride: int, out, stream=None) -> None:
+    _check(_lib.rs_reduce(plan, int(rank), _ptr(partials), int(row_stride), _ptr(out), _stream(stream)),
+           "rs_reduce")
+
+
+def rs_quantize(plan, rank: int, shard, codes, scales, stream=None) -> None:
+    _check(_lib.rs_quantize(plan, int(rank), _ptr(shard), _ptr(codes), _ptr(scales), _stream(stream)),
+           "rs_quantize")
+
+
+def rs_unpack(plan, codes, scales, dst_table, stream=None) -> None:
+    _check(_lib.rs_unpack(plan, _ptr(codes), _ptr(scales), dst_table, _stream(stream)), "rs_unpack")
+
+
+def rs_copy_probe(dst, src, nbytes: int, stream=None) -> None:
+    _check(_lib.rs_copy_probe(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)), "rs_copy_probe")
+
+
+def raw_call(name: str, *args) -> int:
+    """Call an entry point with raw ctypes arguments and get the raw return code (error-path tests)."""
+    return getattr(_lib, name)(*args)

@@ -1,0 +1,348 @@
+// C ABI of the library: argument checking, plan objects, device tables, kernel launches.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <new>
+
+#include "raggedshard.h"
+#include "rs_internal.h"
+#include "rs_launch.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// Device calls require the plan's device to be the caller's current one.
+int check_device(const rs_plan* plan) {
+  if (!plan) return RS_EINVAL;
+  if (plan->dev.device < 0) return RS_ENOTUPLOADED;
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return RS_EHIP;
+  return cur == plan->dev.device ? RS_OK : RS_EINVAL;
+}
+
+int check_table(const rs_plan* plan, const rs_tensor_table* tab) {
+  if (!tab || !tab->ptrs) return RS_EINVAL;
+  if (tab->owner != plan || tab->n != int(plan->t.size())) return RS_EINVAL;
+  return RS_OK;
+}
+
+template <typename T>
+int upload(const std::vector<T>& host, T** dev) {
+  *dev = nullptr;
+  if (host.empty()) return RS_OK;
+  const size_t bytes = host.size() * sizeof(T);
+  if (hipMalloc(reinterpret_cast<void**>(dev), bytes) != hipSuccess) return RS_ENOMEM;
+  if (hipMemcpy(*dev, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return RS_EHIP;
+  return RS_OK;
+}
+
+void free_device_tables(rs::DeviceTables* d) {
+  if (d->device < 0) return;
+  int cur = -1;
+  const bool have = hipGetDevice(&cur) == hipSuccess;
+  if (have && cur != d->device) (void)hipSetDevice(d->device);
+  if (d->tensors) (void)hipFree(d->tensors);
+  if (d->gran_first) (void)hipFree(d->gran_first);
+  if (d->items) (void)hipFree(d->items);
+  if (have && cur != d->device) (void)hipSetDevice(cur);
+  *d = rs::DeviceTables{};
+}
+
+// Number of scales in front of buffer position x: the blocks of all whole granules (a row of
+// tiles, a row of 1x128 runs, or one 1-D run) that start before x.
+int64_t scales_in_front(const rs_plan& plan, int64_t x) {
+  int64_t cnt = 0;
+  for (const rs::TensorHost& h : plan.t) {
+    if (!h.quant || x <= h.ell) continue;
+    int64_t granules = (x - h.ell + h.g - 1) / h.g;
+    if (granules > h.u) granules = h.u;
+    cnt += granules * (h.cols > 0 ? h.nbc : 1);
+  }
+  return cnt;
+}
+
+int build_plan(const rs_tensor_desc* descs, int n, int world, int align_bytes, int min_itemsize,
+               int tensor_align_elems, std::vector<rs::TensorHost>* t, int64_t* g_coll, int64_t* A) {
+  if (!descs || n <= 0 || world <= 0 || align_bytes <= 0 || min_itemsize <= 0 ||
+      tensor_align_elems < 0)
+    return RS_EINVAL;
+  if (align_bytes % min_itemsize != 0) return RS_EINVAL;
+  *g_coll = align_bytes / min_itemsize;
+  *A = tensor_align_elems == 0 ? *g_coll : tensor_align_elems;
+  if (*g_coll % *A != 0) return RS_EINVAL;
+  return rs::describe_tensors(descs, n, t);
+}
+
+}  // namespace
+
+extern "C" {
+
+int rs_version(void) { return 100; }
+
+const char* rs_strerror(int code) {
+  switch (code) {
+    case RS_OK: return "ok";
+    case RS_EINVAL: return "invalid argument";
+    case RS_EOVERFLOW: return "size overflow";
+    case RS_ENOMEM: return "out of memory";
+    case RS_EALIGN: return "pointer or stride not aligned";
+    case RS_EUNSUPPORTED: return "operation not supported for this plan";
+    case RS_EHIP: return "HIP runtime error";
+    case RS_ENOTUPLOADED: return "plan tables not uploaded to a device";
+    default: return "unknown error";
+  }
+}
+
+int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_bytes, int min_itemsize,
+                   int tensor_align_elems, rs_plan** out) {
+  if (!out) return RS_EINVAL;
+  *out = nullptr;
+  try {
+    rs_plan* p = new rs_plan();
+    int rc = build_plan(descs, n, world, align_bytes, min_itemsize, tensor_align_elems, &p->t,
+                        &p->g_coll, &p->A);
+    if (rc == RS_OK) {
+      p->world = world;
+      rc = rs::solve_shard_size(p->t, p->world, p->g_coll, p->A, &p->S);
+    }
+    if (rc == RS_OK) {
+      std::vector<int64_t> starts;
+      if (!rs::check_valid_shard(p->t, p->world, p->S, p->A, &starts)) rc = RS_EINVAL;
+      int64_t sb = 0;
+      p->all_quant = true;
+      for (size_t i = 0; rc == RS_OK && i < p->t.size(); ++i) {
+        p->t[i].ell = starts[i];
+        p->t[i].scale_base = sb;
+        sb += p->t[i].nbr * p->t[i].nbc;
+        p->payload += p->t[i].e;
+        p->all_quant = p->all_quant && p->t[i].quant;
+      }
+      p->num_scales = sb;
+      if (rc == RS_OK) {
+        p->scale_begin.resize(size_t(world) + 1);
+        for (int k = 0; k <= world; ++k) p->scale_begin[size_t(k)] = scales_in_front(*p, int64_t(k) * p->S);
+      }
+    }
+    if (rc != RS_OK) {
+      delete p;
+      return rc;
+    }
+    *out = p;
+    return RS_OK;
+  } catch (const std::bad_alloc&) {
+    return RS_ENOMEM;
+  }
+}
+
+void rs_plan_destroy(rs_plan* plan) {
+  if (!plan) return;
+  free_device_tables(&plan->dev);
+  delete plan;
+}
+
+int rs_check_valid_shard(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                         int min_itemsize, int tensor_align_elems, int64_t S) {
+  try {
+    std::vector<rs::TensorHost> t;
+    int64_t g_coll = 0, A = 0;
+    const int rc = build_plan(descs, n, world, align_bytes, min_itemsize, tensor_align_elems, &t,
+                              &g_coll, &A);
+    if (rc != RS_OK) return rc;
+    if (S <= 0 || S % A != 0) return RS_EINVAL;
+    if (S >= (int64_t(1) << 62) / world) return RS_EOVERFLOW;
+    return rs::check_valid_shard(t, world, S, A, nullptr) ? 1 : 0;
+  } catch (const std::bad_alloc&) {
+    return RS_ENOMEM;
+  }
+}
+
+int rs_plan_num_tensors(const rs_plan* plan) { return plan ? int(plan->t.size()) : RS_EINVAL; }
+int rs_plan_world(const rs_plan* plan) { return plan ? int(plan->world) : RS_EINVAL; }
+int64_t rs_plan_shard_elems(const rs_plan* plan) { return plan ? plan->S : RS_EINVAL; }
+int64_t rs_plan_total_elems(const rs_plan* plan) { return plan ? plan->S * plan->world : RS_EINVAL; }
+int64_t rs_plan_payload_elems(const rs_plan* plan) { return plan ? plan->payload : RS_EINVAL; }
+int64_t rs_plan_padding_elems(const rs_plan* plan) {
+  return plan ? plan->S * plan->world - plan->payload : RS_EINVAL;
+}
+int64_t rs_plan_num_scales(const rs_plan* plan) { return plan ? plan->num_scales : RS_EINVAL; }
+
+int rs_plan_offsets(const rs_plan* plan, int64_t* out, int cap) {
+  if (!plan || !out || cap < int(plan->t.size())) return RS_EINVAL;
+  for (size_t i = 0; i < plan->t.size(); ++i) out[i] = plan->t[i].ell;
+  return RS_OK;
+}
+
+int rs_plan_scale_bases(const rs_plan* plan, int64_t* out, int cap) {
+  if (!plan || !out || cap < int(plan->t.size()) + 1) return RS_EINVAL;
+  for (size_t i = 0; i < plan->t.size(); ++i) out[i] = plan->t[i].scale_base;
+  out[plan->t.size()] = plan->num_scales;
+  return RS_OK;
+}
+
+int rs_plan_scale_range(const rs_plan* plan, int rank, int64_t* lo, int64_t* hi) {
+  if (!plan || !lo || !hi || rank < 0 || rank >= plan->world) return RS_EINVAL;
+  *lo = plan->scale_begin[size_t(rank)];
+  *hi = plan->scale_begin[size_t(rank) + 1];
+  return RS_OK;
+}
+
+int rs_plan_rank_segments(const rs_plan* plan, int rank, rs_segment* out, int cap) {
+  if (!plan || rank < 0 || rank >= plan->world || cap < 0 || (cap > 0 && !out)) return RS_EINVAL;
+  const int64_t lo = int64_t(rank) * plan->S, hi = lo + plan->S;
+  int count = 0;
+  for (size_t i = 0; i < plan->t.size(); ++i) {
+    const rs::TensorHost& h = plan->t[i];
+    const int64_t a = h.ell > lo ? h.ell : lo;
+    const int64_t b = h.ell + h.e < hi ? h.ell + h.e : hi;
+    if (a >= b) continue;
+    if (count < cap) {
+      rs_segment s{};
+      s.tensor = int32_t(i);
+      s.src_off = a - h.ell;
+      s.dst_off = a - lo;
+      s.n = b - a;
+      out[count] = s;
+    }
+    ++count;
+  }
+  return count;
+}
+
+int rs_plan_upload(rs_plan* plan, int device) {
+  if (!plan || device < 0) return RS_EINVAL;
+  if (plan->S % 8 != 0) return RS_EUNSUPPORTED;  // bf16 rank regions must start 16-byte aligned
+  if (plan->dev.device >= 0) return plan->dev.device == device ? RS_OK : RS_EINVAL;
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return RS_EHIP;
+  if (cur != device && hipSetDevice(device) != hipSuccess) return RS_EHIP;
+  int rc = RS_OK;
+  try {
+    rs::build_host_tables(plan->t, plan->world, plan->S, plan->all_quant, &plan->host);
+    rs::DeviceTables d;
+    d.device = device;
+    rc = upload(plan->host.tensors, &d.tensors);
+    if (rc == RS_OK) rc = upload(plan->host.gran_first, &d.gran_first);
+    if (rc == RS_OK) rc = upload(plan->host.items, &d.items);
+    if (rc == RS_OK) {
+      plan->dev = d;
+    } else {
+      free_device_tables(&d);
+    }
+    // the big host mirrors are not needed again
+    std::vector<int32_t>().swap(plan->host.gran_first);
+    std::vector<rs::Item>().swap(plan->host.items);
+  } catch (const std::bad_alloc&) {
+    rc = RS_ENOMEM;
+  }
+  if (cur != device) (void)hipSetDevice(cur);
+  return rc;
+}
+
+int rs_tensor_table_create(const rs_plan* plan, const void* const* ptrs, rs_tensor_table** out) {
+  if (!out) return RS_EINVAL;
+  *out = nullptr;
+  if (!ptrs) return RS_EINVAL;
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  const int n = int(plan->t.size());
+  for (int i = 0; i < n; ++i) {
+    if (!ptrs[i]) return RS_EINVAL;
+    if (reinterpret_cast<uintptr_t>(ptrs[i]) & 1) return RS_EALIGN;  // bf16 element alignment
+  }
+  rs_tensor_table* tab = new (std::nothrow) rs_tensor_table();
+  if (!tab) return RS_ENOMEM;
+  tab->device = plan->dev.device;
+  tab->owner = plan;
+  tab->n = n;
+  if (hipMalloc(reinterpret_cast<void**>(&tab->ptrs), sizeof(void*) * n) != hipSuccess) {
+    delete tab;
+    return RS_ENOMEM;
+  }
+  if (hipMemcpy(tab->ptrs, ptrs, sizeof(void*) * n, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(tab->ptrs);
+    delete tab;
+    return RS_EHIP;
+  }
+  *out = tab;
+  return RS_OK;
+}
+
+void rs_tensor_table_destroy(rs_tensor_table* table) {
+  if (!table) return;
+  if (table->ptrs) (void)hipFree(table->ptrs);
+  delete table;
+}
+
+int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* stream) {
+  int rc = check_device(plan);
+  if (rc == RS_OK) rc = check_table(plan, src);
+  if (rc != RS_OK) return rc;
+  if (!dbuf) return RS_EINVAL;
+  if (!aligned16(dbuf)) return RS_EALIGN;
+  return rs::launch_group_copy(false, plan->dev, int(plan->t.size()), src->ptrs, dbuf, plan->S,
+                               plan->host.granules_per_rank, plan->world,
+                               static_cast<hipStream_t>(stream));
+}
+
+int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream) {
+  int rc = check_device(plan);
+  if (rc == RS_OK) rc = check_table(plan, dst);
+  if (rc != RS_OK) return rc;
+  if (!dbuf) return RS_EINVAL;
+  if (!aligned16(dbuf)) return RS_EALIGN;
+  return rs::launch_group_copy(true, plan->dev, int(plan->t.size()), dst->ptrs,
+                               const_cast<void*>(dbuf), plan->S, plan->host.granules_per_rank,
+                               plan->world, static_cast<hipStream_t>(stream));
+}
+
+int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride, float* out,
+              void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!partials || !out || rank < 0 || rank >= plan->world || row_stride < plan->S) return RS_EINVAL;
+  if (!aligned16(partials) || !aligned16(out) || row_stride % 8 != 0) return RS_EALIGN;
+  return rs::launch_shard_reduce(plan->dev, int(plan->t.size()), partials, row_stride, out, plan->S,
+                                 plan->host.granules_per_rank, rank, int(plan->world),
+                                 static_cast<hipStream_t>(stream));
+}
+
+int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes, float* scales,
+                void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_quant) return RS_EUNSUPPORTED;
+  if (!shard || !codes || !scales || rank < -1 || rank >= plan->world) return RS_EINVAL;
+  if (!aligned16(shard) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3))
+    return RS_EALIGN;
+  const std::vector<int64_t>& ib = plan->host.item_begin;
+  int64_t first = 0, count = ib[size_t(plan->world)], elem_base = 0, scale_off = 0;
+  if (rank >= 0) {
+    first = ib[size_t(rank)];
+    count = ib[size_t(rank) + 1] - first;
+    elem_base = int64_t(rank) * plan->S;
+    scale_off = plan->scale_begin[size_t(rank)];
+  }
+  return rs::launch_block_quant(plan->dev, first, count, shard, codes, scales, elem_base, scale_off,
+                                static_cast<hipStream_t>(stream));
+}
+
+int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
+              const rs_tensor_table* dst, void* stream) {
+  int rc = check_device(plan);
+  if (rc == RS_OK) rc = check_table(plan, dst);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_quant) return RS_EUNSUPPORTED;
+  if (!codes || !scales) return RS_EINVAL;
+  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3)) return RS_EALIGN;
+  return rs::launch_dequant_unpack(plan->dev, plan->host.item_begin[size_t(plan->world)], codes,
+                                   scales, dst->ptrs, static_cast<hipStream_t>(stream));
+}
+
+int rs_copy_probe(void* dst, const void* src, int64_t bytes, void* stream) {
+  if (!dst || !src || bytes < 0 || bytes % 16 != 0) return RS_EINVAL;
+  if (!aligned16(dst) || !aligned16(src)) return RS_EALIGN;
+  return rs::launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

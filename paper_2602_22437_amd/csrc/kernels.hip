@@ -1,0 +1,511 @@
+// HIP kernels for gfx950 (CDNA4, wave64): the four HBM-bound movers of the DBuffer hot path.
+//
+// Common shape: 256-thread workgroups, one 16-byte vector per lane per access, a very large
+// grid (a plain copy on MI355X is fastest that way: one vector per lane, no grid-stride loop),
+// non-temporal loads/stores since nothing is reused, and one scalar table lookup per
+// workgroup to find its tensor.  No MFMA: nothing here is a contraction.
+#include <hip/hip_runtime.h>
+
+#include "rs_internal.h"
+#include "rs_launch.h"
+
+namespace rs {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr float kE4M3Max = 448.0f;
+
+__device__ __forceinline__ u32x4 ld16(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ void st16(void* p, u32x4 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ u32x2 ld8(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+}
+__device__ __forceinline__ void st8(void* p, u32x2 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
+}
+
+// -------------------------------------------------------------------------------------------
+// ragged_pack / unpack_bf16: group copy between per-tensor storage and the DBuffer.
+// One workgroup per granule of kGranule buffer elements of one rank region.
+// -------------------------------------------------------------------------------------------
+template <bool kUnpack>
+__global__ __launch_bounds__(kThreads) void group_copy_kernel(
+    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
+    void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S, int64_t gpr) {
+  const int64_t bid = blockIdx.x;
+  const int64_t k = bid / gpr;
+  const int64_t i0 = (bid - k * gpr) * kGranule;
+  const int64_t d0 = k * S + i0;
+  const int len = int(min(int64_t(kGranule), S - i0));
+  const int lane_off = threadIdx.x * 8;
+  if (lane_off >= len) return;
+  const int64_t d = d0 + lane_off;
+  const int t0 = gran_first[bid];
+
+  bool empty = t0 >= n;
+  if (!empty) {
+    const int64_t ell = T[t0].ell, end = ell + T[t0].e;
+    if (ell <= d0 && d0 + len <= end) {
+      // the whole granule lies inside tensor t0 (the common case by far)
+      uint16_t* base = reinterpret_cast<uint16_t*>(ptrs[t0]) + (d0 - ell);
+      if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
+        if (kUnpack)
+          st16(base + lane_off, ld16(dbuf + d));
+        else
+          st16(dbuf + d, ld16(base + lane_off));
+        return;
+      }
+    }
+    empty = ell >= d0 + len;
+  }
+  if (empty) {  // nothing but padding here
+    if (!kUnpack) st16(dbuf + d, u32x4{0, 0, 0, 0});
+    return;
+  }
+
+  // Mixed granule (tensor boundaries, padding, or a source that is not 16-byte aligned):
+  // resolve every element on its own.
+  int s = t0;
+  uint16_t vals[8];
+  if (kUnpack) {
+    const u32x4 v = ld16(dbuf + d);
+    vals[0] = uint16_t(v.x); vals[1] = uint16_t(v.x >> 16);
+    vals[2] = uint16_t(v.y); vals[3] = uint16_t(v.y >> 16);
+    vals[4] = uint16_t(v.z); vals[5] = uint16_t(v.z >> 16);
+    vals[6] = uint16_t(v.w); vals[7] = uint16_t(v.w >> 16);
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int64_t pos = d + q;
+    while (s < n && T[s].ell + T[s].e <= pos) ++s;
+    const bool inside = s < n && T[s].ell <= pos;
+    if (kUnpack) {
+      if (inside) reinterpret_cast<uint16_t*>(ptrs[s])[pos - T[s].ell] = vals[q];
+    } else {
+      vals[q] = inside ? reinterpret_cast<const uint16_t*>(ptrs[s])[pos - T[s].ell] : uint16_t(0);
+    }
+  }
+  if (!kUnpack) {
+    u32x4 v;
+    v.x = vals[0] | (uint32_t(vals[1]) << 16);
+    v.y = vals[2] | (uint32_t(vals[3]) << 16);
+    v.z = vals[4] | (uint32_t(vals[5]) << 16);
+    v.w = vals[6] | (uint32_t(vals[7]) << 16);
+    st16(dbuf + d, v);
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// shard_reduce: out[i] = (1/W) * sum_w P[w][i] on the payload of one rank region, 0 on padding.
+// Each lane owns 8 consecutive elements and walks the W rows; rows are spread over 8
+// accumulator sets (row w -> set w mod 8) that are combined pairwise at the end, so the
+// summation order is fixed and the rounding error grows with W/8 + 3, not W.
+// -------------------------------------------------------------------------------------------
+__device__ __forceinline__ void add_bf16x8(float (&acc)[8], const u32x4 v) {
+  acc[0] += __uint_as_float(v.x << 16);
+  acc[1] += __uint_as_float(v.x & 0xffff0000u);
+  acc[2] += __uint_as_float(v.y << 16);
+  acc[3] += __uint_as_float(v.y & 0xffff0000u);
+  acc[4] += __uint_as_float(v.z << 16);
+  acc[5] += __uint_as_float(v.z & 0xffff0000u);
+  acc[6] += __uint_as_float(v.w << 16);
+  acc[7] += __uint_as_float(v.w & 0xffff0000u);
+}
+
+__global__ __launch_bounds__(kThreads) void shard_reduce_kernel(
+    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
+    const uint16_t* __restrict__ P, int64_t row_stride, float* __restrict__ out, int64_t S,
+    int64_t gpr, int rank, int W, float inv_w) {
+  const int64_t j = blockIdx.x;
+  const int64_t i0 = j * kGranule;
+  const int64_t d0 = int64_t(rank) * S + i0;
+  const int len = int(min(int64_t(kGranule), S - i0));
+  const int lane_off = threadIdx.x * 8;
+  if (lane_off >= len) return;
+  const int64_t d = d0 + lane_off;
+  float* o = out + i0 + lane_off;
+  const int t0 = gran_first[int64_t(rank) * gpr + j];
+
+  // payload mask of this lane's 8 elements
+  unsigned mask = 0xffu;
+  bool empty = t0 >= n;
+  if (!empty) {
+    const int64_t ell = T[t0].ell, end = ell + T[t0].e;
+    empty = ell >= d0 + len;
+    if (!empty && !(ell <= d0 && d0 + len <= end)) {
+      mask = 0;
+      int s = t0;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int64_t pos = d + q;
+        while (s < n && T[s].ell + T[s].e <= pos) ++s;
+        if (s < n && T[s].ell <= pos) mask |= 1u << q;
+      }
+    }
+  }
+  if (empty || mask == 0) {  // padding only: no reads at all
+    st16(o, u32x4{0, 0, 0, 0});
+    st16(o + 4, u32x4{0, 0, 0, 0});
+    return;
+  }
+
+  float acc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[a][q] = 0.0f;
+
+  const uint16_t* p = P + i0 + lane_off;
+  int w = 0;
+  for (; w + 8 <= W; w += 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) v[a] = ld16(p + int64_t(w + a) * row_stride);
+#pragma unroll
+    for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
+  }
+  for (int a = 0; w < W; ++w, ++a) {  // W mod 8 leftover rows keep the row -> set rule
+    const u32x4 v = ld16(p + int64_t(w) * row_stride);
+    switch (a) {
+      case 0: add_bf16x8(acc[0], v); break;
+      case 1: add_bf16x8(acc[1], v); break;
+      case 2: add_bf16x8(acc[2], v); break;
+      case 3: add_bf16x8(acc[3], v); break;
+      case 4: add_bf16x8(acc[4], v); break;
+      case 5: add_bf16x8(acc[5], v); break;
+      default: add_bf16x8(acc[6], v); break;
+    }
+  }
+  float r[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const float s01 = acc[0][q] + acc[1][q], s23 = acc[2][q] + acc[3][q];
+    const float s45 = acc[4][q] + acc[5][q], s67 = acc[6][q] + acc[7][q];
+    const float m = ((s01 + s23) + (s45 + s67)) * inv_w;
+    r[q] = (mask >> q) & 1u ? m : 0.0f;
+  }
+  st16(o, u32x4{__float_as_uint(r[0]), __float_as_uint(r[1]), __float_as_uint(r[2]),
+                __float_as_uint(r[3])});
+  st16(o + 4, u32x4{__float_as_uint(r[4]), __float_as_uint(r[5]), __float_as_uint(r[6]),
+                    __float_as_uint(r[7])});
+}
+
+// -------------------------------------------------------------------------------------------
+// Work-item geometry shared by block_quant and dequant_unpack.
+// A workgroup owns 128 "row slots" of up to 128 elements: the 128 rows of one 128x128 tile, or
+// 128 consecutive 1x128 blocks.  Lane (r_in, cg) = (tid / 16, tid % 16) handles elements
+// [8*cg, 8*cg + 8) of slots r_in + 16*i, i = 0..7, so one access instruction covers 16 slots
+// of 256 contiguous bytes each.
+// -------------------------------------------------------------------------------------------
+struct Slot {
+  int64_t off;   // element offset inside the tensor of this lane's 8 elements
+  int64_t blk;   // scale index relative to the tensor (1x128 runs only)
+  int ncol;      // how many of the 8 elements exist (0 = nothing to do)
+};
+
+__device__ __forceinline__ Slot tile_slot(const TensorDev& t, int64_t br, int bc, int slot, int col0) {
+  Slot s;
+  const int64_t row = br * 128 + slot;
+  const int64_t col = int64_t(bc) * 128 + col0;
+  s.off = row * t.cols + col;
+  s.blk = 0;
+  const int64_t left = t.cols - col;
+  s.ncol = (row < t.rows && left > 0) ? int(min(int64_t(8), left)) : 0;
+  return s;
+}
+
+__device__ __forceinline__ Slot run_slot(const TensorDev& t, int64_t b0, int count, int slot, int col0) {
+  Slot s;
+  s.blk = b0 + slot;
+  s.off = 0;
+  s.ncol = 0;
+  if (slot >= count) return s;
+  int64_t left;
+  if (t.flags & kFlagContig) {
+    s.off = s.blk * 128 + col0;
+    left = t.e - s.off;
+  } else {
+    const int64_t r = s.blk / t.nbc;
+    const int64_t col = (s.blk - r * t.nbc) * 128 + col0;
+    s.off = r * t.cols + col;
+    left = t.cols - col;
+  }
+  s.ncol = left > 0 ? int(min(int64_t(8), left)) : 0;
+  return s;
+}
+
+__device__ __forceinline__ unsigned abs_max_bits(unsigned m, unsigned packed) {
+  // bf16 magnitudes order like their 15-bit patterns
+  m = max(m, packed & 0x7fffu);
+  return max(m, (packed >> 16) & 0x7fffu);
+}
+
+__device__ __forceinline__ unsigned quant_pair(unsigned packed, float scale) {
+  // two bf16 -> two E4M3 codes in the low 16 bits
+  const float a = __uint_as_float(packed << 16) / scale;
+  const float b = __uint_as_float(packed & 0xffff0000u) / scale;
+  const float ca = __builtin_amdgcn_fmed3f(a, -kE4M3Max, kE4M3Max);
+  const float cb = __builtin_amdgcn_fmed3f(b, -kE4M3Max, kE4M3Max);
+  return unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xffffu;
+}
+
+__device__ __forceinline__ void zero_fill_bytes(uint8_t* dst, int count) {
+  // dst need not be aligned: bytes up to the first 16-byte line, vectors, bytes after
+  const int head = min(count, int((16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15));
+  const int nvec = (count - head) >> 4;
+  const int tail = (count - head) & 15;
+  const int tid = threadIdx.x;
+  if (tid < head) dst[tid] = 0;
+  for (int v = tid; v < nvec; v += kThreads) st16(dst + head + (v << 4), u32x4{0, 0, 0, 0});
+  if (tid < tail) dst[head + (nvec << 4) + tid] = 0;
+}
+
+// -------------------------------------------------------------------------------------------
+// block_quant: amax per block (wavefront shuffles, LDS across the 4 waves of a tile),
+// scale = amax / 448, codes = E4M3(clamp(x / scale)) with the hardware RNE convert.
+// x / codes are addressed relative to elem_base (0 or rank * S), scales to scale_off.
+// -------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void block_quant_kernel(
+    const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
+    const uint16_t* __restrict__ x, uint8_t* __restrict__ codes, float* __restrict__ scales,
+    int64_t elem_base, int64_t scale_off) {
+  __shared__ unsigned wave_max[kThreads / 64];
+  const Item it = items[item_off + blockIdx.x];
+  if (it.tensor < 0) {
+    zero_fill_bytes(codes + (it.first - elem_base), it.count);
+    return;
+  }
+  const TensorDev t = T[it.tensor];
+  const bool tile = (t.flags & kFlagTile) != 0;
+  const bool vec = (t.flags & kFlagVec) != 0;
+  const int tid = threadIdx.x;
+  const int r_in = tid >> 4, col0 = (tid & 15) * 8;
+  const int64_t base = t.ell - elem_base;
+
+  Slot sl[8];
+  u32x4 v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    sl[i] = tile ? tile_slot(t, it.first, it.count, r_in + 16 * i, col0)
+                 : run_slot(t, it.first, it.count, r_in + 16 * i, col0);
+    v[i] = u32x4{0, 0, 0, 0};
+    if (sl[i].ncol == 0) continue;
+    const uint16_t* src = x + base + sl[i].off;
+    if (vec) {
+      v[i] = ld16(src);
+      if (sl[i].ncol < 8) {  // drop what belongs to the next row / lies past the tensor
+        unsigned w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if (q >= sl[i].ncol) w[q >> 1] &= (q & 1) ? 0x0000ffffu : 0xffff0000u;
+        v[i] = u32x4{w[0], w[1], w[2], w[3]};
+      }
+    } else {
+      unsigned w[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q < sl[i].ncol) w[q >> 1] |= unsigned(src[q]) << ((q & 1) * 16);
+      v[i] = u32x4{w[0], w[1], w[2], w[3]};
+    }
+  }
+
+  // per-slot amax over this lane's 8 elements, then over the 16 lanes of the slot
+  unsigned m[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    unsigned a = 0;
+    a = abs_max_bits(a, v[i].x);
+    a = abs_max_bits(a, v[i].y);
+    a = abs_max_bits(a, v[i].z);
+    a = abs_max_bits(a, v[i].w);
+    m[i] = a;
+  }
+  if (tile) {
+    unsigned a = m[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) a = max(a, m[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    __syncthreads();
+    a = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m[i] = a;
+    if (tid == 0) {
+      const int64_t sidx = t.scale_base + it.first * t.nbc + it.count - scale_off;
+      scales[sidx] = __uint_as_float(a << 16) / kE4M3Max;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      unsigned a = m[i];
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+      m[i] = a;
+      if ((tid & 15) == 0 && r_in + 16 * i < it.count)
+        scales[t.scale_base + sl[i].blk - scale_off] = __uint_as_float(a << 16) / kE4M3Max;
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (sl[i].ncol == 0) continue;
+    u32x2 c{0, 0};
+    if (m[i] != 0) {
+      const float scale = __uint_as_float(m[i] << 16) / kE4M3Max;
+      c.x = quant_pair(v[i].x, scale) | (quant_pair(v[i].y, scale) << 16);
+      c.y = quant_pair(v[i].z, scale) | (quant_pair(v[i].w, scale) << 16);
+    }
+    uint8_t* dst = codes + base + sl[i].off;
+    if (vec && sl[i].ncol == 8) {
+      st8(dst, c);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q < sl[i].ncol) dst[q] = uint8_t((q < 4 ? c.x : c.y) >> ((q & 3) * 8));
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// dequant_unpack: codes of the gathered unit -> per-tensor bf16, value(code) * scale then RNE.
+// -------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned bf16_rne(float f) {
+  const unsigned u = __float_as_uint(f);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ void dequant4(unsigned word, float scale, unsigned& lo, unsigned& hi) {
+  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), false);  // bytes 0, 1
+  const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), true);   // bytes 2, 3
+  lo = bf16_rne(a[0] * scale) | (bf16_rne(a[1] * scale) << 16);
+  hi = bf16_rne(b[0] * scale) | (bf16_rne(b[1] * scale) << 16);
+}
+
+__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
+    const TensorDev* __restrict__ T, const Item* __restrict__ items,
+    const uint8_t* __restrict__ codes, const float* __restrict__ scales,
+    void* const* __restrict__ ptrs) {
+  const Item it = items[blockIdx.x];
+  if (it.tensor < 0) return;
+  const TensorDev t = T[it.tensor];
+  const bool tile = (t.flags & kFlagTile) != 0;
+  const bool vec_in = (t.flags & kFlagVec) != 0;
+  uint16_t* out = reinterpret_cast<uint16_t*>(ptrs[it.tensor]);
+  const bool vec_out = vec_in && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+  const int tid = threadIdx.x;
+  const int r_in = tid >> 4, col0 = (tid & 15) * 8;
+  const float tile_scale = tile ? scales[t.scale_base + it.first * t.nbc + it.count] : 0.0f;
+
+  Slot sl[8];
+  u32x2 c[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    sl[i] = tile ? tile_slot(t, it.first, it.count, r_in + 16 * i, col0)
+                 : run_slot(t, it.first, it.count, r_in + 16 * i, col0);
+    c[i] = u32x2{0, 0};
+    if (sl[i].ncol == 0) continue;
+    const uint8_t* src = codes + t.ell + sl[i].off;
+    if (vec_in) {
+      c[i] = ld8(src);  // bytes past ncol are read but never written out
+    } else {
+      unsigned w[2] = {0, 0};
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q < sl[i].ncol) w[q >> 2] |= unsigned(src[q]) << ((q & 3) * 8);
+      c[i] = u32x2{w[0], w[1]};
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (sl[i].ncol == 0) continue;
+    const float scale = tile ? tile_scale : scales[t.scale_base + sl[i].blk];
+    unsigned o0, o1, o2, o3;
+    dequant4(c[i].x, scale, o0, o1);
+    dequant4(c[i].y, scale, o2, o3);
+    const u32x4 o{o0, o1, o2, o3};
+    uint16_t* dst = out + sl[i].off;
+    if (vec_out && sl[i].ncol == 8) {
+      st16(dst, o);
+    } else {
+      const unsigned w[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q < sl[i].ncol) dst[q] = uint16_t(w[q >> 1] >> ((q & 1) * 16));
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// plain copy: the measured ceiling and the counter calibration launch
+// -------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void copy_probe_kernel(const u32x4* __restrict__ src,
+                                                             u32x4* __restrict__ dst, int64_t nvec) {
+  const int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+  if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// -------------------------------------------------------------------------------------------
+// launchers (host)
+// -------------------------------------------------------------------------------------------
+static int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }
+
+int launch_group_copy(bool unpack, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf,
+                      int64_t S, int64_t gpr, int64_t world, hipStream_t st) {
+  const int64_t grid = world * gpr;
+  if (grid <= 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  if (unpack)
+    group_copy_kernel<true><<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
+        dev.tensors, n, dev.gran_first, ptrs, static_cast<uint16_t*>(dbuf), S, gpr);
+  else
+    group_copy_kernel<false><<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
+        dev.tensors, n, dev.gran_first, ptrs, static_cast<uint16_t*>(dbuf), S, gpr);
+  return launched();
+}
+
+int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
+                        float* out, int64_t S, int64_t gpr, int rank, int world, hipStream_t st) {
+  if (gpr <= 0 || gpr > 0x7fffffffLL) return RS_EOVERFLOW;
+  shard_reduce_kernel<<<dim3(unsigned(gpr)), dim3(kThreads), 0, st>>>(
+      dev.tensors, n, dev.gran_first, static_cast<const uint16_t*>(partials), row_stride, out, S,
+      gpr, rank, world, 1.0f / float(world));
+  return launched();
+}
+
+int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
+                       uint8_t* codes, float* scales, int64_t elem_base, int64_t scale_off,
+                       hipStream_t st) {
+  if (item_count == 0) return RS_OK;
+  if (item_count < 0 || item_count > 0x7fffffffLL) return RS_EOVERFLOW;
+  block_quant_kernel<<<dim3(unsigned(item_count)), dim3(kThreads), 0, st>>>(
+      dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, elem_base,
+      scale_off);
+  return launched();
+}
+
+int launch_dequant_unpack(const DeviceTables& dev, int64_t item_count, const uint8_t* codes,
+                          const float* scales, void* const* ptrs, hipStream_t st) {
+  if (item_count == 0) return RS_OK;
+  if (item_count < 0 || item_count > 0x7fffffffLL) return RS_EOVERFLOW;
+  dequant_unpack_kernel<<<dim3(unsigned(item_count)), dim3(kThreads), 0, st>>>(
+      dev.tensors, dev.items, codes, scales, ptrs);
+  return launched();
+}
+
+int launch_copy_probe(void* dst, const void* src, int64_t bytes, hipStream_t st) {
+  const int64_t nvec = bytes / 16;
+  const int64_t grid = (nvec + kThreads - 1) / kThreads;
+  if (grid == 0) return RS_OK;
+  if (grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  copy_probe_kernel<<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
+      static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
+  return launched();
+}
+
+}  // namespace rs

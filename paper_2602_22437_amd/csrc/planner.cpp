@@ -1,0 +1,171 @@
+// Host planner: Algorithm 1 (structure-aware planning for grouped RaggedShard tensors,
+// paper Section 5) for a fixed tensor order.
+//
+// CheckValidShard(S) is evaluated as an earliest-start sweep: whether a start l is
+// admissible for tensor t depends on (l, e_t, g_t, S) alone, and padding between tensors
+// costs nothing, so taking the smallest admissible start after the previous tensor's end
+// minimises every tensor's end and with it dp(t, i; S), the number of device shards used.
+// The smallest admissible start comes from the section's three-case analysis (inside one
+// shard / across one boundary / containing whole shards) in O(1).
+#include <algorithm>
+#include <cstdint>
+#include <vector>
+
+#include "rs_internal.h"
+
+namespace rs {
+namespace {
+
+using i128 = __int128;
+constexpr int64_t kLimit = int64_t(1) << 62;
+
+inline int64_t gcd64(int64_t a, int64_t b) {
+  while (b != 0) {
+    const int64_t r = a % b;
+    a = b;
+    b = r;
+  }
+  return a;
+}
+
+inline int64_t round_up(int64_t v, int64_t unit) { return (v + unit - 1) / unit * unit; }
+
+}  // namespace
+
+// Smallest l >= p with l = 0 (mod A) such that every rank boundary k*S strictly inside
+// [l, l + e) is a multiple of g away from l (the "non-sharded block" constraint).
+// Requires A | S.  Returns -1 when no start exists.
+int64_t smallest_feasible_start(int64_t p, int64_t e, int64_t g, int64_t S, int64_t A) {
+  const int64_t first = round_up(p, A);
+  const int64_t next = (first / S + 1) * S;  // boundary closing the shard `first` lies in
+  if (first + e <= next) return first;        // case 1: no boundary inside the tensor
+
+  if (S % g == 0) {
+    // Boundaries are all congruent mod g, so any number of them may fall inside the tensor
+    // (case 3) as long as l itself is a multiple of g; l must also keep the A alignment.
+    const i128 unit = i128(g / gcd64(g, A)) * A;
+    const i128 v = (i128(first) + unit - 1) / unit * unit;
+    return v >= kLimit ? -1 : int64_t(v);
+  }
+
+  // g does not divide S: two boundaries inside one tensor would force g | S, so exactly one
+  // boundary B may be crossed (case 2), with j >= 1 whole blocks in front of it: l = B - j*g.
+  // A | B, hence l stays aligned iff j is a multiple of A / gcd(A, g); the part behind B
+  // must end by B + S, which bounds j from below.
+  const int64_t j_step = A / gcd64(A, g);
+  const int64_t j_need = e > S ? std::max<int64_t>(1, (e - S + g - 1) / g) : 1;
+  auto across = [&](int64_t boundary, int64_t not_before) -> int64_t {
+    int64_t j = (boundary - not_before) / g;
+    j -= j % j_step;
+    return j >= j_need ? boundary - j * g : -1;
+  };
+  const int64_t a = across(next, first);
+  if (a >= 0) return a;
+  if (e <= S) return next;  // case 1 again: flush against the next boundary
+  return across(next + S, next);  // later boundaries repeat this one with period S
+}
+
+bool check_valid_shard(const std::vector<TensorHost>& t, int64_t world, int64_t S, int64_t A,
+                       std::vector<int64_t>* starts) {
+  const i128 room = i128(world) * S;
+  int64_t cursor = 0;
+  if (starts) starts->assign(t.size(), 0);
+  for (size_t i = 0; i < t.size(); ++i) {
+    const int64_t l = smallest_feasible_start(cursor, t[i].e, t[i].g, S, A);
+    if (l < 0 || i128(l) + t[i].e > room) return false;
+    if (starts) (*starts)[i] = l;
+    cursor = l + t[i].e;
+  }
+  return true;
+}
+
+int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>* out) {
+  out->clear();
+  out->reserve(n);
+  i128 sum = 0;
+  for (int i = 0; i < n; ++i) {
+    const rs_tensor_desc& d = descs[i];
+    if (d.rows <= 0 || d.cols < 0 || d.reserved != 0) return RS_EINVAL;
+    if (d.cols > 0 && d.rows > kLimit / d.cols) return RS_EOVERFLOW;
+    if (d.rows >= kLimit || d.cols >= (int64_t(1) << 40)) return RS_EOVERFLOW;
+    TensorHost h{};
+    h.rows = d.rows;
+    h.cols = d.cols;
+    h.mode = d.block_mode;
+    h.e = d.cols > 0 ? d.rows * d.cols : d.rows;
+    switch (d.block_mode) {
+      case RS_BLOCK_1x128:
+        h.g = d.cols > 0 ? d.cols : 128;
+        h.quant = true;
+        h.nbc = d.cols > 0 ? (d.cols + 127) / 128 : (d.rows + 127) / 128;
+        h.nbr = d.cols > 0 ? d.rows : 1;
+        break;
+      case RS_BLOCK_128x128:
+        if (d.cols == 0) return RS_EINVAL;
+        h.g = 128 * d.cols;
+        h.quant = true;
+        h.nbc = (d.cols + 127) / 128;
+        h.nbr = (d.rows + 127) / 128;
+        break;
+      case RS_BLOCK_WHOLE:
+        h.g = h.e;
+        break;
+      case RS_BLOCK_EXPLICIT:
+        if (d.g_explicit <= 0) return RS_EINVAL;
+        h.g = d.g_explicit;
+        break;
+      default:
+        return RS_EINVAL;
+    }
+    h.u = (h.e + h.g - 1) / h.g;
+    sum += h.e;
+    if (sum >= kLimit) return RS_EOVERFLOW;
+    out->push_back(h);
+  }
+  return RS_OK;
+}
+
+// Outer loop of Algorithm 1: unit g <- g_coll, then g <- lcm(g, g') over the ascending distinct
+// block sizes; per unit the smallest feasible multiple by lower-bound bisection; S* = minimum.
+int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
+                     int64_t* S_out) {
+  i128 total = 0;
+  for (const TensorHost& h : t) total += round_up(h.e, A);
+  if (total >= kLimit) return RS_EOVERFLOW;
+  // Everything start-aligned in a single shard is always feasible; a unit beyond that size
+  // can only tie or lose.
+  const int64_t one_shard = round_up(int64_t(total), g_coll);
+
+  std::vector<int64_t> sizes;
+  for (const TensorHost& h : t) sizes.push_back(h.g);
+  std::sort(sizes.begin(), sizes.end());
+  sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
+
+  std::vector<int64_t> units{g_coll};
+  i128 unit = g_coll;
+  for (int64_t g : sizes) {
+    unit = unit / gcd64(int64_t(unit), g) * g;
+    if (unit > one_shard) break;
+    if (int64_t(unit) != units.back()) units.push_back(int64_t(unit));
+  }
+
+  int64_t best = -1;
+  for (int64_t c : units) {
+    int64_t lo = 1, hi = std::max<int64_t>(1, (int64_t(total) + c - 1) / c);
+    while (lo < hi) {
+      const int64_t mid = lo + (hi - lo) / 2;
+      if (i128(mid) * c < kLimit && check_valid_shard(t, world, mid * c, A, nullptr))
+        hi = mid;
+      else
+        lo = mid + 1;
+    }
+    if (i128(lo) * c >= kLimit) continue;
+    const int64_t cand = lo * c;
+    if (best < 0 || cand < best) best = cand;
+  }
+  if (best < 0 || i128(best) * world >= kLimit) return RS_EOVERFLOW;
+  *S_out = best;
+  return RS_OK;
+}
+
+}  // namespace rs

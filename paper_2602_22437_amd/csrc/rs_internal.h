@@ -1,0 +1,97 @@
+// Internal structures shared by the host planner, the table builder and the HIP kernels.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "raggedshard.h"
+
+namespace rs {
+
+// Tile-table granule: the DBuffer region of every rank is cut into granules of this many
+// elements; the table gives, per granule, the first tensor that ends after the granule's start.
+constexpr int kGranule = 2048;
+// A quantisation work item covers at most this many "row slots" of 128 elements:
+// one 128x128 tile, or 128 consecutive 1x128 blocks.
+constexpr int kItemSlots = 128;
+// A zero-fill item clears at most this many code bytes.
+constexpr int kFillElems = 32768;
+
+enum : int32_t {
+  kFlagTile = 1,     // 128x128 tiles (else 1x128 runs)
+  kFlagQuant = 2,    // tensor has FP8 blocks
+  kFlagVec = 4,      // every row slot starts 8-element aligned in the buffer (16-byte bf16 vectors)
+  kFlagContig = 8    // 1x128 blocks are back to back in memory (1-D, or C % 128 == 0)
+};
+
+// Per-tensor record on the device (48 bytes).
+struct TensorDev {
+  int64_t ell;         // l_t: first element in the buffer
+  int64_t e;           // elements
+  int64_t scale_base;  // first scale index
+  int64_t rows;        // R (1 for 1-D tensors)
+  int64_t cols;        // C (n for 1-D tensors)
+  int32_t nbc;         // quantisation blocks per row of blocks
+  int32_t flags;
+};
+
+// One workgroup's worth of block_quant / dequant_unpack work (16 bytes).
+struct Item {
+  int64_t first;   // tile: block row br;  runs: first block index;  fill: buffer element offset
+  int32_t tensor;  // -1 marks a zero-fill item
+  int32_t count;   // tile: block column bc;  runs: blocks in this item (<= kItemSlots);  fill: elements
+};
+
+struct TensorHost {
+  int64_t rows, cols;  // as described by the caller (cols == 0: 1-D)
+  int32_t mode;
+  int64_t e, g, u;     // elements, granularity, ceil(e/g)
+  int64_t ell;         // planned start
+  int64_t nbr, nbc;    // FP8 block grid (0 x 0 when not quantised)
+  int64_t scale_base;
+  bool quant;
+};
+
+struct HostTables {
+  std::vector<TensorDev> tensors;
+  std::vector<int32_t> gran_first;   // world * granules_per_rank
+  int64_t granules_per_rank = 0;
+  std::vector<Item> items;           // rank-major
+  std::vector<int64_t> item_begin;   // world + 1
+};
+
+struct DeviceTables {
+  int device = -1;
+  TensorDev* tensors = nullptr;
+  int32_t* gran_first = nullptr;
+  Item* items = nullptr;
+};
+
+// ---- planner (planner.cpp) ----
+int64_t smallest_feasible_start(int64_t p, int64_t e, int64_t g, int64_t S, int64_t A);
+bool check_valid_shard(const std::vector<TensorHost>& t, int64_t world, int64_t S, int64_t A,
+                       std::vector<int64_t>* starts);
+int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>* out);
+int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
+                     int64_t* S_out);
+
+// ---- derived tables (tables.cpp) ----
+void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t S, bool all_quant,
+                       HostTables* out);
+
+}  // namespace rs
+
+struct rs_plan {
+  std::vector<rs::TensorHost> t;
+  int64_t world = 0, g_coll = 0, A = 0, S = 0, payload = 0, num_scales = 0;
+  bool all_quant = false;
+  std::vector<int64_t> scale_begin;  // world + 1: first scale of every rank
+  rs::HostTables host;
+  rs::DeviceTables dev;
+};
+
+struct rs_tensor_table {
+  const rs_plan* owner = nullptr;  // tables are valid for the plan they were made for only
+  int device = -1;
+  int n = 0;
+  void** ptrs = nullptr;  // device array of n pointers
+};

@@ -1,0 +1,347 @@
+"""GPU parity: every kernel of the HIP library against the CPU oracle, element by element, on
+the same seeded inputs, through the C ABI.  Bit-exact for pack / unpack / FP8 codes / scales;
+|err| <= 1e-5 * sum_w |x_w| per element for shard_reduce."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dbuffer as OD
+from oracle import fp8 as OF
+from paper_2602_22437_amd import binding as B
+from workloads import (MODE_128x128, MODE_1x128, MODE_WHOLE, WORKLOADS, gen_params, gen_partial,
+                       normal_bf16, uniform_bits)
+
+from gpu_util import Unit, bits_of, say, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+REDUCE_TOL = 1e-5
+
+
+def run_pack(u: Unit, params):
+    dev = [to_dev_bf16(p) for p in params]
+    dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)  # garbage
+    B.rs_pack(u.plan, u.table(dev), dbuf)
+    torch.cuda.synchronize()
+    return dbuf
+
+
+def check_pack_unpack(u: Unit, params, label):
+    say(f"pack {label}: S={u.S} total={u.total}")
+    dbuf = run_pack(u, params)
+    want = OD.ragged_pack(params, u.oracle.offsets, u.total)
+    assert np.array_equal(bits_of(dbuf), want), f"ragged_pack differs ({label})"
+    say(f"unpack_bf16 {label}")
+    outs = [torch.full((p.size,), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.bfloat16) for p in params]
+    B.rs_unpack_bf16(u.plan, dbuf, u.table(outs))
+    torch.cuda.synchronize()
+    for i, (o, p) in enumerate(zip(outs, params)):
+        assert np.array_equal(bits_of(o), p), f"unpack_bf16 tensor {i} differs ({label})"
+    return dbuf, want
+
+
+def check_reduce(u: Unit, rank, partial_bits, label, poison_padding=True):
+    """partial_bits: (W, S) uint16.  Padding columns may hold anything: the result is 0 there."""
+    W, S = partial_bits.shape
+    segs = u.oracle.rank_segments(rank)
+    if poison_padding:
+        pay = np.zeros(S, dtype=bool)
+        for _, _, d, n in segs:
+            pay[d:d + n] = True
+        partial_bits = partial_bits.copy()
+        partial_bits[:, ~pay] = 0x4300          # 128.0 where the kernel must not look
+    say(f"reduce {label}: rank={rank} W={W} S={S}")
+    dev = to_dev_bf16(partial_bits.reshape(-1))
+    out = torch.full((S,), float("nan"), dtype=torch.float32, device="cuda")
+    B.rs_reduce(u.plan, rank, dev, S, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = OD.shard_reduce(partial_bits, segs)
+    bound = REDUCE_TOL * OD.shard_reduce_abs_sum(partial_bits)
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    pay = np.zeros(S, dtype=bool)
+    for _, _, d, n in segs:
+        pay[d:d + n] = True
+    assert np.all(got[~pay] == 0), f"reduce padding not zero ({label})"
+    assert not np.any(np.isnan(got))
+    assert np.all(err[pay] <= bound[pay]), f"reduce error above bound ({label}): {err.max()}"
+    return got
+
+
+def check_quant(u: Unit, db_bits, label, ranks):
+    """rank-by-rank and all-ranks quantisation against the oracle; returns device codes/scales."""
+    want_codes, want_scales = OF.block_quant_all(u.oracle, db_bits)
+    nb = want_scales.size
+    dbuf = to_dev_bf16(db_bits)
+    say(f"quantize all ranks {label}: nb={nb}")
+    codes = torch.full((u.total,), 0xAB, dtype=torch.uint8, device="cuda")
+    scales = torch.full((max(nb, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    B.rs_quantize(u.plan, -1, dbuf, codes, scales)
+    torch.cuda.synchronize()
+    got_s = scales.cpu().numpy()[:nb]
+    assert np.array_equal(got_s.view(np.uint32), want_scales.view(np.uint32)), f"scales differ ({label})"
+    got_c = codes.cpu().numpy()
+    if not np.array_equal(got_c, want_codes):
+        bad = np.flatnonzero(got_c != want_codes)
+        raise AssertionError(f"codes differ ({label}) at {bad[:8]}: got {got_c[bad[:8]]} want {want_codes[bad[:8]]}")
+    for k in ranks:
+        say(f"quantize rank {k} {label}")
+        lo, hi = u.oracle.scale_range(k)
+        assert B.rs_plan_scale_range(u.plan, k) == (lo, hi)
+        c = torch.full((u.S,), 0xCD, dtype=torch.uint8, device="cuda")
+        s = torch.full((max(hi - lo, 1),), float("nan"), dtype=torch.float32, device="cuda")
+        B.rs_quantize(u.plan, k, dbuf[k * u.S:(k + 1) * u.S], c, s)
+        torch.cuda.synchronize()
+        oc, os_ = OF.block_quant_shard(u.oracle, k, db_bits[k * u.S:(k + 1) * u.S])
+        assert np.array_equal(c.cpu().numpy(), oc), f"rank {k} codes differ ({label})"
+        assert np.array_equal(s.cpu().numpy()[:hi - lo].view(np.uint32), os_.view(np.uint32))
+    return codes, scales, want_codes, want_scales
+
+
+def check_dequant_unpack(u: Unit, codes, scales, want_codes, want_scales, label):
+    say(f"dequant_unpack {label}")
+    outs = [torch.full((s.e,), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.bfloat16) for s in u.specs]
+    B.rs_unpack(u.plan, codes, scales, u.table(outs))
+    torch.cuda.synchronize()
+    want = OF.dequant_unpack(u.oracle, want_codes, want_scales)
+    for i, (o, w) in enumerate(zip(outs, want)):
+        assert np.array_equal(bits_of(o), w), f"dequant_unpack tensor {i} differs ({label})"
+
+
+# ---------------------------------------------------------------------------------------------
+# config 1: toy unit, everything, every rank
+# ---------------------------------------------------------------------------------------------
+
+def test_config1_all_ops():
+    wl = WORKLOADS[1]
+    u = Unit.from_workload(wl)
+    try:
+        params = gen_params(wl, seed=1)
+        _, db_bits = check_pack_unpack(u, params, "cfg1")
+        for k in range(wl.world):
+            parts = np.stack([gen_partial(wl, 1, w, u.S, unit=k) for w in range(wl.world)])
+            check_reduce(u, k, parts, "cfg1")
+        c, s, wc, ws = check_quant(u, db_bits, "cfg1", range(wl.world))
+        check_dequant_unpack(u, c, s, wc, ws, "cfg1")
+    finally:
+        u.close()
+
+
+def test_e4m3_encode_every_bf16_value():
+    """All finite bf16 values with |x| <= 448 as quantisation inputs at scale exactly 1
+    (every block also holds 448, so amax/448 = 1): the hardware convert must agree with the
+    format definition on every one, ties and subnormals included."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    x = OD.bf16_bits_to_f32(bits)
+    bits = bits[np.isfinite(x) & (np.abs(x) <= 448.0)]
+    per = 127
+    nblk = -(-bits.size // per)
+    data = np.full(nblk * 128, 0x43E0, dtype=np.uint16)         # 448.0
+    body = np.zeros(nblk * per, dtype=np.uint16)
+    body[:bits.size] = bits
+    data.reshape(nblk, 128)[:, :per] = body.reshape(nblk, per)
+    for tensors, label in [([(data.size, 0, MODE_1x128)], "1-D runs"),
+                           ([(nblk, 128, MODE_1x128)], "row runs"),
+                           ([(data.size // 128, 128, MODE_128x128)], "tiles")]:
+        u = Unit(tensors, 1)
+        try:
+            db = OD.ragged_pack([data], u.oracle.offsets, u.total)
+            c, s, wc, ws = check_quant(u, db, f"exhaustive {label}", [0])
+            if label != "tiles":
+                assert np.all(ws == 1.0)
+            check_dequant_unpack(u, c, s, wc, ws, f"exhaustive {label}")
+        finally:
+            u.close()
+
+
+def test_e4m3_ties_and_neighbours_in_fp32():
+    """y = x / scale lands on (and one ulp around) every midpoint between adjacent E4M3 values:
+    choose scale = 2^k so y is exact, x = midpoint * 2^k."""
+    tab = OF.decode_table()[:0x7F].astype(np.float64)
+    mids = (tab[:-1] + tab[1:]) / 2
+    vals = []
+    for kexp in (-3, 0, 5):
+        for m in mids:
+            for v in (m, -m):
+                vals.append(v * 2.0 ** kexp)
+    # bf16 can hold every midpoint (5 significant bits); neighbours come from the exhaustive test
+    arr = np.array(vals, dtype=np.float32)
+    bits = (arr.view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal(OD.bf16_bits_to_f32(bits), arr)
+    per = len(mids) * 2
+    blocks = []
+    for i, kexp in enumerate((-3, 0, 5)):
+        chunk = bits[i * per:(i + 1) * per]
+        for a in range(0, per, 127):
+            blk = np.zeros(128, dtype=np.uint16)
+            part = chunk[a:a + 127]
+            blk[:part.size] = part
+            blk[127] = (np.array([448.0 * 2.0 ** kexp], dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)[0]
+            blocks.append(blk)
+    data = np.concatenate(blocks)
+    u = Unit([(data.size, 0, MODE_1x128)], 1)
+    try:
+        db = OD.ragged_pack([data], u.oracle.offsets, u.total)
+        check_quant(u, db, "ties", [0])
+    finally:
+        u.close()
+
+
+def test_zero_blocks_negative_zero_and_tiny_values():
+    rows, cols = 300, 384
+    rng_bits = normal_bf16(7, 0, 2, 0, rows * cols, 0.02).reshape(rows, cols)
+    rng_bits[128:256, 128:256] = 0                 # an all-zero tile: scale 0, codes 0
+    rng_bits[0:128, 0:128] = 0x8000                # all negative zeros: still scale 0, codes 0x00
+    rng_bits[0, 256] = 0x0001                      # smallest bf16 subnormal next to normal values
+    rng_bits[1, 256] = 0x8001
+    rng_bits[256:, 256:] = 0x0003                  # a tile of tiny subnormals only (amax tiny)
+    vec = normal_bf16(7, 0, 2, 1, 1000, 1e-30)     # 1-D runs with very small magnitudes
+    vec[128:256] = 0
+    u = Unit([(rows, cols, MODE_128x128), (1000, 0, MODE_1x128)], 2)
+    try:
+        db = OD.ragged_pack([rng_bits.reshape(-1), vec], u.oracle.offsets, u.total)
+        c, s, wc, ws = check_quant(u, db, "zeros/tiny", range(2))
+        check_dequant_unpack(u, c, s, wc, ws, "zeros/tiny")
+    finally:
+        u.close()
+
+
+RAGGED_UNITS = [
+    # (tensors, world, align_bytes, min_itemsize, tensor_align): odd pitches, partial tiles,
+    # rows that are not 16-byte multiples, paper-literal A = 1 (nothing vector-aligned)
+    ([(257, 130, MODE_128x128), (5, 0, MODE_1x128), (129, 7, MODE_128x128), (300, 0, MODE_1x128)], 3, 16, 1, 0),
+    ([(64, 200, MODE_1x128), (33, 136, MODE_1x128), (1, 0, MODE_1x128), (130, 129, MODE_128x128)], 5, 16, 1, 0),
+    ([(257, 130, MODE_128x128), (383, 0, MODE_1x128), (129, 8, MODE_128x128)], 4, 16, 1, 1),
+    ([(17, 24, MODE_1x128), (250, 0, MODE_1x128), (128, 256, MODE_128x128)], 7, 32, 1, 2),
+    ([(2048, 0, MODE_1x128)], 16, 16, 1, 0),
+    ([(128, 128, MODE_128x128)], 8, 16, 1, 0),                      # most ranks empty
+]
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED_UNITS)))
+def test_ragged_units_all_ops(case):
+    tensors, world, align, item, A = RAGGED_UNITS[case]
+    u = Unit(tensors, world, align, item, A)
+    try:
+        params = [normal_bf16(11, case, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        _, db_bits = check_pack_unpack(u, params, f"ragged{case}")
+        for k in range(world):
+            parts = np.stack([normal_bf16(11, case, 1, k * 64 + w, u.S, 1e-3) for w in range(world)])
+            check_reduce(u, k, parts, f"ragged{case}")
+        c, s, wc, ws = check_quant(u, db_bits, f"ragged{case}", range(world))
+        check_dequant_unpack(u, c, s, wc, ws, f"ragged{case}")
+    finally:
+        u.close()
+
+
+def test_unaligned_tensor_storage():
+    """Sources / destinations that are only element-aligned (views at odd offsets)."""
+    tensors = [(130, 136, MODE_128x128), (700, 0, MODE_1x128), (64, 256, MODE_1x128)]
+    u = Unit(tensors, 3)
+    try:
+        params = [normal_bf16(12, 0, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        holders = [torch.zeros(p.size + 8, dtype=torch.bfloat16, device="cuda") for p in params]
+        views = []
+        for i, (h, p) in enumerate(zip(holders, params)):
+            v = h[1 + i:1 + i + p.size]
+            v.copy_(to_dev_bf16(p))
+            views.append(v)
+        dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        say("pack from unaligned sources")
+        B.rs_pack(u.plan, u.table(views), dbuf)
+        torch.cuda.synchronize()
+        want = OD.ragged_pack(params, u.oracle.offsets, u.total)
+        assert np.array_equal(bits_of(dbuf), want)
+        outs_h = [torch.zeros(p.size + 8, dtype=torch.bfloat16, device="cuda") for p in params]
+        outs = [h[3:3 + p.size] for h, p in zip(outs_h, params)]
+        say("unpack_bf16 to unaligned destinations")
+        B.rs_unpack_bf16(u.plan, dbuf, u.table(outs))
+        torch.cuda.synchronize()
+        for o, p, h in zip(outs, params, outs_h):
+            assert np.array_equal(bits_of(o), p)
+            assert bits_of(h)[:3].tolist() == [0, 0, 0] and bits_of(h)[3 + p.size:].tolist() == [0] * 5
+        wc, ws = OF.block_quant_all(u.oracle, want)
+        codes = torch.from_numpy(wc).cuda()
+        scales = torch.from_numpy(ws).cuda()
+        outs_h = [torch.zeros(p.size + 8, dtype=torch.bfloat16, device="cuda") for p in params]
+        outs = [h[5:5 + p.size] for h, p in zip(outs_h, params)]
+        say("dequant_unpack to unaligned destinations")
+        B.rs_unpack(u.plan, codes, scales, u.table(outs))
+        torch.cuda.synchronize()
+        for o, w, h in zip(outs, OF.dequant_unpack(u.oracle, wc, ws), outs_h):
+            assert np.array_equal(bits_of(o), w)
+            assert bits_of(h)[:5].tolist() == [0] * 5 and bits_of(h)[5 + w.size:].tolist() == [0] * 3
+    finally:
+        u.close()
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 9, 15, 16, 17, 100])
+def test_reduce_world_sizes_and_special_cases(W):
+    tensors = [(3000, 0, MODE_1x128), (70, 130, MODE_1x128)]
+    u = Unit(tensors, W)
+    try:
+        rank = W // 2
+        parts = np.stack([normal_bf16(13, W, 1, w, u.S, 1e-3) for w in range(W)])
+        got = check_reduce(u, rank, parts, f"W={W}")
+        if W == 1:      # exact widening of the only partial
+            pay = got != 0
+            assert np.array_equal(got[pay], OD.bf16_bits_to_f32(parts[0])[pay])
+        if W in (2, 8, 16):   # equal partials, W a power of two: the value itself
+            same = np.repeat(parts[:1], W, axis=0)
+            got = check_reduce(u, rank, same, f"W={W} equal", poison_padding=False)
+            segs = u.oracle.rank_segments(rank)
+            for _, _, d, n in segs:
+                assert np.array_equal(got[d:d + n], OD.bf16_bits_to_f32(parts[0, d:d + n]))
+    finally:
+        u.close()
+
+
+def test_reduce_row_stride_and_large_magnitudes():
+    W = 12
+    u = Unit([(5000, 0, MODE_1x128)], 3)
+    try:
+        S = u.S
+        stride = S + 64
+        big = np.stack([normal_bf16(14, 0, 1, w, S, 3.0e4) for w in range(W)])   # cancellation-prone
+        buf = torch.zeros(W * stride, dtype=torch.bfloat16, device="cuda")
+        buf.view(W, stride)[:, :S].copy_(to_dev_bf16(big.reshape(-1)).view(W, S))
+        out = torch.empty(S, dtype=torch.float32, device="cuda")
+        say("reduce with a row stride > S")
+        B.rs_reduce(u.plan, 1, buf, stride, out)
+        torch.cuda.synchronize()
+        # W here is the plan's world (3): only the first 3 rows are read
+        want = OD.shard_reduce(big[:3], u.oracle.rank_segments(1))
+        bound = REDUCE_TOL * OD.shard_reduce_abs_sum(big[:3])
+        assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - want) <= bound)
+    finally:
+        u.close()
+
+
+def test_device_argument_errors():
+    u = Unit([(256, 128, MODE_128x128)], 2)
+    w = Unit([(64, 64, MODE_WHOLE)], 2, 16, 2)
+    try:
+        x = torch.zeros(u.total + 8, dtype=torch.bfloat16, device="cuda")
+        tab = u.table([torch.zeros(256 * 128, dtype=torch.bfloat16, device="cuda")])
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_pack(u.plan, tab, x[1:])                       # misaligned DBuffer
+        assert e.value.code == B.RS_EALIGN
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_reduce(u.plan, 2, x, u.S, torch.zeros(u.S, device="cuda"))   # rank out of range
+        assert e.value.code == B.RS_EINVAL
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_reduce(u.plan, 0, x, u.S + 3, torch.zeros(u.S, device="cuda"))
+        assert e.value.code == B.RS_EALIGN
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_reduce(u.plan, 0, x, u.S - 8, torch.zeros(u.S, device="cuda"))
+        assert e.value.code == B.RS_EINVAL
+        codes = torch.zeros(w.total, dtype=torch.uint8, device="cuda")
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_quantize(w.plan, 0, x, codes, torch.zeros(4, device="cuda"))  # whole-matrix plan
+        assert e.value.code == B.RS_EUNSUPPORTED
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_pack(w.plan, tab, x)                           # table made for another plan
+        assert e.value.code == B.RS_EINVAL
+    finally:
+        u.close()
+        w.close()

@@ -1,0 +1,156 @@
+"""Host side of the HIP library (no GPU needed): the C++ planner must reproduce the oracle's
+S*, offsets and derived ranges exactly, reject bad input with error codes, and the shared
+library must export every symbol the header declares."""
+import ctypes as C
+import os
+import random
+import re
+
+import pytest
+
+from oracle import plan as P
+from paper_2602_22437_amd import binding as B
+from workloads import WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "raggedshard.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rs_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.rs_version() >= 100
+    assert B.rs_strerror(0) == "ok" and "align" in B.rs_strerror(B.RS_EALIGN)
+
+
+@pytest.mark.parametrize("idx", sorted(WORKLOADS))
+def test_configs_match_oracle(idx):
+    wl = WORKLOADS[idx]
+    specs = [P.TensorSpec(t.rows, t.cols, t.mode) for t in wl.tensors]
+    want = P.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize)
+    plan = B.rs_plan_create([(t.rows, t.cols, t.mode) for t in wl.tensors], wl.world, wl.align_bytes,
+                            wl.min_itemsize)
+    try:
+        assert B.rs_plan_shard_elems(plan) == want.S
+        assert B.rs_plan_total_elems(plan) == want.total
+        assert B.rs_plan_payload_elems(plan) == want.payload
+        assert B.rs_plan_padding_elems(plan) == want.padding
+        assert B.rs_plan_offsets(plan) == want.offsets
+        assert B.rs_plan_scale_bases(plan) == want.scale_bases()
+        assert B.rs_plan_num_scales(plan) == want.scale_bases()[-1]
+        assert B.rs_plan_world(plan) == wl.world and B.rs_plan_num_tensors(plan) == len(specs)
+        ranks = range(wl.world) if wl.world <= 128 else list(range(0, wl.world, 37)) + [wl.rank, wl.world - 1]
+        for k in ranks:
+            assert B.rs_plan_rank_segments(plan, k) == want.rank_segments(k)
+            assert B.rs_plan_scale_range(plan, k) == want.scale_range(k)
+    finally:
+        B.rs_plan_destroy(plan)
+
+
+def random_unit(rnd):
+    n = rnd.randint(1, 7)
+    tensors = []
+    for _ in range(n):
+        kind = rnd.random()
+        if kind < 0.25:
+            tensors.append((rnd.randint(1, 700), 0, B.RS_BLOCK_1x128))
+        elif kind < 0.6:
+            tensors.append((rnd.randint(1, 400), rnd.choice([8, 24, 128, 130, 136, 256, 100]), B.RS_BLOCK_128x128))
+        elif kind < 0.8:
+            tensors.append((rnd.randint(1, 60), rnd.choice([8, 40, 128, 200]), B.RS_BLOCK_1x128))
+        elif kind < 0.9:
+            tensors.append((rnd.randint(1, 50), rnd.randint(1, 50), B.RS_BLOCK_WHOLE))
+        else:
+            tensors.append((rnd.randint(1, 50), rnd.randint(1, 50), B.RS_BLOCK_EXPLICIT, rnd.randint(1, 64)))
+    world = rnd.choice([1, 2, 3, 4, 7, 8, 16, 33])
+    align, item = rnd.choice([(16, 1), (16, 2), (16, 4), (32, 1), (8, 8)])
+    A = rnd.choice([0, 0, 1, 2])
+    if A and (align // item) % A:
+        A = 0
+    return tensors, world, align, item, A
+
+
+def test_random_units_match_oracle():
+    rnd = random.Random(21)
+    for _ in range(400):
+        tensors, world, align, item, A = random_unit(rnd)
+        specs = [P.TensorSpec(*t) for t in tensors]
+        want = P.make_plan(specs, world, align, item, tensor_align=A or None)
+        plan = B.rs_plan_create(tensors, world, align, item, A)
+        try:
+            assert B.rs_plan_shard_elems(plan) == want.S, (tensors, world, align, item, A)
+            assert B.rs_plan_offsets(plan) == want.offsets
+            for k in range(world):
+                assert B.rs_plan_rank_segments(plan, k) == want.rank_segments(k)
+                if all(s.quantised for s in specs):
+                    assert B.rs_plan_scale_range(plan, k) == want.scale_range(k)
+        finally:
+            B.rs_plan_destroy(plan)
+
+
+def test_check_valid_shard_matches_oracle():
+    rnd = random.Random(22)
+    for _ in range(300):
+        tensors, world, align, item, A = random_unit(rnd)
+        specs = [P.TensorSpec(*t) for t in tensors]
+        g_coll = align // item
+        a = A or g_coll
+        pairs = [(s.e, s.g) for s in specs]
+        for _ in range(6):
+            S = a * rnd.randint(1, 4000)
+            assert B.rs_check_valid_shard(tensors, world, align, item, A, S) == \
+                P.check_valid_shard(pairs, world, S, a, P.smallest_start)
+
+
+def test_bad_arguments_give_error_codes():
+    ok = [(16, 16, B.RS_BLOCK_128x128)]
+    for args in [
+        ([], 4, 16, 1, 0),
+        (ok, 0, 16, 1, 0),
+        (ok, 4, 0, 1, 0),
+        (ok, 4, 16, 0, 0),
+        (ok, 4, 16, 3, 0),                      # alignment not a multiple of the item size
+        (ok, 4, 16, 1, 3),                      # tensor alignment must divide g_coll
+        ([(0, 4, 0)], 4, 16, 1, 0),             # empty tensor
+        ([(4, -1, 0)], 4, 16, 1, 0),
+        ([(4, 0, B.RS_BLOCK_128x128)], 4, 16, 1, 0),   # tiles need 2-D
+        ([(4, 4, 9)], 4, 16, 1, 0),             # unknown mode
+        ([(4, 4, B.RS_BLOCK_EXPLICIT, 0)], 4, 16, 1, 0),
+    ]:
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_plan_create(*args)
+        assert e.value.code == B.RS_EINVAL
+    with pytest.raises(B.RaggedShardError) as e:
+        B.rs_plan_create([(1 << 40, 1 << 30, B.RS_BLOCK_WHOLE)], 4, 16, 1, 0)
+    assert e.value.code == B.RS_EOVERFLOW
+    with pytest.raises(B.RaggedShardError) as e:
+        B.rs_plan_create([(1 << 50, 0, B.RS_BLOCK_WHOLE)], 1 << 20, 16, 1, 0)
+    assert e.value.code == B.RS_EOVERFLOW
+    # null output pointer / null plan
+    assert B.raw_call("rs_plan_create", None, 1, 1, 16, 1, 0, None) == B.RS_EINVAL
+    assert B.raw_call("rs_plan_num_tensors", None) == B.RS_EINVAL
+    plan = B.rs_plan_create(ok, 4)
+    try:
+        with pytest.raises(B.RaggedShardError):
+            B.rs_plan_scale_range(plan, 4)
+        with pytest.raises(B.RaggedShardError):
+            B.rs_plan_rank_segments(plan, -1)
+        # device calls before upload are refused, never crash
+        assert B.raw_call("rs_pack", C.c_void_p(plan), None, None, None) == B.RS_ENOTUPLOADED
+        assert B.raw_call("rs_reduce", C.c_void_p(plan), 0, None, C.c_int64(0), None, None) == B.RS_ENOTUPLOADED
+    finally:
+        B.rs_plan_destroy(plan)
+
+
+def test_planner_runtime_on_largest_config():
+    import time
+    wl = WORKLOADS[5]
+    t0 = time.time()
+    plan = B.rs_plan_create([(t.rows, t.cols, t.mode) for t in wl.tensors], wl.world)
+    dt = time.time() - t0
+    B.rs_plan_destroy(plan)
+    assert dt < 0.3           # "less than 0.3 seconds" (Section 6.4)
