@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the RaggedShard / DBuffer hot path on one MI355X.
+
+A step is one pass of the whole path over the Llama-3-8B-shaped workload (W = 64, 128x128
+FP8 blocks): for each of 32 decoder units back to back
+    ragged_pack (per-parameter grads -> DBuffer), shard_reduce over rank 0's shard (64 partials),
+    block_quant of rank 0's shard, dequant_unpack of the gathered FP8 unit.
+All inputs are synthetic and resident in HBM before the timed region.  One JSON line is printed:
+whole-step algorithmic GB/s as `value`, per-kernel figures, the roofline of the dominant
+kernel (HIP events around every launch inside the timed region) and the CPU oracle timed on
+a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+
+
+def algorithmic_bytes(E, W, S, payload_r, nb_r, nb):
+    """Bytes each op must move per unit (bf16 = 2, fp32 = 4, fp8 = 1)."""
+    return {
+        "ragged_pack": 2 * E + 2 * W * S,                    # read every tensor, write the whole DBuffer
+        "shard_reduce": 2 * W * payload_r + 4 * S,           # W partials of the payload, fp32 shard out
+        "block_quant": 2 * payload_r + S + 4 * nb_r,         # bf16 shard in, codes (padding zeroed) + scales out
+        "dequant_unpack": E + 4 * nb + 2 * E,                # codes + scales in, bf16 tensors out
+    }
+
+
+def cpu_baseline(wl, seed=1):
+    """The oracle as it stands, on a bounded sample of the workload: the first seven tensors of
+    unit 0 (attn_norm, wq, wk, wv, wo, ffn_norm, w1) for pack / quant / dequant, and the first
+    half of rank 0's shard with all W partials for reduce."""
+    import numpy as np
+    from oracle import dbuffer as OD
+    from oracle import fp8 as OF
+    from oracle import plan as OP
+    from workloads import gen_param, gen_partial
+
+    specs = [OP.TensorSpec(t.rows, t.cols, t.mode) for t in wl.tensors]
+    plan = OP.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize)
+    k = 7
+    params = [gen_param(wl, seed, t) for t in range(k)]
+    total_s = plan.offsets[k - 1] + specs[k - 1].e
+    E_s = sum(s.e for s in specs[:k])
+    n_red = plan.S // 2 // 8 * 8
+    parts = np.stack([gen_partial(wl, seed, w, n_red) for w in range(wl.world)])
+    segs = [(t, so, do, min(n, n_red - do)) for t, so, do, n in plan.rank_segments(wl.rank) if do < n_red]
+    payload_red = sum(s[3] for s in segs)
+
+    t0 = time.perf_counter()
+    db = OD.ragged_pack(params, plan.offsets[:k], total_s)
+    t1 = time.perf_counter()
+    OD.shard_reduce(parts, segs)
+    t2 = time.perf_counter()
+    qs = [OF.quantise_tensor(db[l:l + s.e], s) for s, l in zip(specs[:k], plan.offsets[:k])]
+    t3 = time.perf_counter()
+    for (c, sc), s in zip(qs, specs[:k]):
+        OF.dequantise_tensor(c, sc, s)
+    t4 = time.perf_counter()
+    nb_s = sum(s.num_blocks for s in specs[:k])
+    moved = {
+        "ragged_pack": 2 * E_s + 2 * total_s,
+        "shard_reduce": 2 * wl.world * payload_red + 4 * n_red,
+        "block_quant": 3 * E_s + 4 * nb_s,
+        "dequant_unpack": 3 * E_s + 4 * nb_s,
+    }
+    secs = {"ragged_pack": t1 - t0, "shard_reduce": t2 - t1, "block_quant": t3 - t2, "dequant_unpack": t4 - t3}
+    total_bytes, total_s_ = sum(moved.values()), sum(secs.values())
+    return {
+        "value": round(total_bytes / total_s_ / 1e9, 4),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": (f"unit 0, first {k} tensors ({E_s} of {plan.payload} elements) for pack/quant/dequant; "
+                   f"reduce over {wl.world} partials of the first {n_red} elements of rank {wl.rank}'s shard; "
+                   f"{total_s_:.1f} s of numpy (single thread)"),
+        "per_op_GBps": {k_: round(moved[k_] / secs[k_] / 1e9, 4) for k_ in moved},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--units", type=int, default=0, help="units per step (default: the workload's 32)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the path; this build has no multi-GPU code "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_22437_amd import binding as B   # raises if the HIP library is missing
+    from workloads import WORKLOADS
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    wl = WORKLOADS[2]
+    units = args.units or wl.units
+    desc = [(t.rows, t.cols, t.mode) for t in wl.tensors]
+    plan = B.rs_plan_create(desc, wl.world, wl.align_bytes, wl.min_itemsize)
+    B.rs_plan_upload(plan, 0)
+    S, total, E = B.rs_plan_shard_elems(plan), B.rs_plan_total_elems(plan), B.rs_plan_payload_elems(plan)
+    W, rank = wl.world, wl.rank
+    nb = B.rs_plan_num_scales(plan)
+    lo, hi = B.rs_plan_scale_range(plan, rank)
+    payload_r = sum(s[3] for s in B.rs_plan_rank_segments(plan, rank))
+    per_unit = algorithmic_bytes(E, W, S, payload_r, hi - lo, nb)
+
+    # ---- synthetic inputs, resident in HBM ----
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    U = []
+    for u in range(units):
+        src = [torch.empty(t.numel, dtype=torch.bfloat16, device="cuda").normal_(0, wl.sigma, generator=gen)
+               for t in wl.tensors]
+        dst = [torch.empty(t.numel, dtype=torch.bfloat16, device="cuda") for t in wl.tensors]
+        d = dict(
+            src=src, dst=dst,
+            src_tab=B.rs_tensor_table_create(plan, src), dst_tab=B.rs_tensor_table_create(plan, dst),
+            dbuf=torch.empty(total, dtype=torch.bfloat16, device="cuda"),
+            partials=torch.empty(W * S, dtype=torch.bfloat16, device="cuda").normal_(0, 1e-3, generator=gen),
+            out=torch.empty(S, dtype=torch.float32, device="cuda"),
+            codes=torch.empty(total, dtype=torch.uint8, device="cuda"),
+            scales=torch.empty(nb, dtype=torch.float32, device="cuda"),
+        )
+        # the gathered FP8 unit that AllGather would deliver: quantise every rank's shard once, untimed
+        B.rs_pack(plan, d["src_tab"], d["dbuf"])
+        B.rs_quantize(plan, -1, d["dbuf"], d["codes"], d["scales"])
+        U.append(d)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    names = ["ragged_pack", "shard_reduce", "block_quant", "dequant_unpack"]
+
+    def step(events=None):
+        for d in U:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if events is not None else None
+            if ev:
+                ev[0].record(stream)
+            B.rs_pack(plan, d["src_tab"], d["dbuf"], stream)
+            if ev:
+                ev[1].record(stream)
+            B.rs_reduce(plan, rank, d["partials"], S, d["out"], stream)
+            if ev:
+                ev[2].record(stream)
+            B.rs_quantize(plan, rank, d["dbuf"][rank * S:(rank + 1) * S], d["codes"][rank * S:(rank + 1) * S],
+                          d["scales"][lo:hi], stream)
+            if ev:
+                ev[3].record(stream)
+            B.rs_unpack(plan, d["codes"], d["scales"], d["dst_tab"], stream)
+            if ev:
+                ev[4].record(stream)
+                events.append(ev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    kern_ms = {n: 0.0 for n in names}
+    for ev in events:
+        for i, n in enumerate(names):
+            kern_ms[n] += ev[i].elapsed_time(ev[i + 1])
+    launches = len(events)
+    kern_ms = {n: v / launches for n, v in kern_ms.items()}
+    step_bytes = units * sum(per_unit.values())
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    kernels = {}
+    for n in names:
+        gbps = per_unit[n] / (kern_ms[n] * 1e-3) / 1e9
+        kernels[n] = {"ms": round(kern_ms[n], 4), "bytes": per_unit[n], "GBps": round(gbps, 1),
+                      "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+
+    # ---- extras outside the timed steps: all-shard quantisation and the plain-copy ceiling ----
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for i in range(reps):
+            fn(i)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    qa_bytes = 2 * E + total + 4 * nb
+    qa_ms = timed(lambda i=0: B.rs_quantize(plan, -1, U[i % units]["dbuf"], U[i % units]["codes"],
+                                            U[i % units]["scales"], stream), max(units, 8))
+    kernels["block_quant_all_shards"] = {
+        "ms": round(qa_ms, 4), "bytes": qa_bytes, "GBps": round(qa_bytes / qa_ms / 1e6, 1),
+        "frac_of_peak": round(qa_bytes / qa_ms / 1e6 / HBM_PEAK_GBPS, 4),
+        "note": "same kernel over all W shards of a unit in one launch; not part of the timed step"}
+    nbytes = total * 2
+    cp_ms = timed(lambda i=0: B.rs_copy_probe(U[(i + 1) % units]["dbuf"], U[i % units]["dbuf"], nbytes, stream),
+                  max(units, 8))
+    copy_gbps = 2 * nbytes / cp_ms / 1e6
+
+    dom = max(names, key=lambda n: kern_ms[n])
+    roof = {
+        "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+        "avg_launch_ms": kernels[dom]["ms"], "algorithmic_bytes_per_launch": per_unit[dom],
+        "plain_copy_GBps": round(copy_gbps, 1),
+    }
+    result = {
+        "metric": "HBM GB/s & % of peak: ragged_pack, shard_reduce, FP8 block_quant, unpack",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 in, fp32 accumulate, fp8-e4m3 codes", "data": "synthetic",
+        "config": {"workload": f"configs[1]: {wl.name}, {units} units back to back", "world": W,
+                   "shard_elems": S, "unit_elems": E, "dbuffer_elems": total, "rank": rank,
+                   "blocks": "128x128 (2-D), 1x128 (1-D)", "bytes_per_step": step_bytes},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "kernels": kernels,
+        "roofline": roof,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(result), flush=True)
+
+    for d in U:
+        B.rs_tensor_table_destroy(d["src_tab"])
+        B.rs_tensor_table_destroy(d["dst_tab"])
+    B.rs_plan_destroy(plan)
+
+
+if __name__ == "__main__":
+    main()
