@@ -15,6 +15,7 @@ a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -96,6 +97,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--units", type=int, default=0, help="units per step (default: the workload's 32)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--workload", type=int, default=2,
+                    help="configuration 1-5 (default 2, the one the metric is quoted on)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the path; this build has no multi-GPU code "
@@ -110,8 +113,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    wl = WORKLOADS[2]
+    wl = WORKLOADS[args.workload]
     units = args.units or wl.units
+    quant = wl.quantised
     desc = [(t.rows, t.cols, t.mode) for t in wl.tensors]
     plan = B.rs_plan_create(desc, wl.world, wl.align_bytes, wl.min_itemsize)
     B.rs_plan_upload(plan, 0)
@@ -121,6 +125,9 @@ def main():
     lo, hi = B.rs_plan_scale_range(plan, rank)
     payload_r = sum(s[3] for s in B.rs_plan_rank_segments(plan, rank))
     per_unit = algorithmic_bytes(E, W, S, payload_r, hi - lo, nb)
+    if not quant:   # bf16-only path: pack, reduce, plain unpack
+        per_unit = {"ragged_pack": per_unit["ragged_pack"], "shard_reduce": per_unit["shard_reduce"],
+                    "unpack_bf16": 2 * E + 2 * E}
 
     # ---- synthetic inputs, resident in HBM ----
     gen = torch.Generator(device="cuda")
@@ -136,20 +143,26 @@ def main():
             dbuf=torch.empty(total, dtype=torch.bfloat16, device="cuda"),
             partials=torch.empty(W * S, dtype=torch.bfloat16, device="cuda").normal_(0, 1e-3, generator=gen),
             out=torch.empty(S, dtype=torch.float32, device="cuda"),
-            codes=torch.empty(total, dtype=torch.uint8, device="cuda"),
-            scales=torch.empty(nb, dtype=torch.float32, device="cuda"),
         )
-        # the gathered FP8 unit that AllGather would deliver: quantise every rank's shard once, untimed
         B.rs_pack(plan, d["src_tab"], d["dbuf"])
-        B.rs_quantize(plan, -1, d["dbuf"], d["codes"], d["scales"])
+        if quant:
+            # the gathered FP8 unit that AllGather would deliver: quantise every rank's shard once, untimed
+            d["codes"] = torch.empty(total, dtype=torch.uint8, device="cuda")
+            d["scales"] = torch.empty(max(nb, 1), dtype=torch.float32, device="cuda")
+            B.rs_quantize(plan, -1, d["dbuf"], d["codes"], d["scales"])
+            # rank views made once: the timed loop does no tensor bookkeeping
+            d["shard"] = d["dbuf"][rank * S:(rank + 1) * S]
+            d["shard_codes"] = d["codes"][rank * S:(rank + 1) * S]
+            d["shard_scales"] = d["scales"][lo:hi]
         U.append(d)
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
-    names = ["ragged_pack", "shard_reduce", "block_quant", "dequant_unpack"]
+    names = list(per_unit)
 
     def step(events=None):
         for d in U:
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if events is not None else None
+            ev = ([torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
+                  if events is not None else None)
             if ev:
                 ev[0].record(stream)
             B.rs_pack(plan, d["src_tab"], d["dbuf"], stream)
@@ -158,24 +171,29 @@ def main():
             B.rs_reduce(plan, rank, d["partials"], S, d["out"], stream)
             if ev:
                 ev[2].record(stream)
-            B.rs_quantize(plan, rank, d["dbuf"][rank * S:(rank + 1) * S], d["codes"][rank * S:(rank + 1) * S],
-                          d["scales"][lo:hi], stream)
+            if quant:
+                B.rs_quantize(plan, rank, d["shard"], d["shard_codes"], d["shard_scales"], stream)
+                if ev:
+                    ev[3].record(stream)
+                B.rs_unpack(plan, d["codes"], d["scales"], d["dst_tab"], stream)
+            else:
+                B.rs_unpack_bf16(plan, d["dbuf"], d["dst_tab"], stream)
             if ev:
-                ev[3].record(stream)
-            B.rs_unpack(plan, d["codes"], d["scales"], d["dst_tab"], stream)
-            if ev:
-                ev[4].record(stream)
+                ev[-1].record(stream)
                 events.append(ev)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     events = []
+    gc.collect()
+    gc.disable()          # no collector pauses between launches inside the timed region
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    gc.enable()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     kern_ms = {n: 0.0 for n in names}
@@ -205,15 +223,17 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
-    qa_bytes = 2 * E + total + 4 * nb
-    qa_ms = timed(lambda i=0: B.rs_quantize(plan, -1, U[i % units]["dbuf"], U[i % units]["codes"],
-                                            U[i % units]["scales"], stream), max(units, 8))
-    kernels["block_quant_all_shards"] = {
-        "ms": round(qa_ms, 4), "bytes": qa_bytes, "GBps": round(qa_bytes / qa_ms / 1e6, 1),
-        "frac_of_peak": round(qa_bytes / qa_ms / 1e6 / HBM_PEAK_GBPS, 4),
-        "note": "same kernel over all W shards of a unit in one launch; not part of the timed step"}
+    if quant:
+        qa_bytes = 2 * E + total + 4 * nb
+        qa_ms = timed(lambda i=0: B.rs_quantize(plan, -1, U[i % units]["dbuf"], U[i % units]["codes"],
+                                                U[i % units]["scales"], stream), max(units, 8))
+        kernels["block_quant_all_shards"] = {
+            "ms": round(qa_ms, 4), "bytes": qa_bytes, "GBps": round(qa_bytes / qa_ms / 1e6, 1),
+            "frac_of_peak": round(qa_bytes / qa_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "note": "same kernel over all W shards of a unit in one launch; not part of the timed step"}
     nbytes = total * 2
-    cp_ms = timed(lambda i=0: B.rs_copy_probe(U[(i + 1) % units]["dbuf"], U[i % units]["dbuf"], nbytes, stream),
+    probe_dst = [d["dbuf"] for d in U[1:]] + [torch.empty(total, dtype=torch.bfloat16, device="cuda")]
+    cp_ms = timed(lambda i=0: B.rs_copy_probe(probe_dst[i % units], U[i % units]["dbuf"], nbytes, stream),
                   max(units, 8))
     copy_gbps = 2 * nbytes / cp_ms / 1e6
 
@@ -229,14 +249,14 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 in, fp32 accumulate, fp8-e4m3 codes", "data": "synthetic",
-        "config": {"workload": f"configs[1]: {wl.name}, {units} units back to back", "world": W,
+        "config": {"workload": f"configs[{wl.index - 1}]: {wl.name}, {units} unit(s) back to back", "world": W,
                    "shard_elems": S, "unit_elems": E, "dbuffer_elems": total, "rank": rank,
                    "blocks": "128x128 (2-D), 1x128 (1-D)", "bytes_per_step": step_bytes},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "kernels": kernels,
         "roofline": roof,
     }
-    if not args.no_cpu:
+    if not args.no_cpu and wl.index == 2:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result), flush=True)
 
