@@ -37,8 +37,10 @@ __device__ __forceinline__ void st8(void* p, u32x2 v) {
 template <bool kUnpack>
 __global__ __launch_bounds__(kThreads) void group_copy_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
-    void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S, int64_t gpr) {
-  const int64_t bid = blockIdx.x;
+    const int32_t* __restrict__ granules, void* const* __restrict__ ptrs,
+    uint16_t* __restrict__ dbuf, int64_t S, int64_t gpr) {
+  // pack visits every granule (padding must be zeroed); unpack only those that hold payload
+  const int64_t bid = kUnpack ? int64_t(granules[blockIdx.x]) : int64_t(blockIdx.x);
   const int64_t k = bid / gpr;
   const int64_t i0 = (bid - k * gpr) * kGranule;
   const int64_t d0 = k * S + i0;
@@ -197,12 +199,16 @@ __global__ __launch_bounds__(kThreads) void shard_reduce_kernel(
 }
 
 // -------------------------------------------------------------------------------------------
-// Work-item geometry shared by block_quant and dequant_unpack.
-// A workgroup owns 128 "row slots" of up to 128 elements: the 128 rows of one 128x128 tile, or
-// 128 consecutive 1x128 blocks.  Lane (r_in, cg) = (tid / 16, tid % 16) handles elements
-// [8*cg, 8*cg + 8) of slots r_in + 16*i, i = 0..7, so one access instruction covers 16 slots
-// of 256 contiguous bytes each.
+// block_quant work-item geometry.
+// A workgroup of 512 lanes owns 128 "row slots" of up to 128 elements: the 128 rows of one
+// 128x128 tile, or 128 consecutive 1x128 blocks.  Lane (r_in, cg) = (tid / 16, tid % 16) handles
+// elements [8*cg, 8*cg + 8) of slots r_in + 32*i, i = 0..3, so one access instruction covers 32
+// slots of 256 contiguous bytes each and a lane keeps four 16-byte vectors in flight.
 // -------------------------------------------------------------------------------------------
+constexpr int kQuantThreads = 512;
+constexpr int kQuantLoads = kItemSlots * 16 / kQuantThreads;  // 4
+constexpr int kQuantRowStep = kQuantThreads / 16;             // 32
+
 struct Slot {
   int64_t off;   // element offset inside the tensor of this lane's 8 elements
   int64_t blk;   // scale index relative to the tensor (1x128 runs only)
@@ -246,39 +252,76 @@ __device__ __forceinline__ unsigned abs_max_bits(unsigned m, unsigned packed) {
   return max(m, (packed >> 16) & 0x7fffu);
 }
 
-__device__ __forceinline__ unsigned quant_pair(unsigned packed, float scale) {
+// The divisor of a block (its scale) is shared by all its elements, so the correctly rounded
+// quotient x / scale is obtained without a per-element IEEE division sequence:
+//   r  = RN(1 / b)                      one true division per block
+//   q0 = RN(a * r)                      within 1.5 ulp of a / b
+//   q1 = RN(q0 + RN(a - b * q0) * r)    a faithful rounding of a / b
+//   q2 = RN(q1 + (a - b * q1) * r)      = RN(a / b): from a faithful q1 the residual is exact
+//                                         in an FMA and this last step rounds correctly (Markstein)
+// This holds while no intermediate under- or overflows, which kDivFastLo <= amax < kDivFastHi
+// guarantees for every element whose quotient is not far below the smallest E4M3 subnormal
+// (those give a zero code either way); blocks outside that range take the plain division.
+// The sign is re-applied at the end because the corrections turn -0 into +0.
+constexpr unsigned kDivFastLo = 67u << 7;    // amax >= 2^-60 (bf16 bit pattern)
+constexpr unsigned kDivFastHi = 188u << 7;   // amax <  2^61
+
+struct Divisor {
+  float b, r;
+  bool fast;
+};
+
+__device__ __forceinline__ Divisor make_divisor(unsigned amax_bits) {
+  Divisor d;
+  d.b = __uint_as_float(amax_bits << 16) / kE4M3Max;
+  d.fast = amax_bits >= kDivFastLo && amax_bits < kDivFastHi;
+  d.r = d.fast ? 1.0f / d.b : 0.0f;
+  return d;
+}
+
+__device__ __forceinline__ float divide(float a, const Divisor& d) {
+  if (!d.fast) return a / d.b;
+  float q = a * d.r;
+  float e = __builtin_fmaf(-q, d.b, a);
+  q = __builtin_fmaf(e, d.r, q);
+  e = __builtin_fmaf(-q, d.b, a);
+  q = __builtin_fmaf(e, d.r, q);
+  return __builtin_copysignf(q, a);
+}
+
+__device__ __forceinline__ unsigned quant_pair(unsigned packed, const Divisor& d) {
   // two bf16 -> two E4M3 codes in the low 16 bits
-  const float a = __uint_as_float(packed << 16) / scale;
-  const float b = __uint_as_float(packed & 0xffff0000u) / scale;
+  const float a = divide(__uint_as_float(packed << 16), d);
+  const float b = divide(__uint_as_float(packed & 0xffff0000u), d);
   const float ca = __builtin_amdgcn_fmed3f(a, -kE4M3Max, kE4M3Max);
   const float cb = __builtin_amdgcn_fmed3f(b, -kE4M3Max, kE4M3Max);
   return unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xffffu;
 }
 
-__device__ __forceinline__ void zero_fill_bytes(uint8_t* dst, int count) {
+__device__ __forceinline__ void zero_fill_bytes(uint8_t* dst, int count, int nthreads) {
   // dst need not be aligned: bytes up to the first 16-byte line, vectors, bytes after
   const int head = min(count, int((16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15));
   const int nvec = (count - head) >> 4;
   const int tail = (count - head) & 15;
   const int tid = threadIdx.x;
   if (tid < head) dst[tid] = 0;
-  for (int v = tid; v < nvec; v += kThreads) st16(dst + head + (v << 4), u32x4{0, 0, 0, 0});
+  for (int v = tid; v < nvec; v += nthreads) st16(dst + head + (v << 4), u32x4{0, 0, 0, 0});
   if (tid < tail) dst[head + (nvec << 4) + tid] = 0;
 }
 
 // -------------------------------------------------------------------------------------------
-// block_quant: amax per block (wavefront shuffles, LDS across the 4 waves of a tile),
+// block_quant: amax per block (wavefront shuffles, LDS across the 8 waves of a tile),
 // scale = amax / 448, codes = E4M3(clamp(x / scale)) with the hardware RNE convert.
 // x / codes are addressed relative to elem_base (0 or rank * S), scales to scale_off.
 // -------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void block_quant_kernel(
+__global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
     const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
     const uint16_t* __restrict__ x, uint8_t* __restrict__ codes, float* __restrict__ scales,
     int64_t elem_base, int64_t scale_off) {
-  __shared__ unsigned wave_max[kThreads / 64];
+  __shared__ unsigned wave_max[kQuantThreads / 64];
   const Item it = items[item_off + blockIdx.x];
   if (it.tensor < 0) {
-    zero_fill_bytes(codes + (it.first - elem_base), it.count);
+    zero_fill_bytes(codes + (it.first - elem_base), it.count, kQuantThreads);
     return;
   }
   const TensorDev t = T[it.tensor];
@@ -288,12 +331,12 @@ __global__ __launch_bounds__(kThreads) void block_quant_kernel(
   const int r_in = tid >> 4, col0 = (tid & 15) * 8;
   const int64_t base = t.ell - elem_base;
 
-  Slot sl[8];
-  u32x4 v[8];
+  Slot sl[kQuantLoads];
+  u32x4 v[kQuantLoads];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    sl[i] = tile ? tile_slot(t, it.first, it.count, r_in + 16 * i, col0)
-                 : run_slot(t, it.first, it.count, r_in + 16 * i, col0);
+  for (int i = 0; i < kQuantLoads; ++i) {
+    sl[i] = tile ? tile_slot(t, it.first, it.count, r_in + kQuantRowStep * i, col0)
+                 : run_slot(t, it.first, it.count, r_in + kQuantRowStep * i, col0);
     v[i] = u32x4{0, 0, 0, 0};
     if (sl[i].ncol == 0) continue;
     const uint16_t* src = x + base + sl[i].off;
@@ -316,9 +359,9 @@ __global__ __launch_bounds__(kThreads) void block_quant_kernel(
   }
 
   // per-slot amax over this lane's 8 elements, then over the 16 lanes of the slot
-  unsigned m[8];
+  unsigned m[kQuantLoads];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < kQuantLoads; ++i) {
     unsigned a = 0;
     a = abs_max_bits(a, v[i].x);
     a = abs_max_bits(a, v[i].y);
@@ -329,38 +372,40 @@ __global__ __launch_bounds__(kThreads) void block_quant_kernel(
   if (tile) {
     unsigned a = m[0];
 #pragma unroll
-    for (int i = 1; i < 8; ++i) a = max(a, m[i]);
+    for (int i = 1; i < kQuantLoads; ++i) a = max(a, m[i]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
     if ((tid & 63) == 0) wave_max[tid >> 6] = a;
     __syncthreads();
-    a = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    a = wave_max[0];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) m[i] = a;
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) m[i] = a;
     if (tid == 0) {
       const int64_t sidx = t.scale_base + it.first * t.nbc + it.count - scale_off;
       scales[sidx] = __uint_as_float(a << 16) / kE4M3Max;
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < kQuantLoads; ++i) {
       unsigned a = m[i];
 #pragma unroll
       for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
       m[i] = a;
-      if ((tid & 15) == 0 && r_in + 16 * i < it.count)
+      if ((tid & 15) == 0 && r_in + kQuantRowStep * i < it.count)
         scales[t.scale_base + sl[i].blk - scale_off] = __uint_as_float(a << 16) / kE4M3Max;
     }
   }
 
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < kQuantLoads; ++i) {
     if (sl[i].ncol == 0) continue;
     u32x2 c{0, 0};
     if (m[i] != 0) {
-      const float scale = __uint_as_float(m[i] << 16) / kE4M3Max;
-      c.x = quant_pair(v[i].x, scale) | (quant_pair(v[i].y, scale) << 16);
-      c.y = quant_pair(v[i].z, scale) | (quant_pair(v[i].w, scale) << 16);
+      const Divisor d = make_divisor(m[i]);
+      c.x = quant_pair(v[i].x, d) | (quant_pair(v[i].y, d) << 16);
+      c.y = quant_pair(v[i].z, d) | (quant_pair(v[i].w, d) << 16);
     }
     uint8_t* dst = codes + base + sl[i].off;
     if (vec && sl[i].ncol == 8) {
@@ -375,6 +420,9 @@ __global__ __launch_bounds__(kThreads) void block_quant_kernel(
 
 // -------------------------------------------------------------------------------------------
 // dequant_unpack: codes of the gathered unit -> per-tensor bf16, value(code) * scale then RNE.
+// Buffer-driven like ragged_pack: one workgroup per window of kWindowGranules granules (8192
+// codes) that holds payload; a lane converts 8 codes (one 8-byte load, one 16-byte store) in
+// each of the window's granules.  No block-wide step is needed, only the block's scale.
 // -------------------------------------------------------------------------------------------
 __device__ __forceinline__ unsigned bf16_rne(float f) {
   const unsigned u = __float_as_uint(f);
@@ -388,56 +436,90 @@ __device__ __forceinline__ void dequant4(unsigned word, float scale, unsigned& l
   hi = bf16_rne(b[0] * scale) | (bf16_rne(b[1] * scale) << 16);
 }
 
-__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
-    const TensorDev* __restrict__ T, const Item* __restrict__ items,
-    const uint8_t* __restrict__ codes, const float* __restrict__ scales,
-    void* const* __restrict__ ptrs) {
-  const Item it = items[blockIdx.x];
-  if (it.tensor < 0) return;
-  const TensorDev t = T[it.tensor];
-  const bool tile = (t.flags & kFlagTile) != 0;
-  const bool vec_in = (t.flags & kFlagVec) != 0;
-  uint16_t* out = reinterpret_cast<uint16_t*>(ptrs[it.tensor]);
-  const bool vec_out = vec_in && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
-  const int tid = threadIdx.x;
-  const int r_in = tid >> 4, col0 = (tid & 15) * 8;
-  const float tile_scale = tile ? scales[t.scale_base + it.first * t.nbc + it.count] : 0.0f;
+// scale index (relative to the tensor) of the element at (row, col)
+__device__ __forceinline__ int64_t scale_index(const TensorDev& t, int64_t row, int64_t col) {
+  return ((t.flags & kFlagTile) ? (row >> 7) : row) * t.nbc + (col >> 7);
+}
 
-  Slot sl[8];
-  u32x2 c[8];
+__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
+    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
+    const int32_t* __restrict__ windows, const uint8_t* __restrict__ codes,
+    const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr,
+    int64_t wpr) {
+  constexpr int kWin = kWindowGranules * kGranule;
+  const int64_t wid = windows[blockIdx.x];
+  const int64_t k = wid / wpr;
+  const int64_t j = wid - k * wpr;
+  const int64_t i0 = j * kWin;
+  const int64_t d0 = k * S + i0;
+  const int len = int(min(int64_t(kWin), S - i0));
+  const int t0 = gran_first[k * gpr + j * kWindowGranules];  // a payload window: t0 < n
+  const int lane = threadIdx.x * 8;
+
+  {
+    const TensorDev t = T[t0];
+    uint16_t* out = reinterpret_cast<uint16_t*>(ptrs[t0]);
+    const bool inside = t.ell <= d0 && d0 + len <= t.ell + t.e;
+    if (inside && (t.flags & kFlagVec) && (reinterpret_cast<uintptr_t>(out) & 15) == 0 &&
+        t.cols < (int64_t(1) << 30)) {
+      // The whole window lies in one tensor whose rows keep every 8-element group inside one
+      // row and one block.  (row, col) of the window's first element once per workgroup
+      // (exact: a double holds any element index below 2^53), then 32-bit steps per lane.
+      const int64_t first = d0 - t.ell;
+      int64_t row0 = int64_t(double(first) / double(t.cols));
+      int64_t col0 = first - row0 * t.cols;
+      if (col0 < 0) { col0 += t.cols; --row0; }
+      if (col0 >= t.cols) { col0 -= t.cols; ++row0; }
+      const unsigned C = unsigned(t.cols);
+      const bool contig = (t.flags & kFlagContig) && !(t.flags & kFlagTile);
+      u32x2 c[kWindowGranules];
+      float sc[kWindowGranules];
+      bool on[kWindowGranules];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    sl[i] = tile ? tile_slot(t, it.first, it.count, r_in + 16 * i, col0)
-                 : run_slot(t, it.first, it.count, r_in + 16 * i, col0);
-    c[i] = u32x2{0, 0};
-    if (sl[i].ncol == 0) continue;
-    const uint8_t* src = codes + t.ell + sl[i].off;
-    if (vec_in) {
-      c[i] = ld8(src);  // bytes past ncol are read but never written out
-    } else {
-      unsigned w[2] = {0, 0};
+      for (int h = 0; h < kWindowGranules; ++h) {
+        const int lo = h * kGranule + lane;
+        on[h] = lo < len;
+        if (!on[h]) continue;
+        c[h] = ld8(codes + d0 + lo);
+        int64_t sidx;
+        if (contig) {
+          sidx = (first + lo) >> 7;            // blocks are consecutive runs of 128 elements
+        } else {
+          const unsigned cc = unsigned(col0) + unsigned(lo);
+          const unsigned dr = cc / C;
+          sidx = scale_index(t, row0 + dr, cc - dr * C);
+        }
+        sc[h] = scales[t.scale_base + sidx];
+      }
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        if (q < sl[i].ncol) w[q >> 2] |= unsigned(src[q]) << ((q & 3) * 8);
-      c[i] = u32x2{w[0], w[1]};
+      for (int h = 0; h < kWindowGranules; ++h) {
+        if (!on[h]) continue;
+        unsigned o0, o1, o2, o3;
+        dequant4(c[h].x, sc[h], o0, o1);
+        dequant4(c[h].y, sc[h], o2, o3);
+        st16(out + first + h * kGranule + lane, u32x4{o0, o1, o2, o3});
+      }
+      return;
     }
   }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (sl[i].ncol == 0) continue;
-    const float scale = tile ? tile_scale : scales[t.scale_base + sl[i].blk];
-    unsigned o0, o1, o2, o3;
-    dequant4(c[i].x, scale, o0, o1);
-    dequant4(c[i].y, scale, o2, o3);
-    const u32x4 o{o0, o1, o2, o3};
-    uint16_t* dst = out + sl[i].off;
-    if (vec_out && sl[i].ncol == 8) {
-      st16(dst, o);
-    } else {
-      const unsigned w[4] = {o.x, o.y, o.z, o.w};
-#pragma unroll
-      for (int q = 0; q < 8; ++q)
-        if (q < sl[i].ncol) dst[q] = uint16_t(w[q >> 1] >> ((q & 1) * 16));
+
+  // Window with tensor boundaries or padding, or a tensor without 16-byte structure:
+  // every element finds its tensor, row and column on its own.
+  int s = t0;
+  for (int h = 0; h < kWindowGranules; ++h) {
+    const int lo = h * kGranule + lane;
+    if (lo >= len) break;
+    for (int q = 0; q < 8; ++q) {
+      const int64_t pos = d0 + lo + q;
+      while (s < n && T[s].ell + T[s].e <= pos) ++s;
+      if (s >= n || T[s].ell > pos) continue;
+      const TensorDev t = T[s];
+      const int64_t i = pos - t.ell;
+      const int64_t row = i / t.cols;
+      const int64_t col = i - row * t.cols;
+      const float scale = scales[t.scale_base + scale_index(t, row, col)];
+      const auto f = __builtin_amdgcn_cvt_pk_f32_fp8(int(codes[pos]), false);
+      reinterpret_cast<uint16_t*>(ptrs[s])[i] = uint16_t(bf16_rne(f[0] * scale));
     }
   }
 }
@@ -457,15 +539,18 @@ __global__ __launch_bounds__(kThreads) void copy_probe_kernel(const u32x4* __res
 static int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }
 
 int launch_group_copy(bool unpack, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf,
-                      int64_t S, int64_t gpr, int64_t world, hipStream_t st) {
-  const int64_t grid = world * gpr;
-  if (grid <= 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
+                      int64_t S, int64_t gpr, int64_t world, int64_t n_payload_gran,
+                      hipStream_t st) {
+  const int64_t grid = unpack ? n_payload_gran : world * gpr;
+  if (grid == 0) return RS_OK;
+  if (grid < 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
   if (unpack)
     group_copy_kernel<true><<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
-        dev.tensors, n, dev.gran_first, ptrs, static_cast<uint16_t*>(dbuf), S, gpr);
+        dev.tensors, n, dev.gran_first, dev.payload_gran, ptrs, static_cast<uint16_t*>(dbuf), S,
+        gpr);
   else
     group_copy_kernel<false><<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
-        dev.tensors, n, dev.gran_first, ptrs, static_cast<uint16_t*>(dbuf), S, gpr);
+        dev.tensors, n, dev.gran_first, nullptr, ptrs, static_cast<uint16_t*>(dbuf), S, gpr);
   return launched();
 }
 
@@ -483,18 +568,19 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
                        hipStream_t st) {
   if (item_count == 0) return RS_OK;
   if (item_count < 0 || item_count > 0x7fffffffLL) return RS_EOVERFLOW;
-  block_quant_kernel<<<dim3(unsigned(item_count)), dim3(kThreads), 0, st>>>(
+  block_quant_kernel<<<dim3(unsigned(item_count)), dim3(kQuantThreads), 0, st>>>(
       dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, elem_base,
       scale_off);
   return launched();
 }
 
-int launch_dequant_unpack(const DeviceTables& dev, int64_t item_count, const uint8_t* codes,
-                          const float* scales, void* const* ptrs, hipStream_t st) {
-  if (item_count == 0) return RS_OK;
-  if (item_count < 0 || item_count > 0x7fffffffLL) return RS_EOVERFLOW;
-  dequant_unpack_kernel<<<dim3(unsigned(item_count)), dim3(kThreads), 0, st>>>(
-      dev.tensors, dev.items, codes, scales, ptrs);
+int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_windows, const uint8_t* codes,
+                          const float* scales, void* const* ptrs, int64_t S, int64_t gpr,
+                          int64_t wpr, hipStream_t st) {
+  if (n_windows == 0) return RS_OK;
+  if (n_windows < 0 || n_windows > 0x7fffffffLL) return RS_EOVERFLOW;
+  dequant_unpack_kernel<<<dim3(unsigned(n_windows)), dim3(kThreads), 0, st>>>(
+      dev.tensors, n, dev.gran_first, dev.payload_win, codes, scales, ptrs, S, gpr, wpr);
   return launched();
 }
 

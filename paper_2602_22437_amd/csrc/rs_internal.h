@@ -15,6 +15,8 @@ constexpr int kGranule = 2048;
 constexpr int kItemSlots = 128;
 // A zero-fill item clears at most this many code bytes.
 constexpr int kFillElems = 32768;
+// dequant_unpack walks the buffer in windows of this many granules (8192 codes per workgroup).
+constexpr int kWindowGranules = 4;
 
 enum : int32_t {
   kFlagTile = 1,     // 128x128 tiles (else 1x128 runs)
@@ -57,6 +59,12 @@ struct HostTables {
   int64_t granules_per_rank = 0;
   std::vector<Item> items;           // rank-major
   std::vector<int64_t> item_begin;   // world + 1
+  // granules / windows that hold at least one payload element (ids = rank * per_rank + index):
+  // the unpack kernels launch one workgroup per entry and never visit pure padding
+  std::vector<int32_t> payload_gran;
+  std::vector<int32_t> payload_win;
+  int64_t windows_per_rank = 0;
+  int64_t n_payload_gran = 0, n_payload_win = 0;
 };
 
 struct DeviceTables {
@@ -64,6 +72,8 @@ struct DeviceTables {
   TensorDev* tensors = nullptr;
   int32_t* gran_first = nullptr;
   Item* items = nullptr;
+  int32_t* payload_gran = nullptr;
+  int32_t* payload_win = nullptr;
 };
 
 // ---- planner (planner.cpp) ----
