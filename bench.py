@@ -27,6 +27,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 
+# HBM bytes per launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE), each scaled by what the counter reads for the plain copy launch of known size
+# (fetch x 1.99991, write x 0.99941).  Offline measurements: they cannot be taken inside this
+# process, so they are recorded here next to the algorithmic bytes they are compared with.
+PMC_TRAFFIC_CONFIG2 = {"ragged_pack": 913.2e6, "shard_reduce": 419.4e6, "block_quant": 10.27e6,
+                       "dequant_unpack": 659.8e6}
+
 
 def algorithmic_bytes(E, W, S, payload_r, nb_r, nb):
     """Bytes each op must move per unit (bf16 = 2, fp32 = 4, fp8 = 1)."""
@@ -240,7 +247,8 @@ def main():
     dom = max(names, key=lambda n: kern_ms[n])
     roof = {
         "bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBPS, 4),
+        "traffic": PMC_TRAFFIC_CONFIG2.get(dom) if wl.index == 2 else None,
         "avg_launch_ms": kernels[dom]["ms"], "algorithmic_bytes_per_launch": per_unit[dom],
         "plain_copy_GBps": round(copy_gbps, 1),
     }
