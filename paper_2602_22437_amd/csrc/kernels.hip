@@ -120,15 +120,21 @@ __device__ __forceinline__ void add_bf16x8(float (&acc)[8], const u32x4 v) {
   acc[7] += __uint_as_float(v.w & 0xffff0000u);
 }
 
-__global__ __launch_bounds__(kThreads) void shard_reduce_kernel(
+// kReduceThreads = 256: one granule per workgroup; 512: two granules (8 KiB contiguous per row),
+// which is faster on long regions and slightly slower when the grid is only a few waves deep.
+template <int kReduceThreads>
+__global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
     const uint16_t* __restrict__ P, int64_t row_stride, float* __restrict__ out, int64_t S,
     int64_t gpr, int rank, int W, float inv_w) {
-  const int64_t j = blockIdx.x;
+  // with 512 lanes, waves 0-3 take the even granule of the pair, waves 4-7 the odd one
+  const int half = __builtin_amdgcn_readfirstlane(int(threadIdx.x) / kThreads);  // wave-uniform
+  const int64_t j = int64_t(blockIdx.x) * (kReduceThreads / kThreads) + half;
+  if (j >= gpr) return;
   const int64_t i0 = j * kGranule;
   const int64_t d0 = int64_t(rank) * S + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
-  const int lane_off = threadIdx.x * 8;
+  const int lane_off = (threadIdx.x % kThreads) * 8;
   if (lane_off >= len) return;
   const int64_t d = d0 + lane_off;
   float* o = out + i0 + lane_off;
@@ -172,17 +178,13 @@ __global__ __launch_bounds__(kThreads) void shard_reduce_kernel(
 #pragma unroll
     for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
   }
-  for (int a = 0; w < W; ++w, ++a) {  // W mod 8 leftover rows keep the row -> set rule
-    const u32x4 v = ld16(p + int64_t(w) * row_stride);
-    switch (a) {
-      case 0: add_bf16x8(acc[0], v); break;
-      case 1: add_bf16x8(acc[1], v); break;
-      case 2: add_bf16x8(acc[2], v); break;
-      case 3: add_bf16x8(acc[3], v); break;
-      case 4: add_bf16x8(acc[4], v); break;
-      case 5: add_bf16x8(acc[5], v); break;
-      default: add_bf16x8(acc[6], v); break;
-    }
+  if (w < W) {  // W mod 8 leftover rows keep the row -> set rule; absent rows add +0
+    u32x4 v[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+      v[a] = w + a < W ? ld16(p + int64_t(w + a) * row_stride) : u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
   }
   float r[8];
 #pragma unroll
@@ -208,6 +210,7 @@ __global__ __launch_bounds__(kThreads) void shard_reduce_kernel(
 constexpr int kQuantThreads = 512;
 constexpr int kQuantLoads = kItemSlots * 16 / kQuantThreads;  // 4
 constexpr int kQuantRowStep = kQuantThreads / 16;             // 32
+static_assert(kQuantLoads == 4, "the lean path combines exactly four per-lane maxima");
 
 struct Slot {
   int64_t off;   // element offset inside the tensor of this lane's 8 elements
@@ -309,6 +312,61 @@ __device__ __forceinline__ void zero_fill_bytes(uint8_t* dst, int count, int nth
   if (tid < tail) dst[head + (nvec << 4) + tid] = 0;
 }
 
+// One full work item whose rows are 16-byte structured: 128 slots of exactly 128 elements,
+// slot s at x + s * pitch.  kTile: one scale for the whole item (a 128x128 tile);
+// otherwise one scale per slot (128 consecutive 1x128 blocks), written to scales[slot].
+template <bool kTile>
+__device__ __forceinline__ void quant_full_item(const uint16_t* __restrict__ x,
+                                                uint8_t* __restrict__ codes, int64_t pitch,
+                                                float* __restrict__ scales, unsigned* wave_max) {
+  const int tid = threadIdx.x;
+  const int64_t lane_off = int64_t(tid >> 4) * pitch + (tid & 15) * 8;
+  const int64_t step = int64_t(kQuantRowStep) * pitch;
+  u32x4 v[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) v[i] = ld16(x + lane_off + i * step);
+  unsigned m[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    unsigned a = abs_max_bits(0, v[i].x);
+    a = abs_max_bits(a, v[i].y);
+    a = abs_max_bits(a, v[i].z);
+    m[i] = abs_max_bits(a, v[i].w);
+  }
+  if (kTile) {
+    unsigned a = max(max(m[0], m[1]), max(m[2], m[3]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    __syncthreads();
+    a = wave_max[0];
+#pragma unroll
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
+    if (tid == 0) scales[0] = __uint_as_float(a << 16) / kE4M3Max;
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) m[i] = a;
+  } else {
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) {
+      unsigned a = m[i];
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+      m[i] = a;
+      if ((tid & 15) == 0) scales[(tid >> 4) + kQuantRowStep * i] = __uint_as_float(a << 16) / kE4M3Max;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    u32x2 c{0, 0};
+    if (m[i] != 0) {
+      const Divisor d = make_divisor(m[i]);
+      c.x = quant_pair(v[i].x, d) | (quant_pair(v[i].y, d) << 16);
+      c.y = quant_pair(v[i].z, d) | (quant_pair(v[i].w, d) << 16);
+    }
+    st8(codes + lane_off + i * step, c);
+  }
+}
+
 // -------------------------------------------------------------------------------------------
 // block_quant: amax per block (wavefront shuffles, LDS across the 8 waves of a tile),
 // scale = amax / 448, codes = E4M3(clamp(x / scale)) with the hardware RNE convert.
@@ -330,6 +388,26 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
   const int tid = threadIdx.x;
   const int r_in = tid >> 4, col0 = (tid & 15) * 8;
   const int64_t base = t.ell - elem_base;
+
+  // Full, 16-byte-structured items (nearly all of them) take the lean path: no per-slot
+  // bookkeeping, straight-line loads, one reduction, straight-line stores.
+  if (vec) {
+    if (tile) {
+      if ((it.first + 1) * 128 <= t.rows && int64_t(it.count + 1) * 128 <= t.cols) {
+        const int64_t off = base + it.first * 128 * t.cols + int64_t(it.count) * 128;
+        quant_full_item<true>(x + off, codes + off, t.cols,
+                              scales + (t.scale_base + it.first * t.nbc + it.count - scale_off),
+                              wave_max);
+        return;
+      }
+    } else if ((t.flags & kFlagContig) && it.count == kItemSlots &&
+               (it.first + kItemSlots) * 128 <= t.e) {
+      const int64_t off = base + it.first * 128;
+      quant_full_item<false>(x + off, codes + off, 128,
+                             scales + (t.scale_base + it.first - scale_off), wave_max);
+      return;
+    }
+  }
 
   Slot sl[kQuantLoads];
   u32x4 v[kQuantLoads];
@@ -429,11 +507,19 @@ __device__ __forceinline__ unsigned bf16_rne(float f) {
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+
 __device__ __forceinline__ void dequant4(unsigned word, float scale, unsigned& lo, unsigned& hi) {
   const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), false);  // bytes 0, 1
   const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), true);   // bytes 2, 3
-  lo = bf16_rne(a[0] * scale) | (bf16_rne(a[1] * scale) << 16);
-  hi = bf16_rne(b[0] * scale) | (bf16_rne(b[1] * scale) << 16);
+  lo = pack_bf16(a[0] * scale, a[1] * scale);
+  hi = pack_bf16(b[0] * scale, b[1] * scale);
 }
 
 // scale index (relative to the tensor) of the element at (row, col)
@@ -557,9 +643,14 @@ int launch_group_copy(bool unpack, const DeviceTables& dev, int n, void* const* 
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
                         float* out, int64_t S, int64_t gpr, int rank, int world, hipStream_t st) {
   if (gpr <= 0 || gpr > 0x7fffffffLL) return RS_EOVERFLOW;
-  shard_reduce_kernel<<<dim3(unsigned(gpr)), dim3(kThreads), 0, st>>>(
-      dev.tensors, n, dev.gran_first, static_cast<const uint16_t*>(partials), row_stride, out, S,
-      gpr, rank, world, 1.0f / float(world));
+  const float inv_w = 1.0f / float(world);
+  const uint16_t* P = static_cast<const uint16_t*>(partials);
+  if (gpr >= 4096)
+    shard_reduce_kernel<512><<<dim3(unsigned((gpr + 1) / 2)), dim3(512), 0, st>>>(
+        dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w);
+  else
+    shard_reduce_kernel<256><<<dim3(unsigned(gpr)), dim3(256), 0, st>>>(
+        dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w);
   return launched();
 }
 

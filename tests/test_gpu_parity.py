@@ -345,3 +345,17 @@ def test_device_argument_errors():
     finally:
         u.close()
         w.close()
+
+
+def test_reduce_long_region_two_granule_workgroups():
+    """Regions of 4096 granules or more are reduced by 512-lane workgroups that take two granules
+    each; check that path element by element, ragged tail and padding included."""
+    W = 3
+    u = Unit([(9_000_001, 0, MODE_1x128), (700, 136, MODE_128x128), (16_500_000, 0, MODE_1x128)], W)
+    try:
+        assert -(-u.S // 2048) >= 4096
+        for rank in range(W):
+            parts = np.stack([normal_bf16(15, rank, 1, w, u.S, 1e-3) for w in range(W)])
+            check_reduce(u, rank, parts, f"long region rank {rank}")
+    finally:
+        u.close()
