@@ -46,7 +46,7 @@ void free_device_tables(rs::DeviceTables* d) {
   if (d->gran_first) (void)hipFree(d->gran_first);
   if (d->items) (void)hipFree(d->items);
   if (d->payload_gran) (void)hipFree(d->payload_gran);
-  if (d->payload_win) (void)hipFree(d->payload_win);
+  if (d->padding_gran) (void)hipFree(d->padding_gran);
   if (have && cur != d->device) (void)hipSetDevice(cur);
   *d = rs::DeviceTables{};
 }
@@ -214,8 +214,8 @@ int rs_plan_rank_segments(const rs_plan* plan, int rank, rs_segment* out, int ca
 int rs_plan_upload(rs_plan* plan, int device) {
   if (!plan || device < 0) return RS_EINVAL;
   if (plan->S % 8 != 0) return RS_EUNSUPPORTED;  // bf16 rank regions must start 16-byte aligned
-  // granule / window ids are 32-bit on the device
-  if ((plan->S + rs::kGranule - 1) / rs::kGranule > 0x7fffffffLL / plan->world) return RS_EOVERFLOW;
+  // granule ids are 32-bit on the device and a granule is served by four workgroups
+  if ((plan->S + rs::kGranule - 1) / rs::kGranule > (0x7fffffffLL / 4) / plan->world) return RS_EOVERFLOW;
   if (plan->dev.device >= 0) return plan->dev.device == device ? RS_OK : RS_EINVAL;
   int cur = -1;
   if (hipGetDevice(&cur) != hipSuccess) return RS_EHIP;
@@ -229,7 +229,7 @@ int rs_plan_upload(rs_plan* plan, int device) {
     if (rc == RS_OK) rc = upload(plan->host.gran_first, &d.gran_first);
     if (rc == RS_OK) rc = upload(plan->host.items, &d.items);
     if (rc == RS_OK) rc = upload(plan->host.payload_gran, &d.payload_gran);
-    if (rc == RS_OK) rc = upload(plan->host.payload_win, &d.payload_win);
+    if (rc == RS_OK) rc = upload(plan->host.padding_gran, &d.padding_gran);
     if (rc == RS_OK) {
       plan->dev = d;
     } else {
@@ -239,7 +239,7 @@ int rs_plan_upload(rs_plan* plan, int device) {
     std::vector<int32_t>().swap(plan->host.gran_first);
     std::vector<rs::Item>().swap(plan->host.items);
     std::vector<int32_t>().swap(plan->host.payload_gran);
-    std::vector<int32_t>().swap(plan->host.payload_win);
+    std::vector<int32_t>().swap(plan->host.padding_gran);
   } catch (const std::bad_alloc&) {
     rc = RS_ENOMEM;
   }
@@ -289,8 +289,8 @@ int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* s
   if (!dbuf) return RS_EINVAL;
   if (!aligned16(dbuf)) return RS_EALIGN;
   return rs::launch_group_copy(false, plan->dev, int(plan->t.size()), src->ptrs, dbuf, plan->S,
-                               plan->host.granules_per_rank, plan->world,
-                               plan->host.n_payload_gran, static_cast<hipStream_t>(stream));
+                               plan->host.granules_per_rank, plan->host.n_payload_gran,
+                               plan->host.n_padding_gran, static_cast<hipStream_t>(stream));
 }
 
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream) {
@@ -301,8 +301,7 @@ int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table*
   if (!aligned16(dbuf)) return RS_EALIGN;
   return rs::launch_group_copy(true, plan->dev, int(plan->t.size()), dst->ptrs,
                                const_cast<void*>(dbuf), plan->S, plan->host.granules_per_rank,
-                               plan->world, plan->host.n_payload_gran,
-                               static_cast<hipStream_t>(stream));
+                               plan->host.n_payload_gran, 0, static_cast<hipStream_t>(stream));
 }
 
 int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride, float* out,
@@ -344,9 +343,9 @@ int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
   if (!plan->all_quant) return RS_EUNSUPPORTED;
   if (!codes || !scales) return RS_EINVAL;
   if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3)) return RS_EALIGN;
-  return rs::launch_dequant_unpack(plan->dev, int(plan->t.size()), plan->host.n_payload_win, codes,
+  return rs::launch_dequant_unpack(plan->dev, int(plan->t.size()), plan->host.n_payload_gran, codes,
                                    scales, dst->ptrs, plan->S, plan->host.granules_per_rank,
-                                   plan->host.windows_per_rank, static_cast<hipStream_t>(stream));
+                                   static_cast<hipStream_t>(stream));
 }
 
 int rs_copy_probe(void* dst, const void* src, int64_t bytes, void* stream) {

@@ -1,7 +1,8 @@
 // HIP kernels for gfx950 (CDNA4, wave64): the four HBM-bound movers of the DBuffer hot path.
 //
-// Common shape: 256-thread workgroups, one 16-byte vector per lane per access, a very large
-// grid (a plain copy on MI355X is fastest that way: one vector per lane, no grid-stride loop),
+// Common shape: one 16-byte vector per lane per access and a very large grid (a plain copy on
+// MI355X is fastest that way: no grid-stride loop, no multi-vector tiles), single-wavefront
+// workgroups for the pure streaming kernels (measured 3-4 % faster than 256 lanes),
 // non-temporal loads/stores since nothing is reused, and one scalar table lookup per
 // workgroup to find its tensor.  No MFMA: nothing here is a contraction.
 #include <hip/hip_runtime.h>
@@ -32,20 +33,38 @@ __device__ __forceinline__ void st8(void* p, u32x2 v) {
 
 // -------------------------------------------------------------------------------------------
 // ragged_pack / unpack_bf16: group copy between per-tensor storage and the DBuffer.
-// One workgroup per granule of kGranule buffer elements of one rank region.
+// Four single-wavefront workgroups per granule (kGranule buffer elements of one rank region)
+// that holds payload; ragged_pack adds one workgroup per pure-padding granule to zero it.
 // -------------------------------------------------------------------------------------------
+constexpr int kCopyThreads = 64;
+constexpr int kCopyParts = kGranule / (kCopyThreads * 8);  // workgroups per granule: 4
+
 template <bool kUnpack>
-__global__ __launch_bounds__(kThreads) void group_copy_kernel(
+__global__ __launch_bounds__(kCopyThreads) void group_copy_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
-    const int32_t* __restrict__ granules, void* const* __restrict__ ptrs,
-    uint16_t* __restrict__ dbuf, int64_t S, int64_t gpr) {
-  // pack visits every granule (padding must be zeroed); unpack only those that hold payload
-  const int64_t bid = kUnpack ? int64_t(granules[blockIdx.x]) : int64_t(blockIdx.x);
+    const int32_t* __restrict__ granules, const int32_t* __restrict__ padding,
+    unsigned n_copy_groups, void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S,
+    int64_t gpr) {
+  if (!kUnpack && blockIdx.x >= n_copy_groups) {
+    // a granule of nothing but padding: this wavefront zeroes all of it
+    const int64_t gid = padding[blockIdx.x - n_copy_groups];
+    const int64_t k = gid / gpr;
+    const int64_t i0 = (gid - k * gpr) * kGranule;
+    const int len = int(min(int64_t(kGranule), S - i0));
+#pragma unroll
+    for (int h = 0; h < kCopyParts; ++h) {
+      const int lo = (h * kCopyThreads + int(threadIdx.x)) * 8;
+      if (lo < len) st16(dbuf + k * S + i0 + lo, u32x4{0, 0, 0, 0});
+    }
+    return;
+  }
+  const unsigned slot = blockIdx.x / kCopyParts, part = blockIdx.x % kCopyParts;
+  const int64_t bid = granules[slot];
   const int64_t k = bid / gpr;
   const int64_t i0 = (bid - k * gpr) * kGranule;
   const int64_t d0 = k * S + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
-  const int lane_off = threadIdx.x * 8;
+  const int lane_off = (int(part) * kCopyThreads + int(threadIdx.x)) * 8;
   if (lane_off >= len) return;
   const int64_t d = d0 + lane_off;
   const int t0 = gran_first[bid];
@@ -498,9 +517,9 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
 
 // -------------------------------------------------------------------------------------------
 // dequant_unpack: codes of the gathered unit -> per-tensor bf16, value(code) * scale then RNE.
-// Buffer-driven like ragged_pack: one workgroup per window of kWindowGranules granules (8192
-// codes) that holds payload; a lane converts 8 codes (one 8-byte load, one 16-byte store) in
-// each of the window's granules.  No block-wide step is needed, only the block's scale.
+// Buffer-driven like ragged_pack: one single-wavefront workgroup per granule that holds
+// payload; a lane converts 8 codes (one 8-byte load, one 16-byte store) in each quarter of the
+// granule.  No block-wide step is needed, only the block's scale.
 // -------------------------------------------------------------------------------------------
 __device__ __forceinline__ unsigned bf16_rne(float f) {
   const unsigned u = __float_as_uint(f);
@@ -527,19 +546,20 @@ __device__ __forceinline__ int64_t scale_index(const TensorDev& t, int64_t row, 
   return ((t.flags & kFlagTile) ? (row >> 7) : row) * t.nbc + (col >> 7);
 }
 
-__global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
+constexpr int kDequantThreads = 64;
+constexpr int kDequantParts = kGranule / (kDequantThreads * 8);  // 8-code groups per lane: 4
+constexpr int kDequantStep = kDequantThreads * 8;                // 512 codes per access
+
+__global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
-    const int32_t* __restrict__ windows, const uint8_t* __restrict__ codes,
-    const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr,
-    int64_t wpr) {
-  constexpr int kWin = kWindowGranules * kGranule;
-  const int64_t wid = windows[blockIdx.x];
-  const int64_t k = wid / wpr;
-  const int64_t j = wid - k * wpr;
-  const int64_t i0 = j * kWin;
+    const int32_t* __restrict__ granules, const uint8_t* __restrict__ codes,
+    const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr) {
+  const int64_t gid = granules[blockIdx.x];
+  const int64_t k = gid / gpr;
+  const int64_t i0 = (gid - k * gpr) * kGranule;
   const int64_t d0 = k * S + i0;
-  const int len = int(min(int64_t(kWin), S - i0));
-  const int t0 = gran_first[k * gpr + j * kWindowGranules];  // a payload window: t0 < n
+  const int len = int(min(int64_t(kGranule), S - i0));
+  const int t0 = gran_first[gid];  // a payload granule: t0 < n
   const int lane = threadIdx.x * 8;
 
   {
@@ -548,8 +568,8 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
     const bool inside = t.ell <= d0 && d0 + len <= t.ell + t.e;
     if (inside && (t.flags & kFlagVec) && (reinterpret_cast<uintptr_t>(out) & 15) == 0 &&
         t.cols < (int64_t(1) << 30)) {
-      // The whole window lies in one tensor whose rows keep every 8-element group inside one
-      // row and one block.  (row, col) of the window's first element once per workgroup
+      // The whole granule lies in one tensor whose rows keep every 8-element group inside one
+      // row and one block.  (row, col) of the granule's first element once per workgroup
       // (exact: a double holds any element index below 2^53), then 32-bit steps per lane.
       const int64_t first = d0 - t.ell;
       int64_t row0 = int64_t(double(first) / double(t.cols));
@@ -558,12 +578,12 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
       if (col0 >= t.cols) { col0 -= t.cols; ++row0; }
       const unsigned C = unsigned(t.cols);
       const bool contig = (t.flags & kFlagContig) && !(t.flags & kFlagTile);
-      u32x2 c[kWindowGranules];
-      float sc[kWindowGranules];
-      bool on[kWindowGranules];
+      u32x2 c[kDequantParts];
+      float sc[kDequantParts];
+      bool on[kDequantParts];
 #pragma unroll
-      for (int h = 0; h < kWindowGranules; ++h) {
-        const int lo = h * kGranule + lane;
+      for (int h = 0; h < kDequantParts; ++h) {
+        const int lo = h * kDequantStep + lane;
         on[h] = lo < len;
         if (!on[h]) continue;
         c[h] = ld8(codes + d0 + lo);
@@ -578,22 +598,22 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
         sc[h] = scales[t.scale_base + sidx];
       }
 #pragma unroll
-      for (int h = 0; h < kWindowGranules; ++h) {
+      for (int h = 0; h < kDequantParts; ++h) {
         if (!on[h]) continue;
         unsigned o0, o1, o2, o3;
         dequant4(c[h].x, sc[h], o0, o1);
         dequant4(c[h].y, sc[h], o2, o3);
-        st16(out + first + h * kGranule + lane, u32x4{o0, o1, o2, o3});
+        st16(out + first + h * kDequantStep + lane, u32x4{o0, o1, o2, o3});
       }
       return;
     }
   }
 
-  // Window with tensor boundaries or padding, or a tensor without 16-byte structure:
+  // Granule with tensor boundaries or padding, or a tensor without 16-byte structure:
   // every element finds its tensor, row and column on its own.
   int s = t0;
-  for (int h = 0; h < kWindowGranules; ++h) {
-    const int lo = h * kGranule + lane;
+  for (int h = 0; h < kDequantParts; ++h) {
+    const int lo = h * kDequantStep + lane;
     if (lo >= len) break;
     for (int q = 0; q < 8; ++q) {
       const int64_t pos = d0 + lo + q;
@@ -613,9 +633,10 @@ __global__ __launch_bounds__(kThreads) void dequant_unpack_kernel(
 // -------------------------------------------------------------------------------------------
 // plain copy: the measured ceiling and the counter calibration launch
 // -------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void copy_probe_kernel(const u32x4* __restrict__ src,
-                                                             u32x4* __restrict__ dst, int64_t nvec) {
-  const int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+__global__ __launch_bounds__(kCopyThreads) void copy_probe_kernel(const u32x4* __restrict__ src,
+                                                                 u32x4* __restrict__ dst,
+                                                                 int64_t nvec) {
+  const int64_t i = int64_t(blockIdx.x) * kCopyThreads + threadIdx.x;
   if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
@@ -625,18 +646,21 @@ __global__ __launch_bounds__(kThreads) void copy_probe_kernel(const u32x4* __res
 static int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }
 
 int launch_group_copy(bool unpack, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf,
-                      int64_t S, int64_t gpr, int64_t world, int64_t n_payload_gran,
+                      int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
                       hipStream_t st) {
-  const int64_t grid = unpack ? n_payload_gran : world * gpr;
+  const int64_t copy_groups = n_payload_gran * kCopyParts;
+  const int64_t grid = copy_groups + (unpack ? 0 : n_padding_gran);
   if (grid == 0) return RS_OK;
   if (grid < 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  uint16_t* db = static_cast<uint16_t*>(dbuf);
   if (unpack)
-    group_copy_kernel<true><<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
-        dev.tensors, n, dev.gran_first, dev.payload_gran, ptrs, static_cast<uint16_t*>(dbuf), S,
-        gpr);
+    group_copy_kernel<true><<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(
+        dev.tensors, n, dev.gran_first, dev.payload_gran, nullptr, unsigned(copy_groups), ptrs, db,
+        S, gpr);
   else
-    group_copy_kernel<false><<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
-        dev.tensors, n, dev.gran_first, nullptr, ptrs, static_cast<uint16_t*>(dbuf), S, gpr);
+    group_copy_kernel<false><<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(
+        dev.tensors, n, dev.gran_first, dev.payload_gran, dev.padding_gran, unsigned(copy_groups),
+        ptrs, db, S, gpr);
   return launched();
 }
 
@@ -665,22 +689,22 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
   return launched();
 }
 
-int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_windows, const uint8_t* codes,
-                          const float* scales, void* const* ptrs, int64_t S, int64_t gpr,
-                          int64_t wpr, hipStream_t st) {
-  if (n_windows == 0) return RS_OK;
-  if (n_windows < 0 || n_windows > 0x7fffffffLL) return RS_EOVERFLOW;
-  dequant_unpack_kernel<<<dim3(unsigned(n_windows)), dim3(kThreads), 0, st>>>(
-      dev.tensors, n, dev.gran_first, dev.payload_win, codes, scales, ptrs, S, gpr, wpr);
+int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_payload_gran,
+                          const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
+                          int64_t gpr, hipStream_t st) {
+  if (n_payload_gran == 0) return RS_OK;
+  if (n_payload_gran < 0 || n_payload_gran > 0x7fffffffLL) return RS_EOVERFLOW;
+  dequant_unpack_kernel<<<dim3(unsigned(n_payload_gran)), dim3(kDequantThreads), 0, st>>>(
+      dev.tensors, n, dev.gran_first, dev.payload_gran, codes, scales, ptrs, S, gpr);
   return launched();
 }
 
 int launch_copy_probe(void* dst, const void* src, int64_t bytes, hipStream_t st) {
   const int64_t nvec = bytes / 16;
-  const int64_t grid = (nvec + kThreads - 1) / kThreads;
+  const int64_t grid = (nvec + kCopyThreads - 1) / kCopyThreads;
   if (grid == 0) return RS_OK;
   if (grid > 0x7fffffffLL) return RS_EOVERFLOW;
-  copy_probe_kernel<<<dim3(unsigned(grid)), dim3(kThreads), 0, st>>>(
+  copy_probe_kernel<<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(
       static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
   return launched();
 }

@@ -15,8 +15,6 @@ constexpr int kGranule = 2048;
 constexpr int kItemSlots = 128;
 // A zero-fill item clears at most this many code bytes.
 constexpr int kFillElems = 32768;
-// dequant_unpack walks the buffer in windows of this many granules (8192 codes per workgroup).
-constexpr int kWindowGranules = 4;
 
 enum : int32_t {
   kFlagTile = 1,     // 128x128 tiles (else 1x128 runs)
@@ -59,12 +57,11 @@ struct HostTables {
   int64_t granules_per_rank = 0;
   std::vector<Item> items;           // rank-major
   std::vector<int64_t> item_begin;   // world + 1
-  // granules / windows that hold at least one payload element (ids = rank * per_rank + index):
-  // the unpack kernels launch one workgroup per entry and never visit pure padding
+  // granules that hold at least one payload element (ids = rank * granules_per_rank + index):
+  // the unpack kernels launch workgroups for these only and never visit pure padding
   std::vector<int32_t> payload_gran;
-  std::vector<int32_t> payload_win;
-  int64_t windows_per_rank = 0;
-  int64_t n_payload_gran = 0, n_payload_win = 0;
+  std::vector<int32_t> padding_gran;   // the rest: granules ragged_pack only has to zero
+  int64_t n_payload_gran = 0, n_padding_gran = 0;
 };
 
 struct DeviceTables {
@@ -73,7 +70,7 @@ struct DeviceTables {
   int32_t* gran_first = nullptr;
   Item* items = nullptr;
   int32_t* payload_gran = nullptr;
-  int32_t* payload_win = nullptr;
+  int32_t* padding_gran = nullptr;
 };
 
 // ---- planner (planner.cpp) ----

@@ -57,24 +57,23 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
     }
   }
 
-  // payload lists: a granule holds payload iff its first not-yet-ended tensor starts inside it
-  const int64_t wpr = (gpr + kWindowGranules - 1) / kWindowGranules;
-  out->windows_per_rank = wpr;
+  // payload list: a granule holds payload iff its first not-yet-ended tensor starts before its end
   out->payload_gran.clear();
-  out->payload_win.clear();
+  out->padding_gran.clear();
   for (int64_t k = 0; k < world; ++k) {
     for (int64_t j = 0; j < gpr; ++j) {
       const int32_t f = out->gran_first[size_t(k * gpr + j)];
       const int64_t start = k * S + j * kGranule;
       const int64_t stop = std::min(start + kGranule, (k + 1) * S);
-      if (f >= n || t[f].ell >= stop) continue;
+      if (f >= n || t[f].ell >= stop) {
+        out->padding_gran.push_back(int32_t(k * gpr + j));
+        continue;
+      }
       out->payload_gran.push_back(int32_t(k * gpr + j));
-      const int32_t w = int32_t(k * wpr + j / kWindowGranules);
-      if (out->payload_win.empty() || out->payload_win.back() != w) out->payload_win.push_back(w);
     }
   }
   out->n_payload_gran = int64_t(out->payload_gran.size());
-  out->n_payload_win = int64_t(out->payload_win.size());
+  out->n_padding_gran = int64_t(out->padding_gran.size());
 
   // quantisation work items, rank by rank in buffer order, zero-fill items for every gap
   out->items.clear();
