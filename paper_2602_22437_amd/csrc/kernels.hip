@@ -31,6 +31,23 @@ __device__ __forceinline__ void st8(void* p, u32x2 v) {
   __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
 }
 
+// Workgroups are handed to the 8 XCDs round-robin by block index.  This turns the block index
+// into a work index such that each XCD takes runs of `chunk` consecutive work items (work that is
+// adjacent in memory then shares an XCD's L2 and DRAM pages).  The grid must be a multiple of
+// 8 * chunk; indices at or past the real count are skipped by the caller.
+constexpr int kXcdChunk = 16;  // measured best of 4..256 for block_quant and shard_reduce
+
+__device__ __forceinline__ int64_t xcd_chunked(int64_t block, int chunk) {
+  const int64_t x = block % 8, q = block / 8;
+  return ((q / chunk) * 8 + x) * chunk + q % chunk;
+}
+
+// grid size for `count` work items under xcd_chunked(.., kXcdChunk)
+static inline int64_t xcd_grid(int64_t count) {
+  const int64_t unit = 8 * kXcdChunk;
+  return (count + unit - 1) / unit * unit;
+}
+
 // -------------------------------------------------------------------------------------------
 // ragged_pack / unpack_bf16: group copy between per-tensor storage and the DBuffer.
 // Four single-wavefront workgroups per granule (kGranule buffer elements of one rank region)
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
     int64_t gpr, int rank, int W, float inv_w) {
   // with 512 lanes, waves 0-3 take the even granule of the pair, waves 4-7 the odd one
   const int half = __builtin_amdgcn_readfirstlane(int(threadIdx.x) / kThreads);  // wave-uniform
-  const int64_t j = int64_t(blockIdx.x) * (kReduceThreads / kThreads) + half;
+  const int64_t j = xcd_chunked(blockIdx.x, kXcdChunk) * (kReduceThreads / kThreads) + half;
   if (j >= gpr) return;
   const int64_t i0 = j * kGranule;
   const int64_t d0 = int64_t(rank) * S + i0;
@@ -394,9 +411,12 @@ __device__ __forceinline__ void quant_full_item(const uint16_t* __restrict__ x,
 __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
     const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
     const uint16_t* __restrict__ x, uint8_t* __restrict__ codes, float* __restrict__ scales,
-    int64_t elem_base, int64_t scale_off) {
+    int64_t elem_base, int64_t scale_off, int64_t item_count) {
   __shared__ unsigned wave_max[kQuantThreads / 64];
-  const Item it = items[item_off + blockIdx.x];
+  // adjacent tiles of a row of tiles share DRAM pages and cache lines: keep them on one XCD
+  const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
+  if (idx >= item_count) return;
+  const Item it = items[item_off + idx];
   if (it.tensor < 0) {
     zero_fill_bytes(codes + (it.first - elem_base), it.count, kQuantThreads);
     return;
@@ -670,10 +690,10 @@ int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, in
   const float inv_w = 1.0f / float(world);
   const uint16_t* P = static_cast<const uint16_t*>(partials);
   if (gpr >= 4096)
-    shard_reduce_kernel<512><<<dim3(unsigned((gpr + 1) / 2)), dim3(512), 0, st>>>(
+    shard_reduce_kernel<512><<<dim3(unsigned(xcd_grid((gpr + 1) / 2))), dim3(512), 0, st>>>(
         dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w);
   else
-    shard_reduce_kernel<256><<<dim3(unsigned(gpr)), dim3(256), 0, st>>>(
+    shard_reduce_kernel<256><<<dim3(unsigned(xcd_grid(gpr))), dim3(256), 0, st>>>(
         dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w);
   return launched();
 }
@@ -683,9 +703,9 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
                        hipStream_t st) {
   if (item_count == 0) return RS_OK;
   if (item_count < 0 || item_count > 0x7fffffffLL) return RS_EOVERFLOW;
-  block_quant_kernel<<<dim3(unsigned(item_count)), dim3(kQuantThreads), 0, st>>>(
+  block_quant_kernel<<<dim3(unsigned(xcd_grid(item_count))), dim3(kQuantThreads), 0, st>>>(
       dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, elem_base,
-      scale_off);
+      scale_off, item_count);
   return launched();
 }
 
