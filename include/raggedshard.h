@@ -70,6 +70,7 @@ typedef struct rs_segment {
 
 typedef struct rs_plan rs_plan;                  /* layout plan + device tables, library-owned */
 typedef struct rs_tensor_table rs_tensor_table;  /* device copy of n tensor base pointers */
+typedef struct rs_shard_batch rs_shard_batch;    /* device copy of the buffers of `count` units' shards */
 
 int rs_version(void);
 const char* rs_strerror(int code);
@@ -150,6 +151,18 @@ int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_s
  * holds a tensor without FP8 blocks. */
 int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes, float* scales,
                 void* stream);
+
+/* The same operation for rank `rank`'s shard of `count` units that share this plan (the
+ * transformer layers of a model), fused into one launch as the DBuffer fuses identical
+ * kernels across a group (Section 5): one shard of one unit is too small to fill the GPU.
+ * shards / codes / scales: host arrays of `count` device pointers with rs_quantize's meaning
+ * and alignment for that rank; they are uploaded once and may be reused by any number of calls.
+ * count <= 65535.  rs_quantize_batch == rs_quantize(plan, rank, shards[u], codes[u], scales[u])
+ * for every u, bit for bit. */
+int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* const* shards,
+                          uint8_t* const* codes, float* const* scales, rs_shard_batch** out);
+void rs_shard_batch_destroy(rs_shard_batch* batch);
+int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* stream);
 
 /* ---- dequant_unpack: gathered FP8 unit -> per-parameter bf16 --------------------------------
  * dst_t[i] = bf16_rne( value(codes[l_t + i]) * scales[block of i] ).

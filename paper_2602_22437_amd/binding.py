@@ -20,7 +20,8 @@ EXPORTS = [
     "rs_plan_payload_elems", "rs_plan_padding_elems", "rs_plan_num_scales", "rs_plan_offsets",
     "rs_plan_scale_bases", "rs_plan_scale_range", "rs_plan_rank_segments", "rs_plan_upload",
     "rs_tensor_table_create", "rs_tensor_table_destroy", "rs_pack", "rs_unpack_bf16", "rs_reduce",
-    "rs_quantize", "rs_unpack", "rs_copy_probe",
+    "rs_quantize", "rs_unpack", "rs_copy_probe", "rs_shard_batch_create", "rs_shard_batch_destroy",
+    "rs_quantize_batch",
 ]
 
 
@@ -75,6 +76,11 @@ _lib.rs_unpack_bf16.argtypes = [_P, _P, _P, _P]
 _lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
+_lib.rs_shard_batch_create.argtypes = [_P, C.c_int, C.c_int, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P),
+                                       C.POINTER(_P)]
+_lib.rs_shard_batch_destroy.argtypes = [_P]
+_lib.rs_shard_batch_destroy.restype = None
+_lib.rs_quantize_batch.argtypes = [_P, _P, _P]
 _lib.rs_copy_probe.argtypes = [_P, _P, C.c_int64, _P]
 
 
@@ -229,6 +235,31 @@ def rs_reduce(plan, rank: int, partials, row_stride: int, out, stream=None) -> N
 def rs_quantize(plan, rank: int, shard, codes, scales, stream=None) -> None:
     _check(_lib.rs_quantize(plan, int(rank), _ptr(shard), _ptr(codes), _ptr(scales), _stream(stream)),
            "rs_quantize")
+
+
+def rs_shard_batch_create(plan, rank: int, shards: Sequence, codes: Sequence, scales: Sequence) -> int:
+    """shards / codes / scales: one device tensor (or address) per unit, as rs_quantize takes them."""
+    n = len(shards)
+    if not (len(codes) == len(scales) == n):
+        raise ValueError("one shard, code buffer and scale slice per unit")
+    arrs = []
+    for seq in (shards, codes, scales):
+        a = (_P * max(1, n))()
+        for i, t in enumerate(seq):
+            a[i] = _ptr(t)
+        arrs.append(a)
+    out = _P()
+    _check(_lib.rs_shard_batch_create(plan, int(rank), n, arrs[0], arrs[1], arrs[2], C.byref(out)),
+           "rs_shard_batch_create")
+    return out.value
+
+
+def rs_shard_batch_destroy(batch) -> None:
+    _lib.rs_shard_batch_destroy(batch)
+
+
+def rs_quantize_batch(plan, batch, stream=None) -> None:
+    _check(_lib.rs_quantize_batch(plan, batch, _stream(stream)), "rs_quantize_batch")
 
 
 def rs_unpack(plan, codes, scales, dst_table, stream=None) -> None:

@@ -331,7 +331,63 @@ int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes
     elem_base = int64_t(rank) * plan->S;
     scale_off = plan->scale_begin[size_t(rank)];
   }
-  return rs::launch_block_quant(plan->dev, first, count, shard, codes, scales, elem_base, scale_off,
+  return rs::launch_block_quant(plan->dev, first, count, shard, codes, scales, nullptr, 0, elem_base,
+                                scale_off, static_cast<hipStream_t>(stream));
+}
+
+int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* const* shards,
+                          uint8_t* const* codes, float* const* scales, rs_shard_batch** out) {
+  if (!out) return RS_EINVAL;
+  *out = nullptr;
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_quant) return RS_EUNSUPPORTED;
+  if (!shards || !codes || !scales || count <= 0 || count > 65535 || rank < 0 || rank >= plan->world)
+    return RS_EINVAL;
+  const bool has_scales = plan->scale_begin[size_t(rank) + 1] > plan->scale_begin[size_t(rank)];
+  std::vector<void*> host(size_t(count) * 3);
+  for (int u = 0; u < count; ++u) {
+    if (!shards[u] || !codes[u] || (!scales[u] && has_scales)) return RS_EINVAL;
+    if (!aligned16(shards[u]) || !aligned16(codes[u]) || (reinterpret_cast<uintptr_t>(scales[u]) & 3))
+      return RS_EALIGN;
+    host[size_t(u)] = const_cast<void*>(shards[u]);
+    host[size_t(count) + u] = codes[u];
+    host[size_t(count) * 2 + u] = scales[u];
+  }
+  rs_shard_batch* b = new (std::nothrow) rs_shard_batch();
+  if (!b) return RS_ENOMEM;
+  b->owner = plan;
+  b->rank = rank;
+  b->count = count;
+  const size_t bytes = host.size() * sizeof(void*);
+  if (hipMalloc(reinterpret_cast<void**>(&b->ptrs), bytes) != hipSuccess) {
+    delete b;
+    return RS_ENOMEM;
+  }
+  if (hipMemcpy(b->ptrs, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(b->ptrs);
+    delete b;
+    return RS_EHIP;
+  }
+  *out = b;
+  return RS_OK;
+}
+
+void rs_shard_batch_destroy(rs_shard_batch* batch) {
+  if (!batch) return;
+  if (batch->ptrs) (void)hipFree(batch->ptrs);
+  delete batch;
+}
+
+int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!batch || batch->owner != plan || !batch->ptrs) return RS_EINVAL;
+  const std::vector<int64_t>& ib = plan->host.item_begin;
+  const int64_t first = ib[size_t(batch->rank)];
+  return rs::launch_block_quant(plan->dev, first, ib[size_t(batch->rank) + 1] - first, nullptr,
+                                nullptr, nullptr, batch->ptrs, batch->count,
+                                int64_t(batch->rank) * plan->S, plan->scale_begin[size_t(batch->rank)],
                                 static_cast<hipStream_t>(stream));
 }
 

@@ -410,9 +410,19 @@ __device__ __forceinline__ void quant_full_item(const uint16_t* __restrict__ x,
 // -------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
     const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
-    const uint16_t* __restrict__ x, uint8_t* __restrict__ codes, float* __restrict__ scales,
+    const uint16_t* __restrict__ x_one, uint8_t* __restrict__ codes_one,
+    float* __restrict__ scales_one, void* const* __restrict__ batch, int batch_count,
     int64_t elem_base, int64_t scale_off, int64_t item_count) {
   __shared__ unsigned wave_max[kQuantThreads / 64];
+  // batched launch: blockIdx.y picks the unit; batch = [shards | codes | scales] pointers
+  const uint16_t* __restrict__ x = x_one;
+  uint8_t* __restrict__ codes = codes_one;
+  float* __restrict__ scales = scales_one;
+  if (batch) {
+    x = static_cast<const uint16_t*>(batch[blockIdx.y]);
+    codes = static_cast<uint8_t*>(batch[batch_count + blockIdx.y]);
+    scales = static_cast<float*>(batch[2 * batch_count + blockIdx.y]);
+  }
   // adjacent tiles of a row of tiles share DRAM pages and cache lines: keep them on one XCD
   const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
   if (idx >= item_count) return;
@@ -699,13 +709,15 @@ int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, in
 }
 
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
-                       uint8_t* codes, float* scales, int64_t elem_base, int64_t scale_off,
-                       hipStream_t st) {
-  if (item_count == 0) return RS_OK;
-  if (item_count < 0 || item_count > 0x7fffffffLL) return RS_EOVERFLOW;
-  block_quant_kernel<<<dim3(unsigned(xcd_grid(item_count))), dim3(kQuantThreads), 0, st>>>(
-      dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, elem_base,
-      scale_off, item_count);
+                       uint8_t* codes, float* scales, void* const* batch, int batch_count,
+                       int64_t elem_base, int64_t scale_off, hipStream_t st) {
+  if (item_count == 0 || (batch && batch_count == 0)) return RS_OK;
+  if (item_count < 0 || item_count > 0x7fffffffLL || batch_count < 0 || batch_count > 65535)
+    return RS_EOVERFLOW;
+  const dim3 grid(unsigned(xcd_grid(item_count)), batch ? unsigned(batch_count) : 1u);
+  block_quant_kernel<<<grid, dim3(kQuantThreads), 0, st>>>(
+      dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, batch,
+      batch_count, elem_base, scale_off, item_count);
   return launched();
 }
 

@@ -102,3 +102,10 @@ struct rs_tensor_table {
   int n = 0;
   void** ptrs = nullptr;  // device array of n pointers
 };
+
+struct rs_shard_batch {
+  const rs_plan* owner = nullptr;
+  int rank = 0;
+  int count = 0;
+  void** ptrs = nullptr;  // device array: count shards, count code buffers, count scale slices
+};

@@ -359,3 +359,36 @@ def test_reduce_long_region_two_granule_workgroups():
             check_reduce(u, rank, parts, f"long region rank {rank}")
     finally:
         u.close()
+
+
+def test_quantize_batch_equals_per_unit_quantize():
+    """rs_quantize_batch over several units that share a plan: every unit's codes and scales
+    equal the oracle's shard quantisation bit for bit (and hence rs_quantize's)."""
+    tensors = [(300, 384, MODE_128x128), (1000, 0, MODE_1x128), (257, 130, MODE_128x128), (64, 256, MODE_1x128)]
+    u = Unit(tensors, 3)
+    try:
+        n_units = 5
+        for rank in range(3):
+            lo, hi = u.oracle.scale_range(rank)
+            dbs, shards, codes, scales = [], [], [], []
+            for unit in range(n_units):
+                params = [normal_bf16(16, unit, 0, i, s.e, 0.02 * (unit + 1)) for i, s in enumerate(u.specs)]
+                db = OD.ragged_pack(params, u.oracle.offsets, u.total)
+                dbs.append(db)
+                shards.append(to_dev_bf16(db[rank * u.S:(rank + 1) * u.S].copy()))
+                codes.append(torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda"))
+                scales.append(torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda"))
+            say(f"quantize_batch rank {rank}: {n_units} units")
+            batch = B.rs_shard_batch_create(u.plan, rank, shards, codes, scales)
+            B.rs_quantize_batch(u.plan, batch)
+            torch.cuda.synchronize()
+            B.rs_shard_batch_destroy(batch)
+            for unit in range(n_units):
+                oc, os_ = OF.block_quant_shard(u.oracle, rank, dbs[unit][rank * u.S:(rank + 1) * u.S])
+                assert np.array_equal(codes[unit].cpu().numpy(), oc), f"unit {unit} codes"
+                assert np.array_equal(scales[unit].cpu().numpy()[:hi - lo].view(np.uint32), os_.view(np.uint32))
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_shard_batch_create(u.plan, 3, shards, codes, scales)
+        assert e.value.code == B.RS_EINVAL
+    finally:
+        u.close()
