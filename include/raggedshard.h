@@ -50,6 +50,15 @@ enum {
   RS_BLOCK_EXPLICIT = 3  /* g = g_explicit elements; no FP8 */
 };
 
+/* Tensor orders tried by the planner (Section 5, "heuristic-guided solution": default order,
+ * sorted by sharding block size, sorted by tensor shape; the paper adopts the default). */
+enum {
+  RS_ORDER_DEFAULT = 0,     /* the order of the descriptor array */
+  RS_ORDER_BLOCK_SIZE = 1,  /* stable sort by g_t, ascending */
+  RS_ORDER_SHAPE = 2,       /* stable sort by (element count, rows, cols), ascending */
+  RS_ORDER_BEST = 3         /* all three; the smallest S wins, the earlier order on ties */
+};
+
 typedef struct rs_tensor_desc {
   int64_t rows;        /* R, or the length n of a 1-D tensor */
   int64_t cols;        /* C; 0 marks a 1-D tensor */
@@ -90,6 +99,10 @@ const char* rs_strerror(int code);
  * rs_plan_destroy.  Errors: RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM. */
 int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_bytes,
                    int min_itemsize, int tensor_align_elems, rs_plan** out);
+/* The same with a choice of tensor order (RS_ORDER_*).  Tensors keep the caller's indices in
+ * every query and pointer table; only their positions in the buffer change. */
+int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                           int min_itemsize, int tensor_align_elems, int order, rs_plan** out);
 void rs_plan_destroy(rs_plan* plan);
 
 /* CheckValidShard(S) of Algorithm 1 on its own: 1 feasible, 0 infeasible, <0 error.
@@ -105,6 +118,8 @@ int64_t rs_plan_total_elems(const rs_plan* plan);    /* world * S */
 int64_t rs_plan_payload_elems(const rs_plan* plan);  /* sum of e_t */
 int64_t rs_plan_padding_elems(const rs_plan* plan);  /* world * S - payload */
 int64_t rs_plan_num_scales(const rs_plan* plan);     /* FP8 blocks of the whole unit */
+/* Buffer order: out[j] = index of the j-th tensor in the buffer; cap must be >= n. */
+int rs_plan_order(const rs_plan* plan, int32_t* out, int cap);
 /* l_t for every tensor; cap must be >= n. */
 int rs_plan_offsets(const rs_plan* plan, int64_t* out, int cap);
 /* first scale index of every tensor plus the total (n + 1 values; cap >= n + 1).  Scales form

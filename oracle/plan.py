@@ -278,7 +278,11 @@ class Plan:
     g_coll: int
     A: int
     S: int = 0
-    offsets: List[int] = field(default_factory=list)
+    offsets: List[int] = field(default_factory=list)   # l_t, indexed like specs
+    perm: List[int] = field(default_factory=list)      # buffer order: perm[j] = index of the j-th tensor
+
+    def buffer_order(self) -> List[int]:
+        return self.perm if self.perm else list(range(len(self.specs)))
 
     @property
     def total(self) -> int:
@@ -298,7 +302,8 @@ class Plan:
         offset dst_off of rank k's region."""
         lo, hi = k * self.S, (k + 1) * self.S
         out = []
-        for t, (s, l) in enumerate(zip(self.specs, self.offsets)):
+        for t in self.buffer_order():
+            s, l = self.specs[t], self.offsets[t]
             a, b = max(l, lo), min(l + s.e, hi)
             if a < b:
                 out.append((t, a - l, a - lo, b - a))
@@ -306,11 +311,13 @@ class Plan:
 
     # --- scale layout: one flat fp32 array, tensor-major, block-row, block-column
     def scale_bases(self) -> List[int]:
-        out, acc = [], 0
-        for s in self.specs:
-            out.append(acc)
-            acc += s.num_blocks
-        out.append(acc)
+        """First scale of every tensor (indexed like specs) and, last, the total.  The scale
+        array follows the buffer: tensors in buffer order."""
+        out, acc = [0] * (len(self.specs) + 1), 0
+        for t in self.buffer_order():
+            out[t] = acc
+            acc += self.specs[t].num_blocks
+        out[-1] = acc
         return out
 
     def scale_range(self, k: int) -> Tuple[int, int]:
@@ -327,18 +334,46 @@ class Plan:
         return before(k * self.S), before((k + 1) * self.S)
 
 
+ORDER_DEFAULT = 0      # the order the caller lists the tensors in (the one the paper adopts)
+ORDER_BLOCK_SIZE = 1   # stable sort by sharding block size g_t, ascending
+ORDER_SHAPE = 2        # stable sort by shape: (element count, rows, cols) ascending
+ORDER_BEST = 3         # the three above in turn; smallest S* wins, earlier heuristic on ties
+
+
+def tensor_order(specs: Sequence[TensorSpec], order: int) -> List[int]:
+    """The three tensor orders of Section 5 ("heuristic-guided solution").  The paper names
+    them without fixing directions or tie-breaks; this is the reading taken."""
+    idx = list(range(len(specs)))
+    if order == ORDER_DEFAULT:
+        return idx
+    if order == ORDER_BLOCK_SIZE:
+        return sorted(idx, key=lambda t: specs[t].g)                      # sorted() is stable
+    if order == ORDER_SHAPE:
+        return sorted(idx, key=lambda t: (specs[t].e, specs[t].rows, specs[t].cols))
+    raise ValueError("unknown tensor order")
+
+
 def make_plan(specs: Sequence[TensorSpec], m: int, align_bytes: int = 16, min_itemsize: int = 1,
-              tensor_align: Optional[int] = None, start: StartFn = smallest_start) -> Plan:
+              tensor_align: Optional[int] = None, start: StartFn = smallest_start,
+              order: int = ORDER_DEFAULT) -> Plan:
     """plan(): S* by Algorithm 1, then the canonical (earliest-start) layout at S*."""
     if align_bytes % min_itemsize != 0:
         raise ValueError("alignment must be a multiple of the item size")
     g_coll = align_bytes // min_itemsize
     A = g_coll if tensor_align is None else tensor_align
-    tensors = [(s.e, s.g) for s in specs]
+    if order == ORDER_BEST:
+        plans = [make_plan(specs, m, align_bytes, min_itemsize, tensor_align, start, o)
+                 for o in (ORDER_DEFAULT, ORDER_BLOCK_SIZE, ORDER_SHAPE)]
+        return min(plans, key=lambda p: p.S)                              # min() keeps the first of equals
+    perm = tensor_order(specs, order)
+    tensors = [(specs[t].e, specs[t].g) for t in perm]
     S = plan_shard_size(tensors, m, g_coll, A, start)
-    offsets = greedy_layout(tensors, S, A, start)
-    assert offsets is not None and offsets[-1] + tensors[-1][0] <= m * S
-    return Plan(list(specs), m, g_coll, A, S, offsets)
+    placed = greedy_layout(tensors, S, A, start)
+    assert placed is not None and placed[-1] + tensors[-1][0] <= m * S
+    offsets = [0] * len(specs)
+    for j, t in enumerate(perm):
+        offsets[t] = placed[j]
+    return Plan(list(specs), m, g_coll, A, S, offsets, perm)
 
 
 # --------------------------------------------------------------------------------------

@@ -11,6 +11,7 @@ from typing import List, Sequence, Tuple
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libraggedshard.so")
 
 RS_BLOCK_1x128, RS_BLOCK_128x128, RS_BLOCK_WHOLE, RS_BLOCK_EXPLICIT = 0, 1, 2, 3
+RS_ORDER_DEFAULT, RS_ORDER_BLOCK_SIZE, RS_ORDER_SHAPE, RS_ORDER_BEST = 0, 1, 2, 3
 RS_OK, RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM, RS_EALIGN, RS_EUNSUPPORTED, RS_EHIP, RS_ENOTUPLOADED = (
     0, -1, -2, -3, -4, -5, -6, -7)
 
@@ -21,7 +22,7 @@ EXPORTS = [
     "rs_plan_scale_bases", "rs_plan_scale_range", "rs_plan_rank_segments", "rs_plan_upload",
     "rs_tensor_table_create", "rs_tensor_table_destroy", "rs_pack", "rs_unpack_bf16", "rs_reduce",
     "rs_quantize", "rs_unpack", "rs_copy_probe", "rs_shard_batch_create", "rs_shard_batch_destroy",
-    "rs_quantize_batch",
+    "rs_quantize_batch", "rs_plan_create_ordered", "rs_plan_order",
 ]
 
 
@@ -52,6 +53,9 @@ _lib.rs_strerror.restype = C.c_char_p
 _lib.rs_strerror.argtypes = [C.c_int]
 _lib.rs_plan_create.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                 C.POINTER(_P)]
+_lib.rs_plan_create_ordered.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int,
+                                        C.c_int, C.c_int, C.POINTER(_P)]
+_lib.rs_plan_order.argtypes = [_P, C.POINTER(C.c_int32), C.c_int]
 _lib.rs_plan_destroy.argtypes = [_P]
 _lib.rs_plan_destroy.restype = None
 _lib.rs_check_valid_shard.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int,
@@ -128,6 +132,23 @@ def rs_plan_create(tensors: Sequence[Tuple], world: int, align_bytes: int = 16, 
                                int(min_itemsize), int(tensor_align_elems), C.byref(out)),
            "rs_plan_create")
     return out.value
+
+
+def rs_plan_create_ordered(tensors: Sequence[Tuple], world: int, align_bytes: int = 16,
+                           min_itemsize: int = 1, tensor_align_elems: int = 0,
+                           order: int = RS_ORDER_DEFAULT) -> int:
+    out = _P()
+    _check(_lib.rs_plan_create_ordered(_descs(tensors), len(tensors), int(world), int(align_bytes),
+                                       int(min_itemsize), int(tensor_align_elems), int(order),
+                                       C.byref(out)), "rs_plan_create_ordered")
+    return out.value
+
+
+def rs_plan_order(plan) -> List[int]:
+    n = rs_plan_num_tensors(plan)
+    out = (C.c_int32 * n)()
+    _check(_lib.rs_plan_order(plan, out, n), "rs_plan_order")
+    return list(out)
 
 
 def rs_plan_destroy(plan: int) -> None:

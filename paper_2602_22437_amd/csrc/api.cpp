@@ -96,45 +96,75 @@ const char* rs_strerror(int code) {
   }
 }
 
-int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_bytes, int min_itemsize,
-                   int tensor_align_elems, rs_plan** out) {
+int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                           int min_itemsize, int tensor_align_elems, int order, rs_plan** out) {
   if (!out) return RS_EINVAL;
   *out = nullptr;
+  if (order < RS_ORDER_DEFAULT || order > RS_ORDER_BEST) return RS_EINVAL;
   try {
-    rs_plan* p = new rs_plan();
-    int rc = build_plan(descs, n, world, align_bytes, min_itemsize, tensor_align_elems, &p->t,
-                        &p->g_coll, &p->A);
-    if (rc == RS_OK) {
+    std::vector<rs::TensorHost> listed;
+    int64_t g_coll = 0, A = 0;
+    int rc = build_plan(descs, n, world, align_bytes, min_itemsize, tensor_align_elems, &listed,
+                        &g_coll, &A);
+    if (rc != RS_OK) return rc;
+
+    // the candidate orders, in the heuristic's sequence; a later one must be strictly better
+    std::vector<int> orders;
+    if (order == RS_ORDER_BEST)
+      orders = {RS_ORDER_DEFAULT, RS_ORDER_BLOCK_SIZE, RS_ORDER_SHAPE};
+    else
+      orders = {order};
+    rs_plan* best = nullptr;
+    for (int o : orders) {
+      rs_plan* p = new rs_plan();
+      rs::order_tensors(listed, o, &p->orig);
+      for (int32_t i : p->orig) p->t.push_back(listed[size_t(i)]);
       p->world = world;
+      p->g_coll = g_coll;
+      p->A = A;
       rc = rs::solve_shard_size(p->t, p->world, p->g_coll, p->A, &p->S);
-    }
-    if (rc == RS_OK) {
-      std::vector<int64_t> starts;
-      if (!rs::check_valid_shard(p->t, p->world, p->S, p->A, &starts)) rc = RS_EINVAL;
-      int64_t sb = 0;
-      p->all_quant = true;
-      for (size_t i = 0; rc == RS_OK && i < p->t.size(); ++i) {
-        p->t[i].ell = starts[i];
-        p->t[i].scale_base = sb;
-        sb += p->t[i].nbr * p->t[i].nbc;
-        p->payload += p->t[i].e;
-        p->all_quant = p->all_quant && p->t[i].quant;
+      if (rc != RS_OK) {
+        delete p;
+        delete best;
+        return rc;
       }
-      p->num_scales = sb;
-      if (rc == RS_OK) {
-        p->scale_begin.resize(size_t(world) + 1);
-        for (int k = 0; k <= world; ++k) p->scale_begin[size_t(k)] = scales_in_front(*p, int64_t(k) * p->S);
+      if (best && best->S <= p->S) {
+        delete p;
+      } else {
+        delete best;
+        best = p;
       }
     }
-    if (rc != RS_OK) {
+    rs_plan* p = best;
+    std::vector<int64_t> starts;
+    if (!rs::check_valid_shard(p->t, p->world, p->S, p->A, &starts)) {
       delete p;
-      return rc;
+      return RS_EINVAL;
     }
+    int64_t sb = 0;
+    p->all_quant = true;
+    for (size_t i = 0; i < p->t.size(); ++i) {
+      p->t[i].ell = starts[i];
+      p->t[i].scale_base = sb;
+      sb += p->t[i].nbr * p->t[i].nbc;
+      p->payload += p->t[i].e;
+      p->all_quant = p->all_quant && p->t[i].quant;
+    }
+    p->num_scales = sb;
+    p->scale_begin.resize(size_t(world) + 1);
+    for (int k = 0; k <= world; ++k)
+      p->scale_begin[size_t(k)] = scales_in_front(*p, int64_t(k) * p->S);
     *out = p;
     return RS_OK;
   } catch (const std::bad_alloc&) {
     return RS_ENOMEM;
   }
+}
+
+int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_bytes, int min_itemsize,
+                   int tensor_align_elems, rs_plan** out) {
+  return rs_plan_create_ordered(descs, n, world, align_bytes, min_itemsize, tensor_align_elems,
+                                RS_ORDER_DEFAULT, out);
 }
 
 void rs_plan_destroy(rs_plan* plan) {
@@ -169,15 +199,21 @@ int64_t rs_plan_padding_elems(const rs_plan* plan) {
 }
 int64_t rs_plan_num_scales(const rs_plan* plan) { return plan ? plan->num_scales : RS_EINVAL; }
 
+int rs_plan_order(const rs_plan* plan, int32_t* out, int cap) {
+  if (!plan || !out || cap < int(plan->t.size())) return RS_EINVAL;
+  for (size_t j = 0; j < plan->t.size(); ++j) out[j] = plan->orig[j];
+  return RS_OK;
+}
+
 int rs_plan_offsets(const rs_plan* plan, int64_t* out, int cap) {
   if (!plan || !out || cap < int(plan->t.size())) return RS_EINVAL;
-  for (size_t i = 0; i < plan->t.size(); ++i) out[i] = plan->t[i].ell;
+  for (size_t j = 0; j < plan->t.size(); ++j) out[size_t(plan->orig[j])] = plan->t[j].ell;
   return RS_OK;
 }
 
 int rs_plan_scale_bases(const rs_plan* plan, int64_t* out, int cap) {
   if (!plan || !out || cap < int(plan->t.size()) + 1) return RS_EINVAL;
-  for (size_t i = 0; i < plan->t.size(); ++i) out[i] = plan->t[i].scale_base;
+  for (size_t j = 0; j < plan->t.size(); ++j) out[size_t(plan->orig[j])] = plan->t[j].scale_base;
   out[plan->t.size()] = plan->num_scales;
   return RS_OK;
 }
@@ -200,7 +236,7 @@ int rs_plan_rank_segments(const rs_plan* plan, int rank, rs_segment* out, int ca
     if (a >= b) continue;
     if (count < cap) {
       rs_segment s{};
-      s.tensor = int32_t(i);
+      s.tensor = plan->orig[i];
       s.src_off = a - h.ell;
       s.dst_off = a - lo;
       s.n = b - a;
@@ -267,7 +303,10 @@ int rs_tensor_table_create(const rs_plan* plan, const void* const* ptrs, rs_tens
     delete tab;
     return RS_ENOMEM;
   }
-  if (hipMemcpy(tab->ptrs, ptrs, sizeof(void*) * n, hipMemcpyHostToDevice) != hipSuccess) {
+  // device table in buffer order, like the tensor records
+  std::vector<const void*> ordered(size_t(n), nullptr);
+  for (int j = 0; j < n; ++j) ordered[size_t(j)] = ptrs[plan->orig[size_t(j)]];
+  if (hipMemcpy(tab->ptrs, ordered.data(), sizeof(void*) * n, hipMemcpyHostToDevice) != hipSuccess) {
     (void)hipFree(tab->ptrs);
     delete tab;
     return RS_EHIP;

@@ -125,6 +125,25 @@ int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>
   return RS_OK;
 }
 
+// Tensor orders of the heuristic-guided solution (Section 5): the caller's order, ascending
+// sharding block size, or ascending shape (element count, rows, cols); stable, so equal keys
+// keep the caller's order.
+void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int32_t>* perm) {
+  perm->resize(t.size());
+  for (size_t i = 0; i < t.size(); ++i) (*perm)[i] = int32_t(i);
+  if (order == RS_ORDER_BLOCK_SIZE) {
+    std::stable_sort(perm->begin(), perm->end(),
+                     [&](int32_t a, int32_t b) { return t[size_t(a)].g < t[size_t(b)].g; });
+  } else if (order == RS_ORDER_SHAPE) {
+    std::stable_sort(perm->begin(), perm->end(), [&](int32_t a, int32_t b) {
+      const TensorHost &x = t[size_t(a)], &y = t[size_t(b)];
+      if (x.e != y.e) return x.e < y.e;
+      if (x.rows != y.rows) return x.rows < y.rows;
+      return x.cols < y.cols;
+    });
+  }
+}
+
 // Outer loop of Algorithm 1: unit g <- g_coll, then g <- lcm(g, g') over the ascending distinct
 // block sizes; per unit the smallest feasible multiple by lower-bound bisection; S* = minimum.
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,

@@ -80,6 +80,7 @@ bool check_valid_shard(const std::vector<TensorHost>& t, int64_t world, int64_t 
 int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>* out);
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
                      int64_t* S_out);
+void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int32_t>* perm);
 
 // ---- derived tables (tables.cpp) ----
 void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t S, bool all_quant,
@@ -88,7 +89,8 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
 }  // namespace rs
 
 struct rs_plan {
-  std::vector<rs::TensorHost> t;
+  std::vector<rs::TensorHost> t;   // in BUFFER order (increasing l_t)
+  std::vector<int32_t> orig;       // orig[j] = caller's index of the j-th tensor in the buffer
   int64_t world = 0, g_coll = 0, A = 0, S = 0, payload = 0, num_scales = 0;
   bool all_quant = false;
   std::vector<int64_t> scale_begin;  // world + 1: first scale of every rank

@@ -392,3 +392,24 @@ def test_quantize_batch_equals_per_unit_quantize():
         assert e.value.code == B.RS_EINVAL
     finally:
         u.close()
+
+
+@pytest.mark.parametrize("order", [1, 2, 3])
+def test_reordered_plans_all_ops(order):
+    """Plans whose buffer order differs from the caller's tensor order (sorted by block size, by
+    shape, best of three): pointer tables, offsets and the scale layout must all follow."""
+    wl = WORKLOADS[1]
+    tensors = [(t.rows, t.cols, t.mode) for t in wl.tensors] + [(200, 0, MODE_1x128), (64, 520, MODE_1x128)]
+    u = Unit(tensors, 5, order=order)
+    try:
+        if order != 3:
+            assert u.oracle.buffer_order() != list(range(len(tensors)))
+        params = [normal_bf16(17, order, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        _, db_bits = check_pack_unpack(u, params, f"order{order}")
+        for k in range(5):
+            parts = np.stack([normal_bf16(17, order, 1, k * 8 + w, u.S, 1e-3) for w in range(5)])
+            check_reduce(u, k, parts, f"order{order}")
+        c, s, wc, ws = check_quant(u, db_bits, f"order{order}", range(5))
+        check_dequant_unpack(u, c, s, wc, ws, f"order{order}")
+    finally:
+        u.close()

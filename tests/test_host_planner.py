@@ -154,3 +154,38 @@ def test_planner_runtime_on_largest_config():
     dt = time.time() - t0
     B.rs_plan_destroy(plan)
     assert dt < 0.3           # "less than 0.3 seconds" (Section 6.4)
+
+
+@pytest.mark.parametrize("order", [B.RS_ORDER_DEFAULT, B.RS_ORDER_BLOCK_SIZE, B.RS_ORDER_SHAPE, B.RS_ORDER_BEST])
+def test_tensor_orders_match_oracle(order):
+    rnd = random.Random(100 + order)
+    for _ in range(150):
+        tensors, world, align, item, A = random_unit(rnd)
+        specs = [P.TensorSpec(*t) for t in tensors]
+        want = P.make_plan(specs, world, align, item, tensor_align=A or None, order=order)
+        plan = B.rs_plan_create_ordered(tensors, world, align, item, A, order)
+        try:
+            assert B.rs_plan_shard_elems(plan) == want.S
+            assert B.rs_plan_order(plan) == want.buffer_order()
+            assert B.rs_plan_offsets(plan) == want.offsets
+            assert B.rs_plan_scale_bases(plan) == want.scale_bases()
+            for k in range(world):
+                assert B.rs_plan_rank_segments(plan, k) == want.rank_segments(k)
+        finally:
+            B.rs_plan_destroy(plan)
+    for idx in (2, 4):
+        wl = WORKLOADS[idx]
+        specs = [P.TensorSpec(t.rows, t.cols, t.mode) for t in wl.tensors]
+        want = P.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize, order=order)
+        plan = B.rs_plan_create_ordered([(t.rows, t.cols, t.mode) for t in wl.tensors], wl.world,
+                                        wl.align_bytes, wl.min_itemsize, 0, order)
+        try:
+            assert B.rs_plan_shard_elems(plan) == want.S and B.rs_plan_offsets(plan) == want.offsets
+        finally:
+            B.rs_plan_destroy(plan)
+
+
+def test_unknown_order_is_rejected():
+    with pytest.raises(B.RaggedShardError) as e:
+        B.rs_plan_create_ordered([(16, 16, B.RS_BLOCK_128x128)], 2, 16, 1, 0, 7)
+    assert e.value.code == B.RS_EINVAL

@@ -341,3 +341,46 @@ def test_oracle_matches_stored_plan_sizes():
         pl = P.make_plan(specs_of(wl), wl.world, wl.align_bytes, wl.min_itemsize)
         assert (pl.S, pl.total, pl.payload, pl.scale_bases()[-1]) == (g["S"], g["total"], g["E"], g["nb"])
         assert pl.offsets[:6] == g["offsets"]
+
+
+def test_tensor_orders_are_valid_permutations_and_best_is_minimum():
+    rnd = random.Random(31)
+    for _ in range(200):
+        tensors, m, g_coll, A = random_case(rnd)
+        specs = [P.TensorSpec(e, 0, P.BLOCK_EXPLICIT, g) for e, g in tensors]
+        plans = {}
+        for order in (P.ORDER_DEFAULT, P.ORDER_BLOCK_SIZE, P.ORDER_SHAPE, P.ORDER_BEST):
+            pl = P.make_plan(specs, m, g_coll, 1, tensor_align=A, order=order)
+            plans[order] = pl
+            perm = pl.buffer_order()
+            assert sorted(perm) == list(range(len(specs)))
+            # offsets follow the buffer order and satisfy the constraints for the ORIGINAL indices
+            offs = [pl.offsets[t] for t in perm]
+            assert offs == sorted(offs)
+            assert P.layout_violations(tensors, pl.offsets, m, pl.S, g_coll, A) == []
+        assert plans[P.ORDER_DEFAULT].buffer_order() == list(range(len(specs)))
+        gs = [specs[t].g for t in plans[P.ORDER_BLOCK_SIZE].buffer_order()]
+        assert gs == sorted(gs)
+        es = [specs[t].e for t in plans[P.ORDER_SHAPE].buffer_order()]
+        assert es == sorted(es)
+        assert plans[P.ORDER_BEST].S == min(plans[o].S for o in (0, 1, 2))
+
+
+def test_scale_layout_follows_buffer_order():
+    wl = WORKLOADS[1]
+    specs = specs_of(wl)
+    pl = P.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize, order=P.ORDER_SHAPE)
+    assert pl.buffer_order() != list(range(len(specs)))
+    bases = pl.scale_bases()
+    acc = 0
+    for t in pl.buffer_order():          # scales are laid out as the tensors are in the buffer
+        assert bases[t] == acc
+        acc += specs[t].num_blocks
+    prev = 0
+    for k in range(wl.world):
+        lo, hi = pl.scale_range(k)
+        assert lo == prev and hi >= lo
+        prev = hi
+        segs = pl.rank_segments(k)
+        assert [s[2] for s in segs] == sorted(s[2] for s in segs)
+    assert prev == bases[-1]
