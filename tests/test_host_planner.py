@@ -189,3 +189,18 @@ def test_unknown_order_is_rejected():
     with pytest.raises(B.RaggedShardError) as e:
         B.rs_plan_create_ordered([(16, 16, B.RS_BLOCK_128x128)], 2, 16, 1, 0, 7)
     assert e.value.code == B.RS_EINVAL
+
+
+def test_padding_study_reproduces_the_papers_qualitative_claims():
+    """Section 6.4: with 1x and 16x row granularity the padding stays below 3 % for every FSDP
+    size on both model shapes; 128x rows cost more and grow with the FSDP size; every plan
+    takes well under 0.3 s."""
+    from paper_2602_22437_amd import padding_study as PS
+    worlds = [8, 32, 64, 128, 256, 512, 1024]
+    for model in ("deepseek", "gpt_oss", "gpt_oss_fused"):
+        res = PS.sweep(model, worlds)
+        for g in (1, 16):
+            assert all(res[g][w][0] < 0.03 for w in worlds), (model, g)
+        assert all(res[128][w][0] >= res[1][w][0] for w in worlds)
+        assert res[128][1024][0] > res[128][8][0]
+        assert all(res[g][w][1] < 0.3 for g in res for w in worlds)
