@@ -414,18 +414,23 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
     float* __restrict__ scales_one, void* const* __restrict__ batch, int batch_count,
     int64_t elem_base, int64_t scale_off, int64_t item_count) {
   __shared__ unsigned wave_max[kQuantThreads / 64];
-  // batched launch: blockIdx.y picks the unit; batch = [shards | codes | scales] pointers
+  // batched launch: batch = [shards | codes | scales] pointers of batch_count units
   const uint16_t* __restrict__ x = x_one;
   uint8_t* __restrict__ codes = codes_one;
   float* __restrict__ scales = scales_one;
-  if (batch) {
-    x = static_cast<const uint16_t*>(batch[blockIdx.y]);
-    codes = static_cast<uint8_t*>(batch[batch_count + blockIdx.y]);
-    scales = static_cast<float*>(batch[2 * batch_count + blockIdx.y]);
-  }
   // adjacent tiles of a row of tiles share DRAM pages and cache lines: keep them on one XCD
-  const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
-  if (idx >= item_count) return;
+  int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
+  if (batch) {
+    // the units' item ranges are laid end to end in one flat grid: no idle tail per unit
+    const int64_t u = idx / item_count;
+    if (u >= batch_count) return;
+    idx -= u * item_count;
+    x = static_cast<const uint16_t*>(batch[u]);
+    codes = static_cast<uint8_t*>(batch[batch_count + u]);
+    scales = static_cast<float*>(batch[2 * batch_count + u]);
+  } else if (idx >= item_count) {
+    return;
+  }
   const Item it = items[item_off + idx];
   if (it.tensor < 0) {
     zero_fill_bytes(codes + (it.first - elem_base), it.count, kQuantThreads);
@@ -714,8 +719,9 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
   if (item_count == 0 || (batch && batch_count == 0)) return RS_OK;
   if (item_count < 0 || item_count > 0x7fffffffLL || batch_count < 0 || batch_count > 65535)
     return RS_EOVERFLOW;
-  const dim3 grid(unsigned(xcd_grid(item_count)), batch ? unsigned(batch_count) : 1u);
-  block_quant_kernel<<<grid, dim3(kQuantThreads), 0, st>>>(
+  const int64_t work = item_count * (batch ? batch_count : 1);
+  if (work > 0x7fffff00LL) return RS_EOVERFLOW;
+  block_quant_kernel<<<dim3(unsigned(xcd_grid(work))), dim3(kQuantThreads), 0, st>>>(
       dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, batch,
       batch_count, elem_base, scale_off, item_count);
   return launched();
