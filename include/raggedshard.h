@@ -149,6 +149,23 @@ int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* s
 /* Inverse group copy: dst_t[i] = dbuf[l_t + i] (bf16 DBuffer -> per-tensor bf16). */
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream);
 
+/* ---- the other group-level operators of the DBuffer (Section 5: the add, scale, zero and copy
+ * kernels that each tensor would launch around a collective, fused across the group) ----------
+ * alpha is an fp32 factor (finite, else RS_EINVAL); every product and sum is one fp32
+ * operation in the order written and the result is rounded to bf16 once, to nearest even.
+ * dbuf: device, world*S bf16, 16-byte aligned; src: table of bf16 device tensors.
+ *   rs_pack_scaled  dbuf[l_t + i] = bf16(src_t[i] * alpha), padding = +0  (copy-in + pre-division)
+ *   rs_group_add    dbuf[l_t + i] = bf16(dbuf[l_t + i] + alpha * src_t[i]) (gradient accumulation)
+ *   rs_group_scale  dbuf[l_t + i] = bf16(dbuf[l_t + i] * alpha)
+ *   rs_group_zero   dbuf[0, world*S) = +0
+ * rs_group_add and rs_group_scale leave padding as it is. */
+int rs_pack_scaled(const rs_plan* plan, const rs_tensor_table* src, float alpha, void* dbuf,
+                   void* stream);
+int rs_group_add(const rs_plan* plan, const rs_tensor_table* src, float alpha, void* dbuf,
+                 void* stream);
+int rs_group_scale(const rs_plan* plan, float alpha, void* dbuf, void* stream);
+int rs_group_zero(const rs_plan* plan, void* dbuf, void* stream);
+
 /* ---- shard_reduce: the arithmetic of the gradient ReduceScatter as one rank sees it --------
  * (Section 2.3).  out[i] = (1/world) * sum_w partials[w*row_stride + i] for i in the
  * payload of rank's region, 0 on its padding; fp32 accumulation in a fixed order.

@@ -23,6 +23,7 @@ EXPORTS = [
     "rs_tensor_table_create", "rs_tensor_table_destroy", "rs_pack", "rs_unpack_bf16", "rs_reduce",
     "rs_quantize", "rs_unpack", "rs_copy_probe", "rs_shard_batch_create", "rs_shard_batch_destroy",
     "rs_quantize_batch", "rs_plan_create_ordered", "rs_plan_order",
+    "rs_pack_scaled", "rs_group_add", "rs_group_scale", "rs_group_zero",
 ]
 
 
@@ -77,6 +78,10 @@ _lib.rs_tensor_table_destroy.argtypes = [_P]
 _lib.rs_tensor_table_destroy.restype = None
 _lib.rs_pack.argtypes = [_P, _P, _P, _P]
 _lib.rs_unpack_bf16.argtypes = [_P, _P, _P, _P]
+_lib.rs_pack_scaled.argtypes = [_P, _P, C.c_float, _P, _P]
+_lib.rs_group_add.argtypes = [_P, _P, C.c_float, _P, _P]
+_lib.rs_group_scale.argtypes = [_P, C.c_float, _P, _P]
+_lib.rs_group_zero.argtypes = [_P, _P, _P]
 _lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
@@ -246,6 +251,22 @@ def rs_pack(plan, src_table, dbuf, stream=None) -> None:
 
 def rs_unpack_bf16(plan, dbuf, dst_table, stream=None) -> None:
     _check(_lib.rs_unpack_bf16(plan, _ptr(dbuf), dst_table, _stream(stream)), "rs_unpack_bf16")
+
+
+def rs_pack_scaled(plan, src_table, alpha: float, dbuf, stream=None) -> None:
+    _check(_lib.rs_pack_scaled(plan, src_table, float(alpha), _ptr(dbuf), _stream(stream)), "rs_pack_scaled")
+
+
+def rs_group_add(plan, src_table, alpha: float, dbuf, stream=None) -> None:
+    _check(_lib.rs_group_add(plan, src_table, float(alpha), _ptr(dbuf), _stream(stream)), "rs_group_add")
+
+
+def rs_group_scale(plan, alpha: float, dbuf, stream=None) -> None:
+    _check(_lib.rs_group_scale(plan, float(alpha), _ptr(dbuf), _stream(stream)), "rs_group_scale")
+
+
+def rs_group_zero(plan, dbuf, stream=None) -> None:
+    _check(_lib.rs_group_zero(plan, _ptr(dbuf), _stream(stream)), "rs_group_zero")
 
 
 def rs_reduce(plan, rank: int, partials, row_stride: int, out, stream=None) -> None:

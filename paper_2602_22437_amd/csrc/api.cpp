@@ -321,26 +321,49 @@ void rs_tensor_table_destroy(rs_tensor_table* table) {
   delete table;
 }
 
-int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* stream) {
+// shared body of the group-level operators on the bf16 DBuffer
+static int group_op(int op, const rs_plan* plan, const rs_tensor_table* tab, const void* dbuf,
+                    float alpha, void* stream) {
   int rc = check_device(plan);
-  if (rc == RS_OK) rc = check_table(plan, src);
+  if (rc == RS_OK && op != rs::kGroupScale) rc = check_table(plan, tab);
   if (rc != RS_OK) return rc;
   if (!dbuf) return RS_EINVAL;
   if (!aligned16(dbuf)) return RS_EALIGN;
-  return rs::launch_group_copy(false, plan->dev, int(plan->t.size()), src->ptrs, dbuf, plan->S,
-                               plan->host.granules_per_rank, plan->host.n_payload_gran,
-                               plan->host.n_padding_gran, static_cast<hipStream_t>(stream));
+  if (alpha != alpha || alpha - alpha != 0.0f) return RS_EINVAL;  // NaN or infinite factor
+  return rs::launch_group_op(op, plan->dev, int(plan->t.size()), tab ? tab->ptrs : nullptr,
+                             const_cast<void*>(dbuf), alpha, plan->S, plan->host.granules_per_rank,
+                             plan->host.n_payload_gran, plan->host.n_padding_gran,
+                             static_cast<hipStream_t>(stream));
+}
+
+int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* stream) {
+  return group_op(rs::kGroupPack, plan, src, dbuf, 1.0f, stream);
 }
 
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream) {
-  int rc = check_device(plan);
-  if (rc == RS_OK) rc = check_table(plan, dst);
+  return group_op(rs::kGroupUnpack, plan, dst, dbuf, 1.0f, stream);
+}
+
+int rs_pack_scaled(const rs_plan* plan, const rs_tensor_table* src, float alpha, void* dbuf,
+                   void* stream) {
+  return group_op(rs::kGroupPackScaled, plan, src, dbuf, alpha, stream);
+}
+
+int rs_group_add(const rs_plan* plan, const rs_tensor_table* src, float alpha, void* dbuf,
+                 void* stream) {
+  return group_op(rs::kGroupAdd, plan, src, dbuf, alpha, stream);
+}
+
+int rs_group_scale(const rs_plan* plan, float alpha, void* dbuf, void* stream) {
+  return group_op(rs::kGroupScale, plan, nullptr, dbuf, alpha, stream);
+}
+
+int rs_group_zero(const rs_plan* plan, void* dbuf, void* stream) {
+  const int rc = check_device(plan);
   if (rc != RS_OK) return rc;
   if (!dbuf) return RS_EINVAL;
   if (!aligned16(dbuf)) return RS_EALIGN;
-  return rs::launch_group_copy(true, plan->dev, int(plan->t.size()), dst->ptrs,
-                               const_cast<void*>(dbuf), plan->S, plan->host.granules_per_rank,
-                               plan->host.n_payload_gran, 0, static_cast<hipStream_t>(stream));
+  return rs::launch_fill_zero(dbuf, plan->S * plan->world * 2, static_cast<hipStream_t>(stream));
 }
 
 int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride, float* out,

@@ -49,20 +49,52 @@ static inline int64_t xcd_grid(int64_t count) {
 }
 
 // -------------------------------------------------------------------------------------------
-// ragged_pack / unpack_bf16: group copy between per-tensor storage and the DBuffer.
+// Group-level operators of the DBuffer: one launch for all tensors of the unit.
+//   pack (copy + zero), its inverse, pack with a scale factor, accumulate (axpy), scale.
 // Four single-wavefront workgroups per granule (kGranule buffer elements of one rank region)
-// that holds payload; ragged_pack adds one workgroup per pure-padding granule to zero it.
+// that holds payload; the two pack forms add one workgroup per pure-padding granule to zero it,
+// the others never touch padding.  fp32 arithmetic, one rounding to bf16 (nearest even).
 // -------------------------------------------------------------------------------------------
 constexpr int kCopyThreads = 64;
 constexpr int kCopyParts = kGranule / (kCopyThreads * 8);  // workgroups per granule: 4
 
-template <bool kUnpack>
-__global__ __launch_bounds__(kCopyThreads) void group_copy_kernel(
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+__device__ __forceinline__ float bf16_lo(unsigned packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// d = bf16(d * alpha) / d = bf16(d + alpha * s) on a packed pair; separate multiply and add
+__device__ __forceinline__ unsigned scale_pair(unsigned d, float alpha) {
+  return pack_bf16(bf16_lo(d) * alpha, bf16_hi(d) * alpha);
+}
+__device__ __forceinline__ unsigned axpy_pair(unsigned d, unsigned s, float alpha) {
+  const float lo = alpha * bf16_lo(s), hi = alpha * bf16_hi(s);
+  return pack_bf16(bf16_lo(d) + lo, bf16_hi(d) + hi);
+}
+__device__ __forceinline__ u32x4 scale8(u32x4 d, float alpha) {
+  return u32x4{scale_pair(d.x, alpha), scale_pair(d.y, alpha), scale_pair(d.z, alpha),
+               scale_pair(d.w, alpha)};
+}
+__device__ __forceinline__ u32x4 axpy8(u32x4 d, u32x4 s, float alpha) {
+  return u32x4{axpy_pair(d.x, s.x, alpha), axpy_pair(d.y, s.y, alpha), axpy_pair(d.z, s.z, alpha),
+               axpy_pair(d.w, s.w, alpha)};
+}
+
+template <int kOp>
+__global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
     const int32_t* __restrict__ granules, const int32_t* __restrict__ padding,
     unsigned n_copy_groups, void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S,
-    int64_t gpr) {
-  if (!kUnpack && blockIdx.x >= n_copy_groups) {
+    int64_t gpr, float alpha) {
+  constexpr bool kFillsPadding = kOp == kGroupPack || kOp == kGroupPackScaled;
+  constexpr bool kReadsBuffer = kOp == kGroupUnpack || kOp == kGroupAdd || kOp == kGroupScale;
+  constexpr bool kUsesTensors = kOp != kGroupScale;
+  if (kFillsPadding && blockIdx.x >= n_copy_groups) {
     // a granule of nothing but padding: this wavefront zeroes all of it
     const int64_t gid = padding[blockIdx.x - n_copy_groups];
     const int64_t k = gid / gpr;
@@ -91,27 +123,35 @@ __global__ __launch_bounds__(kCopyThreads) void group_copy_kernel(
     const int64_t ell = T[t0].ell, end = ell + T[t0].e;
     if (ell <= d0 && d0 + len <= end) {
       // the whole granule lies inside tensor t0 (the common case by far)
+      if (!kUsesTensors) {
+        st16(dbuf + d, scale8(ld16(dbuf + d), alpha));
+        return;
+      }
       uint16_t* base = reinterpret_cast<uint16_t*>(ptrs[t0]) + (d0 - ell);
       if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
-        if (kUnpack)
+        if (kOp == kGroupUnpack)
           st16(base + lane_off, ld16(dbuf + d));
-        else
+        else if (kOp == kGroupPack)
           st16(dbuf + d, ld16(base + lane_off));
+        else if (kOp == kGroupPackScaled)
+          st16(dbuf + d, scale8(ld16(base + lane_off), alpha));
+        else
+          st16(dbuf + d, axpy8(ld16(dbuf + d), ld16(base + lane_off), alpha));
         return;
       }
     }
     empty = ell >= d0 + len;
   }
   if (empty) {  // nothing but padding here
-    if (!kUnpack) st16(dbuf + d, u32x4{0, 0, 0, 0});
+    if (kFillsPadding) st16(dbuf + d, u32x4{0, 0, 0, 0});
     return;
   }
 
   // Mixed granule (tensor boundaries, padding, or a source that is not 16-byte aligned):
   // resolve every element on its own.
   int s = t0;
-  uint16_t vals[8];
-  if (kUnpack) {
+  uint16_t vals[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (kReadsBuffer) {
     const u32x4 v = ld16(dbuf + d);
     vals[0] = uint16_t(v.x); vals[1] = uint16_t(v.x >> 16);
     vals[2] = uint16_t(v.y); vals[3] = uint16_t(v.y >> 16);
@@ -123,13 +163,22 @@ __global__ __launch_bounds__(kCopyThreads) void group_copy_kernel(
     const int64_t pos = d + q;
     while (s < n && T[s].ell + T[s].e <= pos) ++s;
     const bool inside = s < n && T[s].ell <= pos;
-    if (kUnpack) {
-      if (inside) reinterpret_cast<uint16_t*>(ptrs[s])[pos - T[s].ell] = vals[q];
-    } else {
-      vals[q] = inside ? reinterpret_cast<const uint16_t*>(ptrs[s])[pos - T[s].ell] : uint16_t(0);
+    if (!inside) continue;   // padding keeps what it holds (+0 for the pack forms)
+    if (kOp == kGroupScale) {
+      vals[q] = uint16_t(scale_pair(vals[q], alpha));
+      continue;
     }
+    uint16_t* elem = reinterpret_cast<uint16_t*>(ptrs[s]) + (pos - T[s].ell);
+    if (kOp == kGroupUnpack)
+      *elem = vals[q];
+    else if (kOp == kGroupPack)
+      vals[q] = *elem;
+    else if (kOp == kGroupPackScaled)
+      vals[q] = uint16_t(scale_pair(*elem, alpha));
+    else
+      vals[q] = uint16_t(axpy_pair(vals[q], *elem, alpha));
   }
-  if (!kUnpack) {
+  if (kOp != kGroupUnpack) {
     u32x4 v;
     v.x = vals[0] | (uint32_t(vals[1]) << 16);
     v.y = vals[2] | (uint32_t(vals[3]) << 16);
@@ -137,6 +186,12 @@ __global__ __launch_bounds__(kCopyThreads) void group_copy_kernel(
     v.w = vals[6] | (uint32_t(vals[7]) << 16);
     st16(dbuf + d, v);
   }
+}
+
+// every element of a buffer of nvec 16-byte vectors becomes +0
+__global__ __launch_bounds__(kCopyThreads) void fill_zero_kernel(u32x4* __restrict__ dst, int64_t nvec) {
+  const int64_t i = int64_t(blockIdx.x) * kCopyThreads + threadIdx.x;
+  if (i < nvec) __builtin_nontemporal_store(u32x4{0, 0, 0, 0}, dst + i);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -561,14 +616,6 @@ __device__ __forceinline__ unsigned bf16_rne(float f) {
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
-}
-
 __device__ __forceinline__ void dequant4(unsigned word, float scale, unsigned& lo, unsigned& hi) {
   const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), false);  // bytes 0, 1
   const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), true);   // bytes 2, 3
@@ -680,22 +727,38 @@ __global__ __launch_bounds__(kCopyThreads) void copy_probe_kernel(const u32x4* _
 // -------------------------------------------------------------------------------------------
 static int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }
 
-int launch_group_copy(bool unpack, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf,
-                      int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
-                      hipStream_t st) {
+int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf, float alpha,
+                    int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
+                    hipStream_t st) {
+  const bool fills = op == kGroupPack || op == kGroupPackScaled;
   const int64_t copy_groups = n_payload_gran * kCopyParts;
-  const int64_t grid = copy_groups + (unpack ? 0 : n_padding_gran);
+  const int64_t grid = copy_groups + (fills ? n_padding_gran : 0);
   if (grid == 0) return RS_OK;
   if (grid < 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
   uint16_t* db = static_cast<uint16_t*>(dbuf);
-  if (unpack)
-    group_copy_kernel<true><<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(
-        dev.tensors, n, dev.gran_first, dev.payload_gran, nullptr, unsigned(copy_groups), ptrs, db,
-        S, gpr);
-  else
-    group_copy_kernel<false><<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(
-        dev.tensors, n, dev.gran_first, dev.payload_gran, dev.padding_gran, unsigned(copy_groups),
-        ptrs, db, S, gpr);
+  const dim3 g{unsigned(grid)}, b{unsigned(kCopyThreads)};
+#define RS_GROUP_OP(OP)                                                                         \
+  group_op_kernel<OP><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,       \
+                                       dev.padding_gran, unsigned(copy_groups), ptrs, db, S,   \
+                                       gpr, alpha)
+  switch (op) {
+    case kGroupPack: RS_GROUP_OP(kGroupPack); break;
+    case kGroupUnpack: RS_GROUP_OP(kGroupUnpack); break;
+    case kGroupPackScaled: RS_GROUP_OP(kGroupPackScaled); break;
+    case kGroupAdd: RS_GROUP_OP(kGroupAdd); break;
+    case kGroupScale: RS_GROUP_OP(kGroupScale); break;
+    default: return RS_EINVAL;
+  }
+#undef RS_GROUP_OP
+  return launched();
+}
+
+int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st) {
+  const int64_t nvec = bytes / 16;
+  const int64_t grid = (nvec + kCopyThreads - 1) / kCopyThreads;
+  if (grid == 0) return RS_OK;
+  if (grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  fill_zero_kernel<<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(static_cast<u32x4*>(dst), nvec);
   return launched();
 }
 

@@ -6,9 +6,12 @@
 
 namespace rs {
 
-int launch_group_copy(bool unpack, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf,
-                      int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
-                      hipStream_t st);
+// group-level operators on the bf16 DBuffer; `op` is one of the values below
+enum : int { kGroupPack = 0, kGroupUnpack = 1, kGroupPackScaled = 2, kGroupAdd = 3, kGroupScale = 4 };
+int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf, float alpha,
+                    int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
+                    hipStream_t st);
+int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st);
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
                         float* out, int64_t S, int64_t gpr, int rank, int world, hipStream_t st);
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,

@@ -1,0 +1,194 @@
+"""GPU parity of the DBuffer's group-level add / scale / zero / scaled copy against the CPU
+oracle, bit for bit, through the C ABI: toy and ragged units (odd pitches, element-aligned
+plans, element-aligned storage), the config-2 unit at full size, reordered plans, error codes."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dbuffer as OD
+from oracle import group_ops as OG
+from paper_2602_22437_amd import binding as B
+from workloads import MODE_128x128, MODE_1x128, MODE_WHOLE, WORKLOADS, gen_params, normal_bf16
+
+from gpu_util import Unit, bits_of, say, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+ALPHAS = (1.0 / 64.0, -0.37109375, 1.0, 3.0e-5)
+GARBAGE = 0x4300   # bf16 128.0: what padding must never turn into
+
+
+def first_diff(got, want, what):
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero(got != want)
+        raise AssertionError(f"{what}: {bad.size} differ, first at {bad[:6]}: got {got[bad[:6]]} want {want[bad[:6]]}")
+
+
+def check_group_ops(u: Unit, params, grads, label, dev_grads=None):
+    sizes = [s.e for s in u.specs]
+    base = OD.ragged_pack(params, u.oracle.offsets, u.total)
+    dev_g = dev_grads if dev_grads is not None else [to_dev_bf16(g) for g in grads]
+    tab = u.table(dev_g)
+    for alpha in ALPHAS:
+        say(f"pack_scaled {label} alpha={alpha}")
+        dbuf = torch.full((u.total,), GARBAGE, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        B.rs_pack_scaled(u.plan, tab, alpha, dbuf)
+        torch.cuda.synchronize()
+        first_diff(bits_of(dbuf), OG.pack_scaled(grads, u.oracle.offsets, u.total, alpha), f"pack_scaled {label}")
+
+        say(f"group_add {label} alpha={alpha}")
+        dbuf = to_dev_bf16(base)
+        B.rs_group_add(u.plan, tab, alpha, dbuf)
+        torch.cuda.synchronize()
+        first_diff(bits_of(dbuf), OG.group_add(base, grads, u.oracle.offsets, alpha), f"group_add {label}")
+
+        say(f"group_scale {label} alpha={alpha}")
+        dbuf = to_dev_bf16(base)
+        B.rs_group_scale(u.plan, alpha, dbuf)
+        torch.cuda.synchronize()
+        first_diff(bits_of(dbuf), OG.group_scale(base, u.oracle.offsets, sizes, alpha), f"group_scale {label}")
+
+    # add and scale must not look at or write padding: poison it and see it survive
+    pay = np.zeros(u.total, dtype=bool)
+    for l, e in zip(u.oracle.offsets, sizes):
+        pay[l:l + e] = True
+    poisoned = base.copy()
+    poisoned[~pay] = GARBAGE
+    for name, run, want in (
+            ("group_add", lambda d: B.rs_group_add(u.plan, tab, 0.5, d),
+             OG.group_add(poisoned, grads, u.oracle.offsets, 0.5)),
+            ("group_scale", lambda d: B.rs_group_scale(u.plan, -2.0, d),
+             OG.group_scale(poisoned, u.oracle.offsets, sizes, -2.0))):
+        say(f"{name} {label} with poisoned padding")
+        dbuf = to_dev_bf16(poisoned)
+        run(dbuf)
+        torch.cuda.synchronize()
+        got = bits_of(dbuf)
+        first_diff(got, want, f"{name} poisoned {label}")
+        assert np.all(got[~pay] == GARBAGE)
+
+    say(f"group_zero {label}")
+    dbuf = to_dev_bf16(poisoned)
+    B.rs_group_zero(u.plan, dbuf)
+    torch.cuda.synchronize()
+    first_diff(bits_of(dbuf), OG.group_zero(u.total), f"group_zero {label}")
+
+
+def test_config1_group_ops():
+    wl = WORKLOADS[1]
+    u = Unit.from_workload(wl)
+    try:
+        check_group_ops(u, gen_params(wl, seed=21), gen_params(wl, seed=22), "cfg1")
+    finally:
+        u.close()
+
+
+RAGGED = [
+    ([(257, 130, MODE_128x128), (5, 0, MODE_1x128), (129, 7, MODE_128x128), (300, 0, MODE_1x128)], 3, 16, 1, 0),
+    ([(257, 130, MODE_128x128), (383, 0, MODE_1x128), (129, 8, MODE_128x128)], 4, 16, 1, 1),   # A = 1
+    ([(17, 24, MODE_1x128), (250, 0, MODE_1x128), (128, 256, MODE_128x128)], 7, 32, 1, 2),
+    ([(128, 128, MODE_128x128)], 8, 16, 1, 0),                                                 # empty ranks
+    ([(300, 200, MODE_WHOLE), (64, 64, MODE_WHOLE), (77, 0, MODE_1x128)], 4, 16, 2, 0),        # bf16-only plan
+]
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+def test_ragged_units_group_ops(case):
+    tensors, world, align, item, A = RAGGED[case]
+    u = Unit(tensors, world, align, item, A)
+    try:
+        params = [normal_bf16(31, case, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        grads = [normal_bf16(31, case, 1, i, s.e, 1e-3) for i, s in enumerate(u.specs)]
+        # tiny and special values: subnormal bf16, -0, values whose product underflows
+        grads[0][:6] = np.array([0x0001, 0x8000, 0x0000, 0x807F, 0x0080, 0x7F7F], dtype=np.uint16)
+        params[0][:6] = np.array([0x8001, 0x0000, 0x8000, 0x007F, 0x8080, 0x0001], dtype=np.uint16)
+        check_group_ops(u, params, grads, f"ragged{case}")
+    finally:
+        u.close()
+
+
+def test_element_aligned_storage_group_ops():
+    """Gradient tensors that are views at odd element offsets: the per-element path."""
+    tensors = [(130, 136, MODE_128x128), (700, 0, MODE_1x128), (64, 256, MODE_1x128)]
+    u = Unit(tensors, 3)
+    try:
+        params = [normal_bf16(32, 0, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        grads = [normal_bf16(32, 0, 1, i, s.e, 1e-3) for i, s in enumerate(u.specs)]
+        holders = [torch.zeros(g.size + 8, dtype=torch.bfloat16, device="cuda") for g in grads]
+        views = []
+        for i, (h, g) in enumerate(zip(holders, grads)):
+            v = h[1 + 2 * i:1 + 2 * i + g.size]
+            v.copy_(to_dev_bf16(g))
+            views.append(v)
+        check_group_ops(u, params, grads, "odd-storage", dev_grads=views)
+    finally:
+        u.close()
+
+
+def test_reordered_plan_group_ops():
+    tensors = [(512, 256, MODE_128x128), (300, 0, MODE_1x128), (128, 384, MODE_128x128), (64, 640, MODE_1x128)]
+    u = Unit(tensors, 5, order=B.RS_ORDER_SHAPE)
+    try:
+        params = [normal_bf16(33, 0, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        grads = [normal_bf16(33, 0, 1, i, s.e, 1e-3) for i, s in enumerate(u.specs)]
+        check_group_ops(u, params, grads, "by-shape order")
+    finally:
+        u.close()
+
+
+def test_config2_group_ops_full_size():
+    """The benched unit (218 M elements, W = 64): accumulate, scale and scaled copy, whole buffer."""
+    wl = WORKLOADS[2]
+    u = Unit.from_workload(wl)
+    try:
+        say("config 2: generating parameters and gradients on the host")
+        params = gen_params(wl, seed=1)
+        grads = gen_params(wl, seed=2)
+        sizes = [s.e for s in u.specs]
+        base = OD.ragged_pack(params, u.oracle.offsets, u.total)
+        tab = u.table([to_dev_bf16(g) for g in grads])
+        alpha = 1.0 / 64.0
+        say("config 2: pack_scaled")
+        dbuf = torch.full((u.total,), GARBAGE, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        B.rs_pack_scaled(u.plan, tab, alpha, dbuf)
+        torch.cuda.synchronize()
+        first_diff(bits_of(dbuf), OG.pack_scaled(grads, u.oracle.offsets, u.total, alpha), "cfg2 pack_scaled")
+        say("config 2: group_add")
+        dbuf = to_dev_bf16(base)
+        B.rs_group_add(u.plan, tab, alpha, dbuf)
+        torch.cuda.synchronize()
+        first_diff(bits_of(dbuf), OG.group_add(base, grads, u.oracle.offsets, alpha), "cfg2 group_add")
+        say("config 2: group_scale")
+        dbuf = to_dev_bf16(base)
+        B.rs_group_scale(u.plan, alpha, dbuf)
+        torch.cuda.synchronize()
+        first_diff(bits_of(dbuf), OG.group_scale(base, u.oracle.offsets, sizes, alpha), "cfg2 group_scale")
+        say("config 2: group_zero")
+        B.rs_group_zero(u.plan, dbuf)
+        torch.cuda.synchronize()
+        assert not bits_of(dbuf).any()
+    finally:
+        u.close()
+
+
+def test_group_op_argument_errors():
+    u = Unit([(256, 128, MODE_128x128)], 2)
+    try:
+        g = torch.zeros(256 * 128, dtype=torch.bfloat16, device="cuda")
+        tab = u.table([g])
+        dbuf = torch.zeros(u.total + 8, dtype=torch.bfloat16, device="cuda")
+        P = C.c_void_p
+        for alpha in (float("nan"), float("inf")):
+            assert B.raw_call("rs_group_scale", P(u.plan), C.c_float(alpha), P(dbuf.data_ptr()), P(0)) == B.RS_EINVAL
+            assert B.raw_call("rs_group_add", P(u.plan), P(tab), C.c_float(alpha), P(dbuf.data_ptr()), P(0)) == B.RS_EINVAL
+        assert B.raw_call("rs_group_scale", P(u.plan), C.c_float(1.0), P(dbuf.data_ptr() + 2), P(0)) == B.RS_EALIGN
+        assert B.raw_call("rs_group_zero", P(u.plan), P(dbuf.data_ptr() + 2), P(0)) == B.RS_EALIGN
+        assert B.raw_call("rs_group_zero", P(u.plan), P(0), P(0)) == B.RS_EINVAL
+        assert B.raw_call("rs_pack_scaled", P(u.plan), P(0), C.c_float(1.0), P(dbuf.data_ptr()), P(0)) == B.RS_EINVAL
+        assert B.raw_call("rs_group_add", P(0), P(tab), C.c_float(1.0), P(dbuf.data_ptr()), P(0)) == B.RS_EINVAL
+        torch.cuda.synchronize()
+        assert not bits_of(dbuf).any()      # no failing call wrote anything
+    finally:
+        u.close()
