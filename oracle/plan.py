@@ -38,6 +38,7 @@ BLOCK_1x128 = 0      # 1-D: g = 128 elements;  2-D: g = one row (C elements), 1x
 BLOCK_128x128 = 1    # 2-D only: g = 128 rows (128*C elements), 128x128 quant blocks
 BLOCK_WHOLE = 2      # g = e (matrix optimisers: the whole tensor on one device), no quantisation
 BLOCK_EXPLICIT = 3   # g given by the caller, no quantisation
+BLOCK_32x32 = 4      # 2-D: g = 32 rows (Section 6.3, block-wise 8-bit optimiser state); 1-D: g = 128
 
 
 def lcm(a: int, b: int) -> int:
@@ -63,6 +64,8 @@ def size_and_granularity(rows: int, cols: int, mode: int, g_explicit: int = 0) -
         if cols == 0:
             raise ValueError("128x128 blocks need a 2-D tensor")
         g = 128 * cols
+    elif mode == BLOCK_32x32:
+        g = 32 * cols if cols > 0 else 128
     elif mode == BLOCK_WHOLE:
         g = e
     elif mode == BLOCK_EXPLICIT:
