@@ -47,7 +47,9 @@ enum {
   RS_BLOCK_1x128 = 0,    /* 1-D: g = 128 elements; 2-D: g = one row; FP8 blocks are 1x128 runs per row */
   RS_BLOCK_128x128 = 1,  /* 2-D only: g = 128 rows; FP8 blocks are 128x128 tiles, edge tiles partial */
   RS_BLOCK_WHOLE = 2,    /* g = e: the whole tensor on one rank (matrix optimisers, Section 6.3); no FP8 */
-  RS_BLOCK_EXPLICIT = 3  /* g = g_explicit elements; no FP8 */
+  RS_BLOCK_EXPLICIT = 3, /* g = g_explicit elements; no FP8 */
+  RS_BLOCK_32x32 = 4     /* 2-D: g = 32 rows; 1-D: g = 128 elements.  The granularity of the block-wise
+                            8-bit optimiser state (Section 6.3); no FP8 */
 };
 
 /* Tensor orders tried by the planner (Section 5, "heuristic-guided solution": default order,
@@ -201,6 +203,45 @@ int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* st
  * codes: device, world*S uint8, 16-byte aligned; scales: device, all of the unit's scales. */
 int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
               const rs_tensor_table* dst, void* stream);
+
+/* ---- block-wise 8-bit optimiser state on the local shard (Section 6.3, "8-bit Adam") ---------
+ * The two Adam moments of rank's shard are held as 8-bit codes in blocks that never cross a
+ * rank boundary, so a rank updates and re-quantises its state with no communication.
+ * State blocks: 32x32 tiles (edge tiles partial) of every 2-D tensor, which must be in
+ * RS_BLOCK_32x32 or RS_BLOCK_128x128 mode; runs of 128 elements of every 1-D tensor, which must
+ * be in RS_BLOCK_32x32 or RS_BLOCK_1x128 mode; otherwise RS_EUNSUPPORTED.  Blocks are numbered
+ * like FP8 scales: tensor-major in buffer order, block row, block column; a rank owns a
+ * contiguous range.  Codes: first moment m, int8, step a/127 (a = the block's max |m|),
+ * code = rint(m / step); second moment v >= 0, uint8, step a/255; all-zero block: a = 0,
+ * codes 0.  All-zero codes and absmax are the valid initial state. */
+int64_t rs_plan_num_state_blocks(const rs_plan* plan);   /* whole unit; RS_EUNSUPPORTED if undefined */
+/* first state block of every tensor plus the total (n + 1 values; cap >= n + 1) */
+int rs_plan_state_bases(const rs_plan* plan, int64_t* out, int cap);
+int rs_plan_state_range(const rs_plan* plan, int rank, int64_t* lo, int64_t* hi);
+
+typedef struct rs_adam8_hyper {
+  double lr, beta1, beta2, eps, weight_decay;
+  int64_t step;        /* 1 for the first update */
+} rs_adam8_hyper;
+
+/* One AdamW step on rank's shard, one launch.  Per payload element, in fp32, every operation
+ * rounded on its own in this order:
+ *   m_old = code_m * (a_m / 127);   v_old = code_v * (a_v / 255)
+ *   m = beta1 * m_old + (1 - beta1) * g;      v = beta2 * v_old + (1 - beta2) * (g * g)
+ *   w = w * (1 - lr * weight_decay)
+ *   w = w - (lr / bc1) * (m / (sqrt(v) / sqrt(bc2) + eps)),     bc_i = 1 - beta_i^step
+ *   param = bf16(w) (nearest even)
+ * then m and v are quantised again per block.  The constants beta_i, (1 - beta_i), eps, lr / bc1,
+ * sqrt(bc2), (1 - lr * weight_decay) are evaluated in double precision and rounded once to fp32.
+ * grad (in), master (in/out): device fp32, S elements at the region's element offsets;
+ * param_bf16 (out, may be NULL): device bf16, S elements; m_codes / v_codes (in/out): device,
+ * S bytes each; m_absmax / v_absmax (in/out): device fp32, the rank's slice [lo, hi) of the
+ * state-block arrays.  Array bases 16-byte aligned (absmax: 4).  Padding positions of every
+ * array are neither read nor written.  RS_EINVAL unless lr, weight_decay finite, 0 <= beta_i < 1,
+ * eps > 0, step >= 1. */
+int rs_adam8_step(const rs_plan* plan, int rank, const rs_adam8_hyper* hyper, const float* grad,
+                  float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
+                  float* m_absmax, float* v_absmax, void* stream);
 
 /* ---- bandwidth probe: plain 16-byte-vector device copy of `bytes` (multiple of 16) ---------
  * Not part of the method: the measured ceiling the four kernels are held against, and the

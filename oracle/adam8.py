@@ -7,7 +7,8 @@ every block is whole on one device and each device (re)quantises its local shard
 communication.  The paper fixes the block shape and nothing else; the reading taken:
 
   state blocks   2-D tensor whose granularity is a multiple of 32 rows (32x32 or 128x128 mode):
-                 32x32 tiles, edge tiles partial.  1-D tensor: runs of 128 elements.  A rank's
+                 32x32 tiles, edge tiles partial.  1-D tensor of granularity 128 (32x32 or
+                 1x128 mode): runs of 128 elements.  Other tensors have none.  A rank's
                  blocks are contiguous in the flat per-unit block order (tensor-major in
                  buffer order, then block row, then block column).
   code maps      linear absmax (the non-linear code book of the cited 8-bit optimiser paper
@@ -37,16 +38,16 @@ from typing import List, Tuple
 
 import numpy as np
 
-from .plan import BLOCK_128x128, BLOCK_32x32, Plan, TensorSpec, ceil_div
+from .plan import BLOCK_128x128, BLOCK_1x128, BLOCK_32x32, Plan, TensorSpec, ceil_div
 
 F = np.float32
 
 
 def state_grid(spec: TensorSpec) -> Tuple[int, int]:
     """(rows of state blocks, state blocks per row of blocks) of one tensor."""
-    if spec.cols == 0:
+    if spec.cols == 0 and spec.mode in (BLOCK_1x128, BLOCK_32x32):
         return ceil_div(spec.rows, 128), 1
-    if spec.mode in (BLOCK_128x128, BLOCK_32x32):
+    if spec.cols > 0 and spec.mode in (BLOCK_128x128, BLOCK_32x32):
         return ceil_div(spec.rows, 32), ceil_div(spec.cols, 32)
     raise ValueError("no 8-bit state blocks for this sharding granularity")
 

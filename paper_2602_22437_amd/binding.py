@@ -10,7 +10,7 @@ from typing import List, Sequence, Tuple
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libraggedshard.so")
 
-RS_BLOCK_1x128, RS_BLOCK_128x128, RS_BLOCK_WHOLE, RS_BLOCK_EXPLICIT = 0, 1, 2, 3
+RS_BLOCK_1x128, RS_BLOCK_128x128, RS_BLOCK_WHOLE, RS_BLOCK_EXPLICIT, RS_BLOCK_32x32 = 0, 1, 2, 3, 4
 RS_ORDER_DEFAULT, RS_ORDER_BLOCK_SIZE, RS_ORDER_SHAPE, RS_ORDER_BEST = 0, 1, 2, 3
 RS_OK, RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM, RS_EALIGN, RS_EUNSUPPORTED, RS_EHIP, RS_ENOTUPLOADED = (
     0, -1, -2, -3, -4, -5, -6, -7)
@@ -24,6 +24,7 @@ EXPORTS = [
     "rs_quantize", "rs_unpack", "rs_copy_probe", "rs_shard_batch_create", "rs_shard_batch_destroy",
     "rs_quantize_batch", "rs_plan_create_ordered", "rs_plan_order",
     "rs_pack_scaled", "rs_group_add", "rs_group_scale", "rs_group_zero",
+    "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
 ]
 
 
@@ -35,6 +36,11 @@ class rs_tensor_desc(C.Structure):
 class rs_segment(C.Structure):
     _fields_ = [("tensor", C.c_int32), ("reserved", C.c_int32), ("src_off", C.c_int64),
                 ("dst_off", C.c_int64), ("n", C.c_int64)]
+
+
+class rs_adam8_hyper(C.Structure):
+    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double), ("step", C.c_int64)]
 
 
 class RaggedShardError(RuntimeError):
@@ -91,6 +97,11 @@ _lib.rs_shard_batch_destroy.argtypes = [_P]
 _lib.rs_shard_batch_destroy.restype = None
 _lib.rs_quantize_batch.argtypes = [_P, _P, _P]
 _lib.rs_copy_probe.argtypes = [_P, _P, C.c_int64, _P]
+_lib.rs_plan_num_state_blocks.argtypes = [_P]
+_lib.rs_plan_num_state_blocks.restype = C.c_int64
+_lib.rs_plan_state_bases.argtypes = [_P, C.POINTER(C.c_int64), C.c_int]
+_lib.rs_plan_state_range.argtypes = [_P, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+_lib.rs_adam8_step.argtypes = [_P, C.c_int, C.POINTER(rs_adam8_hyper), _P, _P, _P, _P, _P, _P, _P, _P]
 
 
 def _check(code: int, where: str) -> int:
@@ -306,6 +317,33 @@ def rs_quantize_batch(plan, batch, stream=None) -> None:
 
 def rs_unpack(plan, codes, scales, dst_table, stream=None) -> None:
     _check(_lib.rs_unpack(plan, _ptr(codes), _ptr(scales), dst_table, _stream(stream)), "rs_unpack")
+
+
+def rs_plan_num_state_blocks(plan) -> int:
+    return _check(_lib.rs_plan_num_state_blocks(plan), "rs_plan_num_state_blocks")
+
+
+def rs_plan_state_bases(plan) -> List[int]:
+    n = rs_plan_num_tensors(plan)
+    out = (C.c_int64 * (n + 1))()
+    _check(_lib.rs_plan_state_bases(plan, out, n + 1), "rs_plan_state_bases")
+    return list(out)
+
+
+def rs_plan_state_range(plan, rank: int) -> Tuple[int, int]:
+    lo, hi = C.c_int64(), C.c_int64()
+    _check(_lib.rs_plan_state_range(plan, int(rank), C.byref(lo), C.byref(hi)), "rs_plan_state_range")
+    return lo.value, hi.value
+
+
+def rs_adam8_step(plan, rank: int, hyper, grad, master, param_bf16, m_codes, v_codes, m_absmax, v_absmax,
+                  stream=None) -> None:
+    """hyper: (lr, beta1, beta2, eps, weight_decay, step) or an rs_adam8_hyper; param_bf16 may be None."""
+    h = hyper if isinstance(hyper, rs_adam8_hyper) else rs_adam8_hyper(
+        float(hyper[0]), float(hyper[1]), float(hyper[2]), float(hyper[3]), float(hyper[4]), int(hyper[5]))
+    _check(_lib.rs_adam8_step(plan, int(rank), C.byref(h), _ptr(grad), _ptr(master),
+                              0 if param_bf16 is None else _ptr(param_bf16), _ptr(m_codes), _ptr(v_codes),
+                              _ptr(m_absmax), _ptr(v_absmax), _stream(stream)), "rs_adam8_step")
 
 
 def rs_copy_probe(dst, src, nbytes: int, stream=None) -> None:

@@ -1,6 +1,7 @@
 // C ABI of the library: argument checking, plan objects, device tables, kernel launches.
 #include <hip/hip_runtime_api.h>
 
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -47,6 +48,7 @@ void free_device_tables(rs::DeviceTables* d) {
   if (d->items) (void)hipFree(d->items);
   if (d->payload_gran) (void)hipFree(d->payload_gran);
   if (d->padding_gran) (void)hipFree(d->padding_gran);
+  if (d->state_items) (void)hipFree(d->state_items);
   if (have && cur != d->device) (void)hipSetDevice(cur);
   *d = rs::DeviceTables{};
 }
@@ -60,6 +62,21 @@ int64_t scales_in_front(const rs_plan& plan, int64_t x) {
     int64_t granules = (x - h.ell + h.g - 1) / h.g;
     if (granules > h.u) granules = h.u;
     cnt += granules * (h.cols > 0 ? h.nbc : 1);
+  }
+  return cnt;
+}
+
+// Number of optimiser-state blocks in front of buffer position x (a rank boundary: it falls
+// between rows of state tiles, or between runs of 128).
+int64_t state_blocks_in_front(const rs_plan& plan, int64_t x) {
+  int64_t cnt = 0;
+  for (const rs::TensorHost& h : plan.t) {
+    if (!h.state || x <= h.ell) continue;
+    const int64_t have = x - h.ell < h.e ? x - h.ell : h.e;
+    if (h.cols > 0)
+      cnt += (have / h.cols + 31) / 32 * h.sbc;
+    else
+      cnt += (have + 127) / 128;
   }
   return cnt;
 }
@@ -141,19 +158,27 @@ int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int al
       delete p;
       return RS_EINVAL;
     }
-    int64_t sb = 0;
+    int64_t sb = 0, stb = 0;
     p->all_quant = true;
+    p->all_state = true;
     for (size_t i = 0; i < p->t.size(); ++i) {
       p->t[i].ell = starts[i];
       p->t[i].scale_base = sb;
       sb += p->t[i].nbr * p->t[i].nbc;
+      p->t[i].state_base = stb;
+      stb += p->t[i].sbr * p->t[i].sbc;
       p->payload += p->t[i].e;
       p->all_quant = p->all_quant && p->t[i].quant;
+      p->all_state = p->all_state && p->t[i].state;
     }
     p->num_scales = sb;
+    p->num_state_blocks = stb;
     p->scale_begin.resize(size_t(world) + 1);
-    for (int k = 0; k <= world; ++k)
+    p->state_begin.assign(size_t(world) + 1, 0);
+    for (int k = 0; k <= world; ++k) {
       p->scale_begin[size_t(k)] = scales_in_front(*p, int64_t(k) * p->S);
+      if (p->all_state) p->state_begin[size_t(k)] = state_blocks_in_front(*p, int64_t(k) * p->S);
+    }
     *out = p;
     return RS_OK;
   } catch (const std::bad_alloc&) {
@@ -225,6 +250,27 @@ int rs_plan_scale_range(const rs_plan* plan, int rank, int64_t* lo, int64_t* hi)
   return RS_OK;
 }
 
+int64_t rs_plan_num_state_blocks(const rs_plan* plan) {
+  if (!plan) return RS_EINVAL;
+  return plan->all_state ? plan->num_state_blocks : RS_EUNSUPPORTED;
+}
+
+int rs_plan_state_bases(const rs_plan* plan, int64_t* out, int cap) {
+  if (!plan || !out || cap < int(plan->t.size()) + 1) return RS_EINVAL;
+  if (!plan->all_state) return RS_EUNSUPPORTED;
+  for (size_t j = 0; j < plan->t.size(); ++j) out[size_t(plan->orig[j])] = plan->t[j].state_base;
+  out[plan->t.size()] = plan->num_state_blocks;
+  return RS_OK;
+}
+
+int rs_plan_state_range(const rs_plan* plan, int rank, int64_t* lo, int64_t* hi) {
+  if (!plan || !lo || !hi || rank < 0 || rank >= plan->world) return RS_EINVAL;
+  if (!plan->all_state) return RS_EUNSUPPORTED;
+  *lo = plan->state_begin[size_t(rank)];
+  *hi = plan->state_begin[size_t(rank) + 1];
+  return RS_OK;
+}
+
 int rs_plan_rank_segments(const rs_plan* plan, int rank, rs_segment* out, int cap) {
   if (!plan || rank < 0 || rank >= plan->world || cap < 0 || (cap > 0 && !out)) return RS_EINVAL;
   const int64_t lo = int64_t(rank) * plan->S, hi = lo + plan->S;
@@ -258,7 +304,8 @@ int rs_plan_upload(rs_plan* plan, int device) {
   if (cur != device && hipSetDevice(device) != hipSuccess) return RS_EHIP;
   int rc = RS_OK;
   try {
-    rs::build_host_tables(plan->t, plan->world, plan->S, plan->all_quant, &plan->host);
+    rs::build_host_tables(plan->t, plan->world, plan->S, plan->all_quant, plan->all_state,
+                          &plan->host);
     rs::DeviceTables d;
     d.device = device;
     rc = upload(plan->host.tensors, &d.tensors);
@@ -266,6 +313,7 @@ int rs_plan_upload(rs_plan* plan, int device) {
     if (rc == RS_OK) rc = upload(plan->host.items, &d.items);
     if (rc == RS_OK) rc = upload(plan->host.payload_gran, &d.payload_gran);
     if (rc == RS_OK) rc = upload(plan->host.padding_gran, &d.padding_gran);
+    if (rc == RS_OK) rc = upload(plan->host.state_items, &d.state_items);
     if (rc == RS_OK) {
       plan->dev = d;
     } else {
@@ -276,6 +324,7 @@ int rs_plan_upload(rs_plan* plan, int device) {
     std::vector<rs::Item>().swap(plan->host.items);
     std::vector<int32_t>().swap(plan->host.payload_gran);
     std::vector<int32_t>().swap(plan->host.padding_gran);
+    std::vector<rs::Item>().swap(plan->host.state_items);
   } catch (const std::bad_alloc&) {
     rc = RS_ENOMEM;
   }
@@ -395,6 +444,44 @@ int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes
   }
   return rs::launch_block_quant(plan->dev, first, count, shard, codes, scales, nullptr, 0, elem_base,
                                 scale_off, static_cast<hipStream_t>(stream));
+}
+
+int rs_adam8_step(const rs_plan* plan, int rank, const rs_adam8_hyper* hyper, const float* grad,
+                  float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
+                  float* m_absmax, float* v_absmax, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_state) return RS_EUNSUPPORTED;
+  if (!hyper || !grad || !master || !m_codes || !v_codes || rank < 0 || rank >= plan->world)
+    return RS_EINVAL;
+  const int64_t nblk = plan->state_begin[size_t(rank) + 1] - plan->state_begin[size_t(rank)];
+  if (nblk > 0 && (!m_absmax || !v_absmax)) return RS_EINVAL;
+  const rs_adam8_hyper& h = *hyper;
+  if (!std::isfinite(h.lr) || !std::isfinite(h.weight_decay) || !(h.beta1 >= 0.0 && h.beta1 < 1.0) ||
+      !(h.beta2 >= 0.0 && h.beta2 < 1.0) || !(h.eps > 0.0) || !std::isfinite(h.eps) || h.step < 1)
+    return RS_EINVAL;
+  if (!aligned16(grad) || !aligned16(master) || !aligned16(param_bf16) || !aligned16(m_codes) ||
+      !aligned16(v_codes) || (reinterpret_cast<uintptr_t>(m_absmax) & 3) ||
+      (reinterpret_cast<uintptr_t>(v_absmax) & 3))
+    return RS_EALIGN;
+  // the step's constants: double precision, rounded once to fp32
+  const double bc1 = 1.0 - std::pow(h.beta1, double(h.step));
+  const double bc2 = 1.0 - std::pow(h.beta2, double(h.step));
+  rs::Adam8Consts c;
+  c.beta1 = float(h.beta1);
+  c.beta2 = float(h.beta2);
+  c.one_minus_beta1 = float(1.0 - h.beta1);
+  c.one_minus_beta2 = float(1.0 - h.beta2);
+  c.eps = float(h.eps);
+  c.step_size = float(h.lr / bc1);
+  c.bc2_sqrt = float(std::sqrt(bc2));
+  c.decay = float(1.0 - h.lr * h.weight_decay);
+  if (!std::isfinite(c.step_size) || !(c.bc2_sqrt > 0.0f)) return RS_EINVAL;
+  const std::vector<int64_t>& ib = plan->host.state_item_begin;
+  return rs::launch_adam8_step(plan->dev, ib[size_t(rank)], ib[size_t(rank) + 1] - ib[size_t(rank)],
+                               grad, master, param_bf16, m_codes, v_codes, m_absmax, v_absmax,
+                               int64_t(rank) * plan->S, plan->state_begin[size_t(rank)], c,
+                               static_cast<hipStream_t>(stream));
 }
 
 int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* const* shards,

@@ -87,7 +87,7 @@ int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>
     const rs_tensor_desc& d = descs[i];
     if (d.rows <= 0 || d.cols < 0 || d.reserved != 0) return RS_EINVAL;
     if (d.cols > 0 && d.rows > kLimit / d.cols) return RS_EOVERFLOW;
-    if (d.rows >= kLimit || d.cols >= (int64_t(1) << 40)) return RS_EOVERFLOW;
+    if (d.rows >= kLimit || d.cols >= (int64_t(1) << 35)) return RS_EOVERFLOW;  // block counts per row fit 32 bits
     TensorHost h{};
     h.rows = d.rows;
     h.cols = d.cols;
@@ -107,6 +107,9 @@ int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>
         h.nbc = (d.cols + 127) / 128;
         h.nbr = (d.rows + 127) / 128;
         break;
+      case RS_BLOCK_32x32:
+        h.g = d.cols > 0 ? 32 * d.cols : 128;
+        break;
       case RS_BLOCK_WHOLE:
         h.g = h.e;
         break;
@@ -116,6 +119,17 @@ int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>
         break;
       default:
         return RS_EINVAL;
+    }
+    // 8-bit optimiser-state blocks: 32x32 tiles where the granularity is whole rows of such
+    // tiles, runs of 128 on 1-D tensors whose granularity is 128
+    if (d.cols > 0 && (d.block_mode == RS_BLOCK_32x32 || d.block_mode == RS_BLOCK_128x128)) {
+      h.state = true;
+      h.sbr = (d.rows + 31) / 32;
+      h.sbc = (d.cols + 31) / 32;
+    } else if (d.cols == 0 && (d.block_mode == RS_BLOCK_32x32 || d.block_mode == RS_BLOCK_1x128)) {
+      h.state = true;
+      h.sbr = (d.rows + 127) / 128;
+      h.sbc = 1;
     }
     h.u = (h.e + h.g - 1) / h.g;
     sum += h.e;

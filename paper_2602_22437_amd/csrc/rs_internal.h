@@ -13,6 +13,10 @@ constexpr int kGranule = 2048;
 // A quantisation work item covers at most this many "row slots" of 128 elements:
 // one 128x128 tile, or 128 consecutive 1x128 blocks.
 constexpr int kItemSlots = 128;
+// Optimiser-state work items: 32 rows x kStateCols columns of a 2-D tensor (one row of
+// kStateCols / 32 state tiles), or kStateRuns consecutive 128-element runs of a 1-D tensor.
+constexpr int kStateCols = 256;
+constexpr int kStateRuns = 64;
 // A zero-fill item clears at most this many code bytes.
 constexpr int kFillElems = 32768;
 
@@ -20,10 +24,13 @@ enum : int32_t {
   kFlagTile = 1,     // 128x128 tiles (else 1x128 runs)
   kFlagQuant = 2,    // tensor has FP8 blocks
   kFlagVec = 4,      // every row slot starts 8-element aligned in the buffer (16-byte bf16 vectors)
-  kFlagContig = 8    // 1x128 blocks are back to back in memory (1-D, or C % 128 == 0)
+  kFlagContig = 8,   // 1x128 blocks are back to back in memory (1-D, or C % 128 == 0)
+  kFlagState = 16,   // tensor has 8-bit optimiser-state blocks
+  kFlagVec4 = 32,    // every row starts 4-element aligned in the buffer (16-byte fp32 vectors)
+  kFlagOneD = 64     // 1-D tensor (state blocks are runs of 128 elements)
 };
 
-// Per-tensor record on the device (48 bytes).
+// Per-tensor record on the device (64 bytes).
 struct TensorDev {
   int64_t ell;         // l_t: first element in the buffer
   int64_t e;           // elements
@@ -32,13 +39,17 @@ struct TensorDev {
   int64_t cols;        // C (n for 1-D tensors)
   int32_t nbc;         // quantisation blocks per row of blocks
   int32_t flags;
+  int64_t state_base;  // first optimiser-state block
+  int32_t sbc;         // state blocks per row of state blocks (2-D)
+  int32_t reserved;
 };
 
-// One workgroup's worth of block_quant / dequant_unpack work (16 bytes).
+// One workgroup's worth of block_quant or optimiser-state work (16 bytes).
 struct Item {
   int64_t first;   // tile: block row br;  runs: first block index;  fill: buffer element offset
   int32_t tensor;  // -1 marks a zero-fill item
   int32_t count;   // tile: block column bc;  runs: blocks in this item (<= kItemSlots);  fill: elements
+                   // state items: first = row of 32x32 tiles / first run; count = column strip / runs
 };
 
 struct TensorHost {
@@ -49,6 +60,9 @@ struct TensorHost {
   int64_t nbr, nbc;    // FP8 block grid (0 x 0 when not quantised)
   int64_t scale_base;
   bool quant;
+  bool state;          // 8-bit optimiser-state blocks are defined (and whole on a rank)
+  int64_t sbr, sbc;    // state block grid: 32x32 tiles, or (runs of 128) x 1 for 1-D
+  int64_t state_base;
 };
 
 struct HostTables {
@@ -62,6 +76,8 @@ struct HostTables {
   std::vector<int32_t> payload_gran;
   std::vector<int32_t> padding_gran;   // the rest: granules ragged_pack only has to zero
   int64_t n_payload_gran = 0, n_padding_gran = 0;
+  std::vector<Item> state_items;            // rank-major; empty unless every tensor has state blocks
+  std::vector<int64_t> state_item_begin;    // world + 1
 };
 
 struct DeviceTables {
@@ -71,6 +87,7 @@ struct DeviceTables {
   Item* items = nullptr;
   int32_t* payload_gran = nullptr;
   int32_t* padding_gran = nullptr;
+  Item* state_items = nullptr;
 };
 
 // ---- planner (planner.cpp) ----
@@ -84,7 +101,7 @@ void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int3
 
 // ---- derived tables (tables.cpp) ----
 void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t S, bool all_quant,
-                       HostTables* out);
+                       bool all_state, HostTables* out);
 
 }  // namespace rs
 
@@ -94,6 +111,9 @@ struct rs_plan {
   int64_t world = 0, g_coll = 0, A = 0, S = 0, payload = 0, num_scales = 0;
   bool all_quant = false;
   std::vector<int64_t> scale_begin;  // world + 1: first scale of every rank
+  bool all_state = false;            // every tensor has 8-bit optimiser-state blocks
+  int64_t num_state_blocks = 0;
+  std::vector<int64_t> state_begin;  // world + 1: first state block of every rank
   rs::HostTables host;
   rs::DeviceTables dev;
 };

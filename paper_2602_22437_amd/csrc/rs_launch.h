@@ -20,6 +20,14 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
 int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
                           int64_t gpr, hipStream_t st);
+// fp32 constants of one 8-bit Adam step
+struct Adam8Consts {
+  float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_size, bc2_sqrt, decay;
+};
+int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_count, const float* grad,
+                      float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
+                      float* m_absmax, float* v_absmax, int64_t elem_base, int64_t state_off,
+                      const Adam8Consts& c, hipStream_t st);
 int launch_copy_probe(void* dst, const void* src, int64_t bytes, hipStream_t st);
 
 }  // namespace rs

@@ -22,7 +22,7 @@ void add_fill(std::vector<Item>* items, int64_t from, int64_t to) {
 }  // namespace
 
 void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t S, bool all_quant,
-                       HostTables* out) {
+                       bool all_state, HostTables* out) {
   const int n = int(t.size());
   out->tensors.resize(n);
   for (int i = 0; i < n; ++i) {
@@ -40,7 +40,12 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
     const bool one_d = h.cols == 0;
     if (h.ell % 8 == 0 && (one_d || d.cols % 8 == 0)) f |= kFlagVec;
     if (one_d || d.cols % 128 == 0) f |= kFlagContig;
+    if (h.state) f |= kFlagState;
+    if (h.ell % 4 == 0 && (one_d || d.cols % 4 == 0)) f |= kFlagVec4;
+    if (one_d) f |= kFlagOneD;
     d.flags = f;
+    d.state_base = h.state_base;
+    d.sbc = int32_t(h.sbc);
     out->tensors[i] = d;
   }
 
@@ -74,6 +79,45 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
   }
   out->n_payload_gran = int64_t(out->payload_gran.size());
   out->n_padding_gran = int64_t(out->padding_gran.size());
+
+  // optimiser-state work items, rank by rank in buffer order: a rank's part of a tensor is a
+  // run of whole granules, hence of whole rows of state tiles (or whole runs)
+  out->state_items.clear();
+  out->state_item_begin.assign(size_t(world + 1), 0);
+  if (all_state) {
+    int first = 0;
+    for (int64_t k = 0; k < world; ++k) {
+      out->state_item_begin[size_t(k)] = int64_t(out->state_items.size());
+      const int64_t lo = k * S, hi = lo + S;
+      while (first < n && t[first].ell + t[first].e <= lo) ++first;
+      for (int i = first; i < n && t[i].ell < hi; ++i) {
+        const TensorHost& h = t[i];
+        const int64_t a = std::max(h.ell, lo) - h.ell, b = std::min(h.ell + h.e, hi) - h.ell;
+        if (h.cols > 0) {
+          const int64_t br_a = a / h.cols / 32, br_b = (b / h.cols + 31) / 32;
+          const int64_t strips = (h.cols + kStateCols - 1) / kStateCols;
+          for (int64_t br = br_a; br < br_b; ++br)
+            for (int64_t cs = 0; cs < strips; ++cs) {
+              Item it{};
+              it.first = br;
+              it.tensor = i;
+              it.count = int32_t(cs);
+              out->state_items.push_back(it);
+            }
+        } else {
+          const int64_t q_a = a / 128, q_b = (b + 127) / 128;
+          for (int64_t q = q_a; q < q_b; q += kStateRuns) {
+            Item it{};
+            it.first = q;
+            it.tensor = i;
+            it.count = int32_t(std::min<int64_t>(kStateRuns, q_b - q));
+            out->state_items.push_back(it);
+          }
+        }
+      }
+    }
+    out->state_item_begin[size_t(world)] = int64_t(out->state_items.size());
+  }
 
   // quantisation work items, rank by rank in buffer order, zero-fill items for every gap
   out->items.clear();

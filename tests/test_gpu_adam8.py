@@ -1,0 +1,170 @@
+"""GPU parity of rs_adam8_step (AdamW on the local shard with block-wise 8-bit moments,
+Section 6.3) against the CPU oracle, bit for bit on every output (master weights, bf16
+parameters, both code arrays, both absmax arrays), through the C ABI, over several consecutive
+steps so that the quantised state feeds back."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import adam8 as OA
+from paper_2602_22437_amd import binding as B
+from workloads import MODE_128x128, MODE_1x128, MODE_32x32, MODE_WHOLE, WORKLOADS
+
+from gpu_util import Unit, say
+
+pytestmark = pytest.mark.gpu
+
+W_SENTINEL, P_SENTINEL, M_SENTINEL, V_SENTINEL = np.float32(123.0), np.uint16(0x4300), np.int8(0x55), np.uint8(0xAA)
+
+
+def diff(got, want, what):
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero(got != want)
+        raise AssertionError(f"{what}: {bad.size} differ, first at {bad[:6]}: got {got[bad[:6]]} want {want[bad[:6]]}")
+
+
+def run_steps(u: Unit, rank: int, seed: int, hypers, label, grad_sigma=1e-3, with_param=True):
+    """Zero state, then one step per entry of `hypers`, each compared with the oracle."""
+    S = u.S
+    rng = np.random.default_rng(seed)
+    pay = np.zeros(S, dtype=bool)
+    for _, _, d, n in u.oracle.rank_segments(rank):
+        pay[d:d + n] = True
+    lo, hi = OA.state_range(u.oracle, rank)
+    assert B.rs_plan_state_range(u.plan, rank) == (lo, hi)
+    nb = hi - lo
+    w = (rng.standard_normal(S) * 0.02).astype(np.float32)
+    w[~pay] = W_SENTINEL
+    pb = np.full(S, P_SENTINEL, np.uint16)
+    mc = np.zeros(S, np.int8)
+    vc = np.zeros(S, np.uint8)
+    mc[~pay], vc[~pay] = M_SENTINEL, V_SENTINEL
+    am, av = np.zeros(nb, np.float32), np.zeros(nb, np.float32)
+    d_w = torch.from_numpy(w).cuda()
+    d_p = torch.from_numpy(pb.view(np.int16)).cuda()
+    d_mc, d_vc = torch.from_numpy(mc).cuda(), torch.from_numpy(vc).cuda()
+    d_am = torch.from_numpy(np.concatenate([am, [7.0]]).astype(np.float32)).cuda()   # one guard word behind
+    d_av = torch.from_numpy(np.concatenate([av, [7.0]]).astype(np.float32)).cuda()
+    for i, h in enumerate(hypers):
+        g = (rng.standard_normal(S) * grad_sigma).astype(np.float32)
+        if i == 1:
+            g[pay & (rng.random(S) < 0.01)] = 0.0
+        g[~pay] = np.nan                                  # the kernel must not look at padding
+        say(f"adam8 {label}: rank={rank} step={h.step} S={S} blocks={nb}")
+        B.rs_adam8_step(u.plan, rank, (h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step),
+                        torch.from_numpy(g).cuda(), d_w, d_p if with_param else None, d_mc, d_vc, d_am, d_av)
+        torch.cuda.synchronize()
+        w, pb_new, mc, vc, am, av = OA.adam8_step_shard(u.oracle, rank, g, w, pb, mc, vc, am, av, h)
+        if with_param:
+            pb = pb_new
+        diff(d_w.cpu().numpy().view(np.uint32), w.view(np.uint32), f"master {label} step {h.step}")
+        diff(d_p.cpu().numpy().view(np.uint16), pb, f"param {label} step {h.step}")
+        diff(d_am.cpu().numpy()[:nb].view(np.uint32), am.view(np.uint32), f"m absmax {label} step {h.step}")
+        diff(d_av.cpu().numpy()[:nb].view(np.uint32), av.view(np.uint32), f"v absmax {label} step {h.step}")
+        diff(d_mc.cpu().numpy(), mc, f"m codes {label} step {h.step}")
+        diff(d_vc.cpu().numpy(), vc, f"v codes {label} step {h.step}")
+        assert d_am.cpu().numpy()[nb] == 7.0 and d_av.cpu().numpy()[nb] == 7.0
+    # padding untouched in every array
+    assert np.all(w[~pay] == W_SENTINEL) and np.all(mc[~pay] == M_SENTINEL) and np.all(vc[~pay] == V_SENTINEL)
+    if nb:
+        assert am.max() > 0 and av.max() > 0 and np.abs(mc[pay]).max() == 127 and vc[pay].max() == 255
+
+
+def hypers(n, lr=2e-3, wd=0.1):
+    return [OA.Hyper(lr=lr, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=wd, step=s) for s in range(1, n + 1)]
+
+
+UNITS = [
+    # 32-row granularity (the paper's 8-bit Adam set-up): full and partial tiles, several column strips
+    ([(256, 384, MODE_32x32), (384, 0, MODE_32x32), (96, 64, MODE_32x32), (70, 40, MODE_32x32),
+      (1000, 0, MODE_32x32)], 4, 0),
+    # 128-row granularity shared with FP8 blocks, 1-D tensors in 1x128 mode, odd pitches (130, 30)
+    ([(256, 128, MODE_128x128), (300, 0, MODE_1x128), (257, 130, MODE_128x128), (33, 30, MODE_128x128)], 3, 0),
+    # element-aligned tensor starts (A = 1) and a pitch that is not a multiple of 4: scalar path
+    ([(64, 36, MODE_32x32), (100, 0, MODE_32x32), (37, 35, MODE_32x32)], 3, 1),
+    ([(64, 64, MODE_32x32)], 5, 0),                      # most ranks empty
+    ([(64, 1100, MODE_32x32), (16384, 0, MODE_32x32)], 2, 0),   # 5 column strips, the last partial; many runs
+]
+
+
+@pytest.mark.parametrize("case", range(len(UNITS)))
+def test_adam8_units_every_rank(case):
+    tensors, world, A = UNITS[case]
+    u = Unit(tensors, world, 16, 1, A)
+    try:
+        assert B.rs_plan_num_state_blocks(u.plan) == OA.state_bases(u.oracle)[-1]
+        assert B.rs_plan_state_bases(u.plan) == OA.state_bases(u.oracle)
+        for k in range(world):
+            run_steps(u, k, 100 * case + k, hypers(3), f"unit{case}")
+    finally:
+        u.close()
+
+
+def test_adam8_without_param_output_and_no_decay():
+    u = Unit(UNITS[0][0], UNITS[0][1])
+    try:
+        run_steps(u, 1, 77, hypers(2, lr=1e-3, wd=0.0), "no-param", with_param=False)
+    finally:
+        u.close()
+
+
+def test_adam8_llama_layer_shard_at_32_row_granularity():
+    """Config-2 shapes with the 32-row granularity of the paper's 8-bit Adam runs, FSDP size 64:
+    a full-size shard (the launch shape the bench times)."""
+    wl = WORKLOADS[2]
+    tensors = [(t.rows, t.cols, MODE_32x32) for t in wl.tensors]
+    u = Unit(tensors, wl.world, wl.align_bytes, wl.min_itemsize)
+    try:
+        for k in (0, 37):
+            run_steps(u, k, 500 + k, hypers(2, lr=3e-4), "llama-32row")
+    finally:
+        u.close()
+
+
+def test_adam8_on_the_fp8_plan_of_config2():
+    """The same optimiser step on the 128x128 FP8 plan of config 2 (32x32 state tiles nest in it)."""
+    u = Unit.from_workload(WORKLOADS[2])
+    try:
+        run_steps(u, 63, 900, hypers(2, lr=3e-4), "cfg2-fp8-plan")
+    finally:
+        u.close()
+
+
+def test_adam8_errors():
+    P = C.c_void_p
+    u = Unit([(64, 64, MODE_32x32)], 2)
+    un = Unit([(64, 64, MODE_WHOLE)], 2, 16, 2)
+    try:
+        S = u.S
+        g = torch.zeros(S + 4, dtype=torch.float32, device="cuda")
+        w = torch.zeros(S + 4, dtype=torch.float32, device="cuda")
+        p = torch.zeros(S + 8, dtype=torch.bfloat16, device="cuda")
+        mc = torch.zeros(S + 16, dtype=torch.int8, device="cuda")
+        vc = torch.zeros(S + 16, dtype=torch.uint8, device="cuda")
+        am = torch.zeros(8, dtype=torch.float32, device="cuda")
+        av = torch.zeros(8, dtype=torch.float32, device="cuda")
+
+        def call(plan, rank, h, gp=None, wp=None):
+            hs = B.rs_adam8_hyper(*h)
+            return B.raw_call("rs_adam8_step", P(plan), C.c_int(rank), C.byref(hs), P(gp or g.data_ptr()),
+                              P(wp or w.data_ptr()), P(p.data_ptr()), P(mc.data_ptr()), P(vc.data_ptr()),
+                              P(am.data_ptr()), P(av.data_ptr()), P(0))
+
+        ok = (1e-3, 0.9, 0.95, 1e-8, 0.0, 1)
+        assert call(u.plan, 0, ok) == B.RS_OK
+        assert call(u.plan, 2, ok) == B.RS_EINVAL
+        assert call(u.plan, 0, (1e-3, 1.0, 0.95, 1e-8, 0.0, 1)) == B.RS_EINVAL
+        assert call(u.plan, 0, (1e-3, 0.9, -0.1, 1e-8, 0.0, 1)) == B.RS_EINVAL
+        assert call(u.plan, 0, (1e-3, 0.9, 0.95, 0.0, 0.0, 1)) == B.RS_EINVAL
+        assert call(u.plan, 0, (1e-3, 0.9, 0.95, 1e-8, 0.0, 0)) == B.RS_EINVAL
+        assert call(u.plan, 0, (float("nan"), 0.9, 0.95, 1e-8, 0.0, 1)) == B.RS_EINVAL
+        assert call(u.plan, 0, ok, gp=g.data_ptr() + 4) == B.RS_EALIGN
+        assert call(u.plan, 0, ok, wp=w.data_ptr() + 8) == B.RS_EALIGN
+        assert call(un.plan, 0, ok) == B.RS_EUNSUPPORTED
+        assert B.raw_call("rs_plan_num_state_blocks", P(un.plan)) == B.RS_EUNSUPPORTED
+        torch.cuda.synchronize()
+    finally:
+        u.close()
+        un.close()

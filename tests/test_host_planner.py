@@ -204,3 +204,44 @@ def test_padding_study_reproduces_the_papers_qualitative_claims():
         assert all(res[128][w][0] >= res[1][w][0] for w in worlds)
         assert res[128][1024][0] > res[128][8][0]
         assert all(res[g][w][1] < 0.3 for g in res for w in worlds)
+
+
+def test_state_block_layout_matches_oracle():
+    """32-row granularity (Section 6.3) and the 8-bit state-block numbering: library == oracle on
+    random units whose tensors all have state blocks; other units report RS_EUNSUPPORTED."""
+    from oracle import adam8 as OA
+    rnd = random.Random(29)
+    for _ in range(200):
+        tensors = []
+        for _ in range(rnd.randint(1, 6)):
+            kind = rnd.random()
+            if kind < 0.25:
+                tensors.append((rnd.randint(1, 1500), 0, rnd.choice([B.RS_BLOCK_32x32, B.RS_BLOCK_1x128])))
+            elif kind < 0.8:
+                tensors.append((rnd.randint(1, 300), rnd.choice([8, 30, 32, 40, 100, 256, 300, 1100]), B.RS_BLOCK_32x32))
+            else:
+                tensors.append((rnd.randint(1, 300), rnd.choice([24, 128, 130, 256]), B.RS_BLOCK_128x128))
+        world = rnd.choice([1, 2, 3, 4, 7, 16, 33])
+        specs = [P.TensorSpec(*t) for t in tensors]
+        want = P.make_plan(specs, world, 16, 1)
+        plan = B.rs_plan_create(tensors, world, 16, 1)
+        try:
+            assert B.rs_plan_shard_elems(plan) == want.S and B.rs_plan_offsets(plan) == want.offsets
+            assert B.rs_plan_state_bases(plan) == OA.state_bases(want)
+            assert B.rs_plan_num_state_blocks(plan) == OA.state_bases(want)[-1]
+            for k in range(world):
+                assert B.rs_plan_state_range(plan, k) == OA.state_range(want, k)
+        finally:
+            B.rs_plan_destroy(plan)
+    for bad in ([(64, 256, B.RS_BLOCK_1x128)], [(64, 64, B.RS_BLOCK_WHOLE)], [(512, 0, B.RS_BLOCK_EXPLICIT, 128)]):
+        plan = B.rs_plan_create(bad, 2, 16, 1)
+        try:
+            with pytest.raises(B.RaggedShardError) as e:
+                B.rs_plan_num_state_blocks(plan)
+            assert e.value.code == B.RS_EUNSUPPORTED
+            with pytest.raises(B.RaggedShardError):
+                B.rs_plan_state_range(plan, 0)
+        finally:
+            B.rs_plan_destroy(plan)
+    with pytest.raises(B.RaggedShardError):
+        B.rs_plan_create([(64, 0, B.RS_BLOCK_128x128)], 2, 16, 1)

@@ -10,7 +10,8 @@ Shapes stand in for the public model architectures the paper evaluates (Section 
 LLaMA-3, GPT-OSS-120B, DeepSeek-V3); values are N(0, sigma) rounded to bf16, gradient
 partials N(0, 1e-3).  No real weights or datasets are used.
 
-Block modes (same integers as the C ABI): 0 = 1x128, 1 = 128x128, 2 = whole tensor.
+Block modes (same integers as the C ABI): 0 = 1x128, 1 = 128x128, 2 = whole tensor,
+3 = explicit granularity, 4 = 32x32 (8-bit optimiser state).
 """
 from __future__ import annotations
 
@@ -20,7 +21,7 @@ from typing import List, Tuple
 import numpy as np
 import torch
 
-MODE_1x128, MODE_128x128, MODE_WHOLE = 0, 1, 2
+MODE_1x128, MODE_128x128, MODE_WHOLE, MODE_EXPLICIT, MODE_32x32 = 0, 1, 2, 3, 4
 
 ROLE_PARAM, ROLE_PARTIAL, ROLE_MISC = 0, 1, 2
 
