@@ -266,6 +266,58 @@ def main():
             "ms": round(qa_ms, 4), "bytes": qa_bytes, "GBps": round(qa_bytes / qa_ms / 1e6, 1),
             "frac_of_peak": round(qa_bytes / qa_ms / 1e6 / HBM_PEAK_GBPS, 4),
             "note": "same kernel over all W shards of a unit in one launch; not part of the timed step"}
+    # group-level operators and the 8-bit Adam step (widening beyond the four timed kernels)
+    group_bytes = {"pack_scaled": 2 * E + 2 * total, "group_add": 6 * E, "group_scale": 4 * E,
+                   "group_zero": 2 * total}
+    group_calls = {
+        "pack_scaled": lambda i=0: B.rs_pack_scaled(plan, U[i % units]["src_tab"], 1.0 / W, U[i % units]["dbuf"], stream),
+        "group_add": lambda i=0: B.rs_group_add(plan, U[i % units]["src_tab"], 1.0, U[i % units]["dbuf"], stream),
+        "group_scale": lambda i=0: B.rs_group_scale(plan, 0.999, U[i % units]["dbuf"], stream),
+        "group_zero": lambda i=0: B.rs_group_zero(plan, U[i % units]["dbuf"], stream),
+    }
+    for name in ("group_add", "group_scale", "pack_scaled", "group_zero"):   # ends with the buffer zeroed, then repacked
+        ms = timed(group_calls[name], max(units, 8))
+        kernels[name] = {"ms": round(ms, 4), "bytes": group_bytes[name], "GBps": round(group_bytes[name] / ms / 1e6, 1),
+                         "frac_of_peak": round(group_bytes[name] / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                         "note": "group-level DBuffer operator; not part of the timed step"}
+    for d in U:
+        B.rs_pack(plan, d["src_tab"], d["dbuf"], stream)
+    try:
+        slo, shi = B.rs_plan_state_range(plan, rank)
+    except B.RaggedShardError:
+        slo = shi = None
+    if slo is not None:
+        for d in U:
+            d["master"] = torch.empty(S, dtype=torch.float32, device="cuda").normal_(0, wl.sigma, generator=gen)
+            d["param"] = torch.empty(S, dtype=torch.bfloat16, device="cuda")
+            d["m_codes"] = torch.zeros(S, dtype=torch.int8, device="cuda")
+            d["v_codes"] = torch.zeros(S, dtype=torch.uint8, device="cuda")
+            d["m_absmax"] = torch.zeros(max(shi - slo, 1), dtype=torch.float32, device="cuda")
+            d["v_absmax"] = torch.zeros(max(shi - slo, 1), dtype=torch.float32, device="cuda")
+        hyper = B.rs_adam8_hyper(3e-4, 0.9, 0.95, 1e-8, 0.1, 2)
+
+        def adam(i=0):
+            d = U[i % units]
+            B.rs_adam8_step(plan, rank, hyper, d["out"], d["master"], d["param"], d["m_codes"], d["v_codes"],
+                            d["m_absmax"], d["v_absmax"], stream)
+        for i in range(units):       # a first step so that the timed ones start from a non-trivial state
+            adam(i)
+        a_bytes = 18 * payload_r + 16 * (shi - slo)
+        a_ms = timed(adam, max(units, 8))
+        if units > 1:
+            ab = B.rs_adam8_batch_create(plan, rank, *[[d[k] for d in U] for k in
+                                                       ("out", "master", "param", "m_codes", "v_codes", "m_absmax", "v_absmax")])
+            ab_ms = timed(lambda i=0: B.rs_adam8_step_batch(plan, ab, hyper, stream), 8)
+            B.rs_adam8_batch_destroy(ab)
+            kernels["adam8_step_batch"] = {
+                "ms": round(ab_ms, 4), "bytes": units * a_bytes, "GBps": round(units * a_bytes / ab_ms / 1e6, 1),
+                "frac_of_peak": round(units * a_bytes / ab_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                "note": f"the same step over rank {rank}'s shard of all {units} units in one launch"}
+        kernels["adam8_step"] = {
+            "ms": round(a_ms, 4), "bytes": a_bytes, "GBps": round(a_bytes / a_ms / 1e6, 1),
+            "frac_of_peak": round(a_bytes / a_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "note": f"AdamW with 8-bit 32x32-block moments on rank {rank}'s shard (fp32 grad and master, bf16 "
+                    "param out, codes in place: 18 B per element); not part of the timed step"}
     nbytes = total * 2
     probe_dst = [d["dbuf"] for d in U[1:]] + [torch.empty(total, dtype=torch.bfloat16, device="cuda")]
     cp_ms = timed(lambda i=0: B.rs_copy_probe(probe_dst[i % units], U[i % units]["dbuf"], nbytes, stream),

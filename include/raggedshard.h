@@ -82,6 +82,7 @@ typedef struct rs_segment {
 typedef struct rs_plan rs_plan;                  /* layout plan + device tables, library-owned */
 typedef struct rs_tensor_table rs_tensor_table;  /* device copy of n tensor base pointers */
 typedef struct rs_shard_batch rs_shard_batch;    /* device copy of the buffers of `count` units' shards */
+typedef struct rs_adam8_batch rs_adam8_batch;    /* the same for the optimiser buffers of `count` units */
 
 int rs_version(void);
 const char* rs_strerror(int code);
@@ -242,6 +243,20 @@ typedef struct rs_adam8_hyper {
 int rs_adam8_step(const rs_plan* plan, int rank, const rs_adam8_hyper* hyper, const float* grad,
                   float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
                   float* m_absmax, float* v_absmax, void* stream);
+
+/* The same step for rank's shard of `count` units that share this plan (the layers of a model)
+ * in one launch, as an optimiser applies one update to all parameters: one unit's shard is too
+ * small to fill the GPU.  Each argument is a host array of `count` device pointers with
+ * rs_adam8_step's meaning and alignment (params_bf16 may be NULL, or hold NULL entries); they
+ * are uploaded once and may be reused by any number of steps.  count <= 65535.  Bit for bit the
+ * result of rs_adam8_step on every unit. */
+int rs_adam8_batch_create(const rs_plan* plan, int rank, int count, const float* const* grads,
+                          float* const* masters, void* const* params_bf16, int8_t* const* m_codes,
+                          uint8_t* const* v_codes, float* const* m_absmax, float* const* v_absmax,
+                          rs_adam8_batch** out);
+void rs_adam8_batch_destroy(rs_adam8_batch* batch);
+int rs_adam8_step_batch(const rs_plan* plan, const rs_adam8_batch* batch, const rs_adam8_hyper* hyper,
+                        void* stream);
 
 /* ---- bandwidth probe: plain 16-byte-vector device copy of `bytes` (multiple of 16) ---------
  * Not part of the method: the measured ceiling the four kernels are held against, and the

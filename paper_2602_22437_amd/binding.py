@@ -25,6 +25,7 @@ EXPORTS = [
     "rs_quantize_batch", "rs_plan_create_ordered", "rs_plan_order",
     "rs_pack_scaled", "rs_group_add", "rs_group_scale", "rs_group_zero",
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
+    "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch",
 ]
 
 
@@ -102,6 +103,10 @@ _lib.rs_plan_num_state_blocks.restype = C.c_int64
 _lib.rs_plan_state_bases.argtypes = [_P, C.POINTER(C.c_int64), C.c_int]
 _lib.rs_plan_state_range.argtypes = [_P, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 _lib.rs_adam8_step.argtypes = [_P, C.c_int, C.POINTER(rs_adam8_hyper), _P, _P, _P, _P, _P, _P, _P, _P]
+_lib.rs_adam8_batch_create.argtypes = [_P, C.c_int, C.c_int] + [C.POINTER(_P)] * 7 + [C.POINTER(_P)]
+_lib.rs_adam8_batch_destroy.argtypes = [_P]
+_lib.rs_adam8_batch_destroy.restype = None
+_lib.rs_adam8_step_batch.argtypes = [_P, _P, C.POINTER(rs_adam8_hyper), _P]
 
 
 def _check(code: int, where: str) -> int:
@@ -336,11 +341,46 @@ def rs_plan_state_range(plan, rank: int) -> Tuple[int, int]:
     return lo.value, hi.value
 
 
+def _hyper(hyper) -> rs_adam8_hyper:
+    if isinstance(hyper, rs_adam8_hyper):
+        return hyper
+    return rs_adam8_hyper(float(hyper[0]), float(hyper[1]), float(hyper[2]), float(hyper[3]), float(hyper[4]),
+                          int(hyper[5]))
+
+
+def rs_adam8_batch_create(plan, rank: int, grads, masters, params_bf16, m_codes, v_codes, m_absmax, v_absmax) -> int:
+    """One device tensor (or address) per unit in every sequence; params_bf16 may be None."""
+    n = len(grads)
+    seqs = [grads, masters, params_bf16, m_codes, v_codes, m_absmax, v_absmax]
+    arrs = []
+    for seq in seqs:
+        if seq is None:
+            arrs.append(None)
+            continue
+        if len(seq) != n:
+            raise ValueError("one buffer of every kind per unit")
+        a = (_P * max(1, n))()
+        for i, t in enumerate(seq):
+            a[i] = 0 if t is None else _ptr(t)
+        arrs.append(a)
+    out = _P()
+    _check(_lib.rs_adam8_batch_create(plan, int(rank), n, *arrs, C.byref(out)), "rs_adam8_batch_create")
+    return out.value
+
+
+def rs_adam8_batch_destroy(batch) -> None:
+    _lib.rs_adam8_batch_destroy(batch)
+
+
+def rs_adam8_step_batch(plan, batch, hyper, stream=None) -> None:
+    h = _hyper(hyper)
+    _check(_lib.rs_adam8_step_batch(plan, batch, C.byref(h), _stream(stream)), "rs_adam8_step_batch")
+
+
 def rs_adam8_step(plan, rank: int, hyper, grad, master, param_bf16, m_codes, v_codes, m_absmax, v_absmax,
                   stream=None) -> None:
     """hyper: (lr, beta1, beta2, eps, weight_decay, step) or an rs_adam8_hyper; param_bf16 may be None."""
-    h = hyper if isinstance(hyper, rs_adam8_hyper) else rs_adam8_hyper(
-        float(hyper[0]), float(hyper[1]), float(hyper[2]), float(hyper[3]), float(hyper[4]), int(hyper[5]))
+    h = _hyper(hyper)
     _check(_lib.rs_adam8_step(plan, int(rank), C.byref(h), _ptr(grad), _ptr(master),
                               0 if param_bf16 is None else _ptr(param_bf16), _ptr(m_codes), _ptr(v_codes),
                               _ptr(m_absmax), _ptr(v_absmax), _stream(stream)), "rs_adam8_step")

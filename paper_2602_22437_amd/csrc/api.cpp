@@ -446,42 +446,125 @@ int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes
                                 scale_off, static_cast<hipStream_t>(stream));
 }
 
-int rs_adam8_step(const rs_plan* plan, int rank, const rs_adam8_hyper* hyper, const float* grad,
-                  float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
-                  float* m_absmax, float* v_absmax, void* stream) {
-  const int rc = check_device(plan);
-  if (rc != RS_OK) return rc;
-  if (!plan->all_state) return RS_EUNSUPPORTED;
-  if (!hyper || !grad || !master || !m_codes || !v_codes || rank < 0 || rank >= plan->world)
-    return RS_EINVAL;
-  const int64_t nblk = plan->state_begin[size_t(rank) + 1] - plan->state_begin[size_t(rank)];
-  if (nblk > 0 && (!m_absmax || !v_absmax)) return RS_EINVAL;
+// checks the hyper-parameters and derives the step's fp32 constants: each is evaluated in
+// double precision and rounded once
+static int adam8_consts(const rs_adam8_hyper* hyper, rs::Adam8Consts* c) {
+  if (!hyper) return RS_EINVAL;
   const rs_adam8_hyper& h = *hyper;
   if (!std::isfinite(h.lr) || !std::isfinite(h.weight_decay) || !(h.beta1 >= 0.0 && h.beta1 < 1.0) ||
       !(h.beta2 >= 0.0 && h.beta2 < 1.0) || !(h.eps > 0.0) || !std::isfinite(h.eps) || h.step < 1)
     return RS_EINVAL;
+  const double bc1 = 1.0 - std::pow(h.beta1, double(h.step));
+  const double bc2 = 1.0 - std::pow(h.beta2, double(h.step));
+  c->beta1 = float(h.beta1);
+  c->beta2 = float(h.beta2);
+  c->one_minus_beta1 = float(1.0 - h.beta1);
+  c->one_minus_beta2 = float(1.0 - h.beta2);
+  c->eps = float(h.eps);
+  c->step_size = float(h.lr / bc1);
+  c->bc2_sqrt = float(std::sqrt(bc2));
+  c->decay = float(1.0 - h.lr * h.weight_decay);
+  if (!std::isfinite(c->step_size) || !(c->bc2_sqrt > 0.0f)) return RS_EINVAL;
+  return RS_OK;
+}
+
+static int adam8_check_buffers(const rs_plan* plan, int rank, const float* grad, const float* master,
+                               const void* param_bf16, const int8_t* m_codes, const uint8_t* v_codes,
+                               const float* m_absmax, const float* v_absmax) {
+  if (!grad || !master || !m_codes || !v_codes) return RS_EINVAL;
+  const int64_t nblk = plan->state_begin[size_t(rank) + 1] - plan->state_begin[size_t(rank)];
+  if (nblk > 0 && (!m_absmax || !v_absmax)) return RS_EINVAL;
   if (!aligned16(grad) || !aligned16(master) || !aligned16(param_bf16) || !aligned16(m_codes) ||
       !aligned16(v_codes) || (reinterpret_cast<uintptr_t>(m_absmax) & 3) ||
       (reinterpret_cast<uintptr_t>(v_absmax) & 3))
     return RS_EALIGN;
-  // the step's constants: double precision, rounded once to fp32
-  const double bc1 = 1.0 - std::pow(h.beta1, double(h.step));
-  const double bc2 = 1.0 - std::pow(h.beta2, double(h.step));
+  return RS_OK;
+}
+
+int rs_adam8_step(const rs_plan* plan, int rank, const rs_adam8_hyper* hyper, const float* grad,
+                  float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
+                  float* m_absmax, float* v_absmax, void* stream) {
+  int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_state) return RS_EUNSUPPORTED;
+  if (rank < 0 || rank >= plan->world) return RS_EINVAL;
   rs::Adam8Consts c;
-  c.beta1 = float(h.beta1);
-  c.beta2 = float(h.beta2);
-  c.one_minus_beta1 = float(1.0 - h.beta1);
-  c.one_minus_beta2 = float(1.0 - h.beta2);
-  c.eps = float(h.eps);
-  c.step_size = float(h.lr / bc1);
-  c.bc2_sqrt = float(std::sqrt(bc2));
-  c.decay = float(1.0 - h.lr * h.weight_decay);
-  if (!std::isfinite(c.step_size) || !(c.bc2_sqrt > 0.0f)) return RS_EINVAL;
+  rc = adam8_consts(hyper, &c);
+  if (rc == RS_OK)
+    rc = adam8_check_buffers(plan, rank, grad, master, param_bf16, m_codes, v_codes, m_absmax, v_absmax);
+  if (rc != RS_OK) return rc;
   const std::vector<int64_t>& ib = plan->host.state_item_begin;
   return rs::launch_adam8_step(plan->dev, ib[size_t(rank)], ib[size_t(rank) + 1] - ib[size_t(rank)],
-                               grad, master, param_bf16, m_codes, v_codes, m_absmax, v_absmax,
-                               int64_t(rank) * plan->S, plan->state_begin[size_t(rank)], c,
+                               grad, master, param_bf16, m_codes, v_codes, m_absmax, v_absmax, nullptr,
+                               0, int64_t(rank) * plan->S, plan->state_begin[size_t(rank)], c,
                                static_cast<hipStream_t>(stream));
+}
+
+int rs_adam8_batch_create(const rs_plan* plan, int rank, int count, const float* const* grads,
+                          float* const* masters, void* const* params_bf16, int8_t* const* m_codes,
+                          uint8_t* const* v_codes, float* const* m_absmax, float* const* v_absmax,
+                          rs_adam8_batch** out) {
+  if (!out) return RS_EINVAL;
+  *out = nullptr;
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_state) return RS_EUNSUPPORTED;
+  if (!grads || !masters || !m_codes || !v_codes || !m_absmax || !v_absmax || count <= 0 ||
+      count > 65535 || rank < 0 || rank >= plan->world)
+    return RS_EINVAL;
+  std::vector<void*> host(size_t(count) * 7);
+  for (int u = 0; u < count; ++u) {
+    void* const param = params_bf16 ? params_bf16[u] : nullptr;
+    const int brc = adam8_check_buffers(plan, rank, grads[u], masters[u], param, m_codes[u], v_codes[u],
+                                        m_absmax[u], v_absmax[u]);
+    if (brc != RS_OK) return brc;
+    host[size_t(u)] = const_cast<float*>(grads[u]);
+    host[size_t(count) + u] = masters[u];
+    host[size_t(count) * 2 + u] = param;
+    host[size_t(count) * 3 + u] = m_codes[u];
+    host[size_t(count) * 4 + u] = v_codes[u];
+    host[size_t(count) * 5 + u] = m_absmax[u];
+    host[size_t(count) * 6 + u] = v_absmax[u];
+  }
+  rs_adam8_batch* b = new (std::nothrow) rs_adam8_batch();
+  if (!b) return RS_ENOMEM;
+  b->owner = plan;
+  b->rank = rank;
+  b->count = count;
+  const size_t bytes = host.size() * sizeof(void*);
+  if (hipMalloc(reinterpret_cast<void**>(&b->ptrs), bytes) != hipSuccess) {
+    delete b;
+    return RS_ENOMEM;
+  }
+  if (hipMemcpy(b->ptrs, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(b->ptrs);
+    delete b;
+    return RS_EHIP;
+  }
+  *out = b;
+  return RS_OK;
+}
+
+void rs_adam8_batch_destroy(rs_adam8_batch* batch) {
+  if (!batch) return;
+  if (batch->ptrs) (void)hipFree(batch->ptrs);
+  delete batch;
+}
+
+int rs_adam8_step_batch(const rs_plan* plan, const rs_adam8_batch* batch, const rs_adam8_hyper* hyper,
+                        void* stream) {
+  int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!batch || batch->owner != plan || !batch->ptrs) return RS_EINVAL;
+  rs::Adam8Consts c;
+  rc = adam8_consts(hyper, &c);
+  if (rc != RS_OK) return rc;
+  const int rank = batch->rank;
+  const std::vector<int64_t>& ib = plan->host.state_item_begin;
+  return rs::launch_adam8_step(plan->dev, ib[size_t(rank)], ib[size_t(rank) + 1] - ib[size_t(rank)],
+                               nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                               batch->ptrs, batch->count, int64_t(rank) * plan->S,
+                               plan->state_begin[size_t(rank)], c, static_cast<hipStream_t>(stream));
 }
 
 int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* const* shards,

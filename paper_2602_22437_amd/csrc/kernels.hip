@@ -714,18 +714,21 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
 
 // -------------------------------------------------------------------------------------------
 // adam8_step: AdamW on the local shard with block-wise 8-bit moments.
-// A workgroup of 256 lanes owns one state work item: 32 rows x 256 columns of a 2-D tensor (a
+// A workgroup of 1024 lanes owns one state work item: 32 rows x 256 columns of a 2-D tensor (a
 // row of eight 32x32 state tiles), or 64 runs of 128 elements of a 1-D tensor seen as 32 rows of
 // 256 elements.  Lane (cq, rw) = (tid % 64, tid / 64) handles the 4 elements at column 4 * cq of
-// rows rw + 4 * i, i = 0..7, so one access instruction of a wavefront covers one row (1 KiB of
-// fp32) and a lane's eight slots lie in one tile.  Pass 1 loads everything, applies the update,
+// rows rw and rw + 16, so one access instruction of a wavefront covers one row (1 KiB of fp32)
+// and a lane's two slots lie in one tile.  (Measured: 256 columns per item beat 512 and 1024,
+// and beat one tile per wavefront by far - narrow row pieces waste DRAM pages; 1024 lanes beat
+// 512 and 256.)  Items that are full and 16-byte structured skip all masking.  Pass 1 loads everything, applies the update,
 // stores the master weight and the bf16 parameter and keeps the new moments in registers;
-// after the block maxima are known (shuffles inside a wavefront, LDS across the four
+// after the block maxima are known (shuffles inside a wavefront, LDS across the
 // wavefronts of a tile) pass 2 quantises and stores the codes.  One HBM read and one write
 // per array.
 // -------------------------------------------------------------------------------------------
-constexpr int kStateThreads = 256;
-constexpr int kStateSlots = 8;
+constexpr int kStateThreads = 1024;
+constexpr int kStateWaves = kStateThreads / 64;
+constexpr int kStateSlots = 32 / kStateWaves;  // rows per lane
 
 struct StateSlot {
   int64_t off;  // offset of the slot's first element in the rank's region
@@ -764,13 +767,26 @@ __device__ __forceinline__ StateSlot state_slot(const TensorDev& t, const Item& 
 
 __device__ __forceinline__ float quant_step(float absmax, float levels) { return absmax / levels; }
 
-// code = rint(x / step) clamped to [lo, hi]; an all-zero block (step from absmax 0) gives 0
-__device__ __forceinline__ int state_code(float x, float absmax, float step, float lo, float hi) {
-  if (absmax == 0.0f) return 0;
-  return int(__builtin_amdgcn_fmed3f(__builtin_rintf(x / step), lo, hi));
+// A divisor shared by many dividends, with the exact-division shortcut described at `divide`
+// above.  It is taken while the divisor lies in [2^-60, 2^60]: every dividend used with it here
+// is either at most a few hundred times the divisor in magnitude or a square root (never
+// subnormal unless zero), so no intermediate of a quotient that matters under- or overflows.
+__device__ __forceinline__ Divisor shared_divisor(float b) {
+  Divisor d;
+  d.b = b;
+  const unsigned e = (__float_as_uint(b) >> 23) & 0xffu;
+  d.fast = e >= 67u && e < 187u;
+  d.r = d.fast ? 1.0f / b : 0.0f;
+  return d;
 }
 
-template <bool kTile>
+// code = rint(x / step) clamped to [lo, hi]; an all-zero block (absmax 0) gives 0
+__device__ __forceinline__ int state_code(float x, float absmax, const Divisor& step, float lo, float hi) {
+  if (absmax == 0.0f) return 0;
+  return int(__builtin_amdgcn_fmed3f(__builtin_rintf(divide(x, step)), lo, hi));
+}
+
+template <bool kTile, bool kFull>
 __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
                                            const float* __restrict__ g, float* __restrict__ w,
                                            uint16_t* __restrict__ p, uint8_t* __restrict__ mc,
@@ -780,7 +796,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
                                            float (*tile_max)[kStateThreads / 64][kStateCols / 32]) {
   const int tid = threadIdx.x;
   const int cq = tid & 63, rw = tid >> 6;
-  const bool vec = (t.flags & kFlagVec4) != 0;
+  const bool vec = kFull || (t.flags & kFlagVec4) != 0;
   const int64_t base = t.ell - elem_base;
 
   StateSlot sl[kStateSlots];
@@ -788,11 +804,18 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
   unsigned mcode[kStateSlots], vcode[kStateSlots];
 #pragma unroll
   for (int i = 0; i < kStateSlots; ++i) {
-    sl[i] = state_slot<kTile>(t, it, rw + 4 * i, cq, base, state_off);
+    if (kFull) {  // a whole row of tiles inside the tensor: no masks
+      const int64_t col = int64_t(it.count) * kStateCols + 4 * cq;
+      sl[i].nv = 4;
+      sl[i].off = base + (it.first * 32 + rw + kStateWaves * i) * t.cols + col;
+      sl[i].blk = int(t.state_base + it.first * t.sbc + (col >> 5) - state_off);
+    } else {
+      sl[i] = state_slot<kTile>(t, it, rw + kStateWaves * i, cq, base, state_off);
+    }
     gv[i] = wv[i] = u32x4{0, 0, 0, 0};
     mcode[i] = vcode[i] = 0;
-    if (sl[i].nv == 0) continue;
-    if (vec && sl[i].nv == 4) {
+    if (!kFull && sl[i].nv == 0) continue;
+    if (kFull || (vec && sl[i].nv == 4)) {
       gv[i] = ld16(g + sl[i].off);
       wv[i] = ld16(w + sl[i].off);
       mcode[i] = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(mc + sl[i].off));
@@ -816,7 +839,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
   float sm[kStateSlots], sv[kStateSlots];
   if (kTile) {
     float a = 0.0f, b = 0.0f;
-    if (sl[0].nv > 0) {
+    if (kFull || sl[0].nv > 0) {
       a = quant_step(am[sl[0].blk], 127.0f);
       b = quant_step(av[sl[0].blk], 255.0f);
     }
@@ -837,6 +860,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
   }
 
   // pass 1: the update; new moments stay in registers
+  const Divisor bc2 = shared_divisor(c.bc2_sqrt);
   float m[kStateSlots][4], v[kStateSlots][4];
   float mmax[kStateSlots], vmax[kStateSlots];
 #pragma unroll
@@ -856,15 +880,15 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
       const float t3 = c.beta2 * v_old, t4 = c.one_minus_beta2 * gg;
       v[i][j] = t3 + t4;
       const float w1 = __uint_as_float(wq[j]) * c.decay;
-      const float root = __builtin_sqrtf(v[i][j]) / c.bc2_sqrt;
+      const float root = divide(__builtin_sqrtf(v[i][j]), bc2);
       const float denom = root + c.eps;
       const float upd = c.step_size * (m[i][j] / denom);
       wn[j] = w1 - upd;
       mmax[i] = fmaxf(mmax[i], __builtin_fabsf(m[i][j]));
       vmax[i] = fmaxf(vmax[i], v[i][j]);
     }
-    if (sl[i].nv == 0) continue;
-    if (vec && sl[i].nv == 4) {
+    if (!kFull && sl[i].nv == 0) continue;
+    if (kFull || (vec && sl[i].nv == 4)) {
       st16(w + sl[i].off, u32x4{__float_as_uint(wn[0]), __float_as_uint(wn[1]), __float_as_uint(wn[2]),
                                 __float_as_uint(wn[3])});
       if (p) st8(p + sl[i].off, u32x2{pack_bf16(wn[0], wn[1]), pack_bf16(wn[2], wn[3])});
@@ -903,7 +927,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
       a = fmaxf(a, tile_max[0][q][cq >> 3]);
       b = fmaxf(b, tile_max[1][q][cq >> 3]);
     }
-    if (rw == 0 && (cq & 7) == 0 && sl[0].nv > 0) {
+    if (rw == 0 && (cq & 7) == 0 && (kFull || sl[0].nv > 0)) {
       am[sl[0].blk] = a;
       av[sl[0].blk] = b;
     }
@@ -933,15 +957,16 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
   // pass 2: quantise the new moments
 #pragma unroll
   for (int i = 0; i < kStateSlots; ++i) {
-    if (sl[i].nv == 0) continue;
-    const float s1 = quant_step(mmax[i], 127.0f), s2 = quant_step(vmax[i], 255.0f);
+    if (!kFull && sl[i].nv == 0) continue;
+    const Divisor s1 = shared_divisor(quant_step(mmax[i], 127.0f));
+    const Divisor s2 = shared_divisor(quant_step(vmax[i], 255.0f));
     unsigned cm = 0, cv = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       cm |= (unsigned(state_code(m[i][j], mmax[i], s1, -127.0f, 127.0f)) & 0xffu) << (8 * j);
       cv |= (unsigned(state_code(v[i][j], vmax[i], s2, 0.0f, 255.0f)) & 0xffu) << (8 * j);
     }
-    if (vec && sl[i].nv == 4) {
+    if (kFull || (vec && sl[i].nv == 4)) {
       __builtin_nontemporal_store(cm, reinterpret_cast<unsigned*>(mc + sl[i].off));
       __builtin_nontemporal_store(cv, reinterpret_cast<unsigned*>(vc + sl[i].off));
     } else {
@@ -959,18 +984,36 @@ __global__ __launch_bounds__(kStateThreads) void adam8_step_kernel(
     const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
     int64_t item_count, const float* __restrict__ g, float* __restrict__ w,
     uint16_t* __restrict__ p, uint8_t* __restrict__ mc, uint8_t* __restrict__ vc,
-    float* __restrict__ am, float* __restrict__ av, int64_t elem_base, int64_t state_off,
-    Adam8Consts c) {
+    float* __restrict__ am, float* __restrict__ av, void* const* __restrict__ batch,
+    int batch_count, int64_t elem_base, int64_t state_off, Adam8Consts c) {
   __shared__ float tile_max[2][kStateThreads / 64][kStateCols / 32];
   // neighbouring column strips of a row of tiles share DRAM pages: keep them on one XCD
-  const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
-  if (idx >= item_count) return;
+  int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
+  if (batch) {
+    // the same shard of batch_count units, their item ranges end to end in one flat grid;
+    // batch = [grad | master | param | m codes | v codes | m absmax | v absmax] pointers
+    const int64_t u = idx / item_count;
+    if (u >= batch_count) return;
+    idx -= u * item_count;
+    g = static_cast<const float*>(batch[u]);
+    w = static_cast<float*>(batch[batch_count + u]);
+    p = static_cast<uint16_t*>(batch[2 * batch_count + u]);
+    mc = static_cast<uint8_t*>(batch[3 * batch_count + u]);
+    vc = static_cast<uint8_t*>(batch[4 * batch_count + u]);
+    am = static_cast<float*>(batch[5 * batch_count + u]);
+    av = static_cast<float*>(batch[6 * batch_count + u]);
+  } else if (idx >= item_count) {
+    return;
+  }
   const Item it = items[item_off + idx];
   const TensorDev t = T[it.tensor];
   if (t.flags & kFlagOneD)
-    adam8_item<false>(t, it, g, w, p, mc, vc, am, av, elem_base, state_off, c, tile_max);
+    adam8_item<false, false>(t, it, g, w, p, mc, vc, am, av, elem_base, state_off, c, tile_max);
+  else if ((t.flags & kFlagVec4) && (it.first + 1) * 32 <= t.rows &&
+           int64_t(it.count + 1) * kStateCols <= t.cols)
+    adam8_item<true, true>(t, it, g, w, p, mc, vc, am, av, elem_base, state_off, c, tile_max);
   else
-    adam8_item<true>(t, it, g, w, p, mc, vc, am, av, elem_base, state_off, c, tile_max);
+    adam8_item<true, false>(t, it, g, w, p, mc, vc, am, av, elem_base, state_off, c, tile_max);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -1063,14 +1106,16 @@ int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_payload_gran
 
 int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_count, const float* grad,
                       float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
-                      float* m_absmax, float* v_absmax, int64_t elem_base, int64_t state_off,
-                      const Adam8Consts& c, hipStream_t st) {
-  if (item_count == 0) return RS_OK;
-  if (item_count < 0 || item_count > 0x7fffff00LL) return RS_EOVERFLOW;
-  adam8_step_kernel<<<dim3(unsigned(xcd_grid(item_count))), dim3(kStateThreads), 0, st>>>(
+                      float* m_absmax, float* v_absmax, void* const* batch, int batch_count,
+                      int64_t elem_base, int64_t state_off, const Adam8Consts& c, hipStream_t st) {
+  if (item_count == 0 || (batch && batch_count == 0)) return RS_OK;
+  if (item_count < 0 || batch_count < 0) return RS_EOVERFLOW;
+  const int64_t work = item_count * (batch ? batch_count : 1);
+  if (work > 0x7fffff00LL) return RS_EOVERFLOW;
+  adam8_step_kernel<<<dim3(unsigned(xcd_grid(work))), dim3(kStateThreads), 0, st>>>(
       dev.tensors, dev.state_items, item_off, item_count, grad, master,
       static_cast<uint16_t*>(param_bf16), reinterpret_cast<uint8_t*>(m_codes), v_codes, m_absmax,
-      v_absmax, elem_base, state_off, c);
+      v_absmax, batch, batch_count, elem_base, state_off, c);
   return launched();
 }
 

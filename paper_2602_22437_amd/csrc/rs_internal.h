@@ -131,3 +131,10 @@ struct rs_shard_batch {
   int count = 0;
   void** ptrs = nullptr;  // device array: count shards, count code buffers, count scale slices
 };
+
+struct rs_adam8_batch {
+  const rs_plan* owner = nullptr;
+  int rank = 0;
+  int count = 0;
+  void** ptrs = nullptr;  // device array: count each of grad, master, param, m codes, v codes, m absmax, v absmax
+};

@@ -26,8 +26,8 @@ struct Adam8Consts {
 };
 int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_count, const float* grad,
                       float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
-                      float* m_absmax, float* v_absmax, int64_t elem_base, int64_t state_off,
-                      const Adam8Consts& c, hipStream_t st);
+                      float* m_absmax, float* v_absmax, void* const* batch, int batch_count,
+                      int64_t elem_base, int64_t state_off, const Adam8Consts& c, hipStream_t st);
 int launch_copy_probe(void* dst, const void* src, int64_t bytes, hipStream_t st);
 
 }  // namespace rs

@@ -168,3 +168,59 @@ def test_adam8_errors():
     finally:
         u.close()
         un.close()
+
+
+def test_adam8_step_batch_equals_per_unit_steps():
+    """One launch over rank 1's shard of five units == five rs_adam8_step calls, bit for bit; unit 0
+    is also held against the oracle."""
+    tensors, world, _ = UNITS[0]
+    u = Unit(tensors, world)
+    try:
+        S, rank, count = u.S, 1, 5
+        lo, hi = B.rs_plan_state_range(u.plan, rank)
+        nb = hi - lo
+        rng = np.random.default_rng(4242)
+        h1, h2 = hypers(2)
+
+        def fresh():
+            return dict(
+                g=[torch.from_numpy((rng.standard_normal(S) * 1e-3).astype(np.float32)).cuda() for _ in range(count)],
+                w=[torch.from_numpy((rng.standard_normal(S) * 0.02).astype(np.float32)).cuda() for _ in range(count)],
+                p=[torch.zeros(S, dtype=torch.bfloat16, device="cuda") for _ in range(count)],
+                mc=[torch.zeros(S, dtype=torch.int8, device="cuda") for _ in range(count)],
+                vc=[torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(count)],
+                am=[torch.zeros(nb, dtype=torch.float32, device="cuda") for _ in range(count)],
+                av=[torch.zeros(nb, dtype=torch.float32, device="cuda") for _ in range(count)])
+        a = fresh()
+        b = {k: [t.clone() for t in v] for k, v in a.items()}
+        host = {k: [t.cpu().numpy().copy() for t in v] for k, v in a.items() if k != "p"}
+        batch = B.rs_adam8_batch_create(u.plan, rank, a["g"], a["w"], a["p"], a["mc"], a["vc"], a["am"], a["av"])
+        for h in (h1, h2):
+            tup = (h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step)
+            say(f"adam8 batch of {count} units, step {h.step}")
+            B.rs_adam8_step_batch(u.plan, batch, tup)
+            for i in range(count):
+                B.rs_adam8_step(u.plan, rank, tup, b["g"][i], b["w"][i], b["p"][i], b["mc"][i], b["vc"][i],
+                                b["am"][i], b["av"][i])
+            torch.cuda.synchronize()
+            for k in ("w", "p", "mc", "vc", "am", "av"):
+                for i in range(count):
+                    x, y = a[k][i], b[k][i]
+                    if x.dtype == torch.bfloat16:
+                        x, y = x.view(torch.int16), y.view(torch.int16)
+                    assert torch.equal(x, y), f"{k} of unit {i} differs at step {h.step}"
+        B.rs_adam8_batch_destroy(batch)
+        # unit 0 against the oracle, two steps from the zero state
+        w, pb, mc, vc = host["w"][0], np.zeros(S, np.uint16), host["mc"][0], host["vc"][0].astype(np.uint8)
+        am, av = host["am"][0], host["av"][0]
+        for h in (h1, h2):
+            w, pb, mc, vc, am, av = OA.adam8_step_shard(u.oracle, rank, host["g"][0], w, pb, mc, vc, am, av, h)
+        pay = np.zeros(S, dtype=bool)
+        for _, _, d, n in u.oracle.rank_segments(rank):
+            pay[d:d + n] = True
+        diff(a["w"][0].cpu().numpy()[pay].view(np.uint32), w[pay].view(np.uint32), "batch master vs oracle")
+        diff(a["mc"][0].cpu().numpy()[pay], mc[pay], "batch m codes vs oracle")
+        diff(a["vc"][0].cpu().numpy()[pay], vc[pay], "batch v codes vs oracle")
+        diff(a["am"][0].cpu().numpy().view(np.uint32), am.view(np.uint32), "batch m absmax vs oracle")
+    finally:
+        u.close()
