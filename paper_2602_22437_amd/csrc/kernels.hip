@@ -188,10 +188,15 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
   }
 }
 
+// Pure writes want 256-lane workgroups with one vector per lane (measured 6.9 TB/s against
+// 4.8 TB/s for single-wavefront workgroups and 6.4 TB/s for 4 vectors per lane), the opposite
+// of what copies want.
+constexpr int kFillThreads = 256;
+
 // every element of a buffer of nvec 16-byte vectors becomes +0
-__global__ __launch_bounds__(kCopyThreads) void fill_zero_kernel(u32x4* __restrict__ dst, int64_t nvec) {
-  const int64_t i = int64_t(blockIdx.x) * kCopyThreads + threadIdx.x;
-  if (i < nvec) __builtin_nontemporal_store(u32x4{0, 0, 0, 0}, dst + i);
+__global__ __launch_bounds__(kFillThreads) void fill_zero_kernel(u32x4* __restrict__ dst, int64_t nvec) {
+  const int64_t i = int64_t(blockIdx.x) * kFillThreads + threadIdx.x;
+  if (i < nvec) dst[i] = u32x4{0, 0, 0, 0};
 }
 
 // -------------------------------------------------------------------------------------------
@@ -211,9 +216,26 @@ __device__ __forceinline__ void add_bf16x8(float (&acc)[8], const u32x4 v) {
   acc[7] += __uint_as_float(v.w & 0xffff0000u);
 }
 
-// kReduceThreads = 256: one granule per workgroup; 512: two granules (8 KiB contiguous per row),
-// which is faster on long regions and slightly slower when the grid is only a few waves deep.
-template <int kReduceThreads>
+// rows w .. w + 7 of this lane's column; rows at or past W read as +0 (they keep the row -> set rule)
+__device__ __forceinline__ void load_rows(u32x4 (&v)[8], const uint16_t* p, int64_t row_stride, int w,
+                                          int W) {
+  if (w + 8 <= W) {
+#pragma unroll
+    for (int a = 0; a < 8; ++a) v[a] = ld16(p + int64_t(w + a) * row_stride);
+  } else {
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+      v[a] = w + a < W ? ld16(p + int64_t(w + a) * row_stride) : u32x4{0, 0, 0, 0};
+  }
+}
+
+// kReduceThreads = 256: one granule per workgroup; 512: two granules (8 KiB contiguous per row).
+// kDouble keeps the next eight rows in flight while the current ones are added.  Measured on
+// regions of 4096 granules and more: 512 lanes with kDouble is the fastest shape (+5 % at
+// W = 32, +3 % at W = 128); on short regions 256 lanes without it.  Requesting the first rows
+// before the table lookups was tried and lost everywhere: what it reads on padding costs more
+// than the latency it hides.
+template <int kReduceThreads, bool kDouble>
 __global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
     const uint16_t* __restrict__ P, int64_t row_stride, float* __restrict__ out, int64_t S,
@@ -229,9 +251,9 @@ __global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
   if (lane_off >= len) return;
   const int64_t d = d0 + lane_off;
   float* o = out + i0 + lane_off;
-  const int t0 = gran_first[int64_t(rank) * gpr + j];
 
   // payload mask of this lane's 8 elements
+  const int t0 = gran_first[int64_t(rank) * gpr + j];
   unsigned mask = 0xffu;
   bool empty = t0 >= n;
   if (!empty) {
@@ -254,28 +276,30 @@ __global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
     return;
   }
 
+  const uint16_t* p = P + i0 + lane_off;
+  u32x4 v[8];
+  load_rows(v, p, row_stride, 0, W);
   float acc[8][8];
 #pragma unroll
   for (int a = 0; a < 8; ++a)
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc[a][q] = 0.0f;
 
-  const uint16_t* p = P + i0 + lane_off;
-  int w = 0;
-  for (; w + 8 <= W; w += 8) {
-    u32x4 v[8];
+  for (int w = 8;; w += 8) {   // v holds rows w - 8 .. w - 1
+    if (kDouble) {
+      u32x4 next[8];
+      if (w < W) load_rows(next, p, row_stride, w, W);
 #pragma unroll
-    for (int a = 0; a < 8; ++a) v[a] = ld16(p + int64_t(w + a) * row_stride);
+      for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
+      if (w >= W) break;
 #pragma unroll
-    for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
-  }
-  if (w < W) {  // W mod 8 leftover rows keep the row -> set rule; absent rows add +0
-    u32x4 v[8];
+      for (int a = 0; a < 8; ++a) v[a] = next[a];
+    } else {
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
-      v[a] = w + a < W ? ld16(p + int64_t(w + a) * row_stride) : u32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
+      for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
+      if (w >= W) break;
+      load_rows(v, p, row_stride, w, W);
+    }
   }
   float r[8];
 #pragma unroll
@@ -1035,11 +1059,13 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
                     int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
                     hipStream_t st) {
   const bool fills = op == kGroupPack || op == kGroupPackScaled;
+  uint16_t* db = static_cast<uint16_t*>(dbuf);
   const int64_t copy_groups = n_payload_gran * kCopyParts;
+  // padding is zeroed by extra workgroups of the same launch (a separate fill launch was
+  // measured slower even where padding is 88 % of the buffer)
   const int64_t grid = copy_groups + (fills ? n_padding_gran : 0);
   if (grid == 0) return RS_OK;
   if (grid < 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
-  uint16_t* db = static_cast<uint16_t*>(dbuf);
   const dim3 g{unsigned(grid)}, b{unsigned(kCopyThreads)};
 #define RS_GROUP_OP(OP)                                                                         \
   group_op_kernel<OP><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,       \
@@ -1059,10 +1085,10 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
 
 int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st) {
   const int64_t nvec = bytes / 16;
-  const int64_t grid = (nvec + kCopyThreads - 1) / kCopyThreads;
+  const int64_t grid = (nvec + kFillThreads - 1) / kFillThreads;
   if (grid == 0) return RS_OK;
   if (grid > 0x7fffffffLL) return RS_EOVERFLOW;
-  fill_zero_kernel<<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(static_cast<u32x4*>(dst), nvec);
+  fill_zero_kernel<<<dim3(unsigned(grid)), dim3(kFillThreads), 0, st>>>(static_cast<u32x4*>(dst), nvec);
   return launched();
 }
 
@@ -1071,12 +1097,15 @@ int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, in
   if (gpr <= 0 || gpr > 0x7fffffffLL) return RS_EOVERFLOW;
   const float inv_w = 1.0f / float(world);
   const uint16_t* P = static_cast<const uint16_t*>(partials);
+  const dim3 g256{unsigned(xcd_grid(gpr))}, g512{unsigned(xcd_grid((gpr + 1) / 2))};
+#define RS_REDUCE(THREADS, DOUBLE, GRID)                                                         \
+  shard_reduce_kernel<THREADS, DOUBLE><<<GRID, dim3(THREADS), 0, st>>>(                         \
+      dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w)
   if (gpr >= 4096)
-    shard_reduce_kernel<512><<<dim3(unsigned(xcd_grid((gpr + 1) / 2))), dim3(512), 0, st>>>(
-        dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w);
+    RS_REDUCE(512, true, g512);
   else
-    shard_reduce_kernel<256><<<dim3(unsigned(xcd_grid(gpr))), dim3(256), 0, st>>>(
-        dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w);
+    RS_REDUCE(256, false, g256);
+#undef RS_REDUCE
   return launched();
 }
 

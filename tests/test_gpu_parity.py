@@ -275,7 +275,7 @@ def test_unaligned_tensor_storage():
         u.close()
 
 
-@pytest.mark.parametrize("W", [1, 2, 3, 8, 9, 15, 16, 17, 100])
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 9, 15, 16, 17, 100, 128, 131, 257])
 def test_reduce_world_sizes_and_special_cases(W):
     tensors = [(3000, 0, MODE_1x128), (70, 130, MODE_1x128)]
     u = Unit(tensors, W)
@@ -349,7 +349,8 @@ def test_device_argument_errors():
 
 def test_reduce_long_region_two_granule_workgroups():
     """Regions of 4096 granules or more are reduced by 512-lane workgroups that take two granules
-    each; check that path element by element, ragged tail and padding included."""
+    each and keep the next eight rows in flight; check that path element by element, ragged tail
+    and padding included."""
     W = 3
     u = Unit([(9_000_001, 0, MODE_1x128), (700, 136, MODE_128x128), (16_500_000, 0, MODE_1x128)], W)
     try:
@@ -357,6 +358,19 @@ def test_reduce_long_region_two_granule_workgroups():
         for rank in range(W):
             parts = np.stack([normal_bf16(15, rank, 1, w, u.S, 1e-3) for w in range(W)])
             check_reduce(u, rank, parts, f"long region rank {rank}")
+    finally:
+        u.close()
+
+
+def test_reduce_long_region_many_partials():
+    """The long-region kernel with more rows than one batch of eight, W not a multiple of 8."""
+    W = 35
+    u = Unit([(W * 8_400_000 + 77, 0, MODE_1x128)], W)
+    try:
+        assert -(-u.S // 2048) >= 4096
+        rank = W - 1
+        parts = np.stack([normal_bf16(16, rank, 1, w, u.S, 1e-3) for w in range(W)])
+        check_reduce(u, rank, parts, f"long region, W={W}, rank {rank}")
     finally:
         u.close()
 
