@@ -266,6 +266,21 @@ def main():
             "ms": round(qa_ms, 4), "bytes": qa_bytes, "GBps": round(qa_bytes / qa_ms / 1e6, 1),
             "frac_of_peak": round(qa_bytes / qa_ms / 1e6 / HBM_PEAK_GBPS, 4),
             "note": "same kernel over all W shards of a unit in one launch; not part of the timed step"}
+    if quant:   # gathered FP8 unit straight into fp32 master copies (first 4 units: 4 bytes per element)
+        f32_units = U[:min(units, 4)]
+        for d in f32_units:
+            d["dst32"] = [torch.empty(t.numel, dtype=torch.float32, device="cuda") for t in wl.tensors]
+            d["dst32_tab"] = B.rs_tensor_table_create(plan, d["dst32"])
+        nf = len(f32_units)
+        uf_ms = timed(lambda i=0: B.rs_unpack_f32(plan, U[i % nf]["codes"], U[i % nf]["scales"], U[i % nf]["dst32_tab"],
+                                                  stream), max(nf, 8))
+        uf_bytes = E + 4 * nb + 4 * E
+        kernels["unpack_f32"] = {"ms": round(uf_ms, 4), "bytes": uf_bytes, "GBps": round(uf_bytes / uf_ms / 1e6, 1),
+                                 "frac_of_peak": round(uf_bytes / uf_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                 "note": "dequant_unpack into fp32 tensors; not part of the timed step"}
+        for d in f32_units:
+            B.rs_tensor_table_destroy(d.pop("dst32_tab"))
+            del d["dst32"]
     # group-level operators and the 8-bit Adam step (widening beyond the four timed kernels)
     group_bytes = {"pack_scaled": 2 * E + 2 * total, "group_add": 6 * E, "group_scale": 4 * E,
                    "group_zero": 2 * total}

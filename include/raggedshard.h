@@ -171,7 +171,9 @@ int rs_group_zero(const rs_plan* plan, void* dbuf, void* stream);
 
 /* ---- shard_reduce: the arithmetic of the gradient ReduceScatter as one rank sees it --------
  * (Section 2.3).  out[i] = (1/world) * sum_w partials[w*row_stride + i] for i in the
- * payload of rank's region, 0 on its padding; fp32 accumulation in a fixed order.
+ * payload of rank's region, 0 on its padding; fp32 accumulation in a fixed order, so the result
+ * is reproducible bit for bit: partial w is added, in increasing w, to running sum (w mod 8);
+ * the eight sums combine as ((a0+a1)+(a2+a3))+((a4+a5)+(a6+a7)); then one multiply by fp32(1/world).
  * partials: device, `world` rows of S bf16, row_stride elements apart (multiple of 8,
  * base 16-byte aligned); out: device, S fp32, 16-byte aligned. */
 int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride,
@@ -204,6 +206,12 @@ int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* st
  * codes: device, world*S uint8, 16-byte aligned; scales: device, all of the unit's scales. */
 int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
               const rs_tensor_table* dst, void* stream);
+
+/* The same into fp32 tensors (the fp32 master copy of the gathered parameters, without the
+ * detour through bf16): dst_t[i] = value(codes[l_t + i]) * scales[block of i], one fp32 multiply.
+ * dst: table of fp32 device tensors (4-byte aligned, else RS_EALIGN). */
+int rs_unpack_f32(const rs_plan* plan, const uint8_t* codes, const float* scales,
+                  const rs_tensor_table* dst, void* stream);
 
 /* ---- block-wise 8-bit optimiser state on the local shard (Section 6.3, "8-bit Adam") ---------
  * The two Adam moments of rank's shard are held as 8-bit codes in blocks that never cross a

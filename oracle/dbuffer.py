@@ -54,6 +54,25 @@ def shard_reduce(partials: np.ndarray, segments: Sequence[Tuple[int, int, int, i
     return out
 
 
+def shard_reduce_f32_ordered(partials: np.ndarray, segments: Sequence[Tuple[int, int, int, int]]) -> np.ndarray:
+    """The same mean evaluated in fp32 in one stated order, for bit-for-bit reproducibility
+    of the reduction (a reading: the paper fixes no order; any fixed one is a valid
+    ReduceScatter):  partial w is added, in increasing w, to running sum number (w mod 8),
+    each sum starting from +0; the eight sums a0..a7 are combined as
+    ((a0 + a1) + (a2 + a3)) + ((a4 + a5) + (a6 + a7)); the result is multiplied by the fp32
+    value of 1/W.  Every operation is a single rounded fp32 operation."""
+    W, S = partials.shape
+    out = np.zeros(S, dtype=np.float32)
+    inv = np.float32(1.0) / np.float32(W)
+    for _, _, d, n in segments:
+        a = [np.zeros(n, dtype=np.float32) for _ in range(8)]
+        for w in range(W):
+            a[w % 8] = a[w % 8] + bf16_bits_to_f32(partials[w, d:d + n])
+        total = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]))
+        out[d:d + n] = total * inv
+    return out
+
+
 def shard_reduce_abs_sum(partials: np.ndarray) -> np.ndarray:
     """sum_w |P[w][i]| in float64: the scale of the accepted error of shard_reduce."""
     W, S = partials.shape

@@ -134,6 +134,25 @@ def dequantise_tensor(codes: np.ndarray, scales: np.ndarray, spec: TensorSpec) -
     return out.reshape(-1)
 
 
+def dequantise_tensor_f32(codes: np.ndarray, scales: np.ndarray, spec: TensorSpec) -> np.ndarray:
+    """Step 4 without the final rounding: fp32 value(code) * scale (one fp32 multiply), flat.
+    The form an fp32 master copy of the gathered parameters takes."""
+    R, C, bh, bw = _as_2d(spec)
+    nbr, nbc = -(-R // bh), -(-C // bw)
+    tab = decode_table()
+    cod = np.asarray(codes, dtype=np.uint8).reshape(R, C)
+    sc = np.asarray(scales, dtype=np.float32).reshape(nbr, nbc)
+    out = np.empty((R, C), dtype=np.float32)
+    for br in range(nbr):
+        rows = cod[br * bh:(br + 1) * bh]
+        h = rows.shape[0]
+        wide = np.zeros((h, nbc * bw), dtype=np.uint8)
+        wide[:, :C] = rows
+        v = tab[wide].reshape(h, nbc, bw) * sc[br][None, :, None]      # fp32 * fp32
+        out[br * bh:(br + 1) * bh] = v.reshape(h, nbc * bw)[:, :C]
+    return out.reshape(-1)
+
+
 def block_quant_all(plan: Plan, db: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Quantise every tensor of the packed unit as a whole.  codes: m*S uint8 at the same
     element offsets as db (padding 0x00); scales: the unit's flat scale array."""
@@ -170,6 +189,16 @@ def block_quant_shard(plan: Plan, k: int, region: np.ndarray) -> Tuple[np.ndarra
         out_scales.append(s)
     sc = np.concatenate(out_scales) if out_scales else np.zeros(0, dtype=np.float32)
     return codes, sc.astype(np.float32)
+
+
+def dequant_unpack_f32(plan: Plan, codes: np.ndarray, scales: np.ndarray) -> List[np.ndarray]:
+    """Per-parameter fp32 values from the gathered codes (m*S) and all scales."""
+    out = []
+    for spec, l, sb in zip(plan.specs, plan.offsets, plan.scale_bases()):
+        if not spec.quantised:
+            raise ValueError("dequant_unpack needs quantised tensors")
+        out.append(dequantise_tensor_f32(codes[l:l + spec.e], scales[sb:sb + spec.num_blocks], spec))
+    return out
 
 
 def dequant_unpack(plan: Plan, codes: np.ndarray, scales: np.ndarray) -> List[np.ndarray]:

@@ -25,7 +25,7 @@ EXPORTS = [
     "rs_quantize_batch", "rs_plan_create_ordered", "rs_plan_order",
     "rs_pack_scaled", "rs_group_add", "rs_group_scale", "rs_group_zero",
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
-    "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch",
+    "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
 ]
 
 
@@ -92,6 +92,7 @@ _lib.rs_group_zero.argtypes = [_P, _P, _P]
 _lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
+_lib.rs_unpack_f32.argtypes = [_P, _P, _P, _P, _P]
 _lib.rs_shard_batch_create.argtypes = [_P, C.c_int, C.c_int, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P),
                                        C.POINTER(_P)]
 _lib.rs_shard_batch_destroy.argtypes = [_P]
@@ -384,6 +385,10 @@ def rs_adam8_step(plan, rank: int, hyper, grad, master, param_bf16, m_codes, v_c
     _check(_lib.rs_adam8_step(plan, int(rank), C.byref(h), _ptr(grad), _ptr(master),
                               0 if param_bf16 is None else _ptr(param_bf16), _ptr(m_codes), _ptr(v_codes),
                               _ptr(m_absmax), _ptr(v_absmax), _stream(stream)), "rs_adam8_step")
+
+
+def rs_unpack_f32(plan, codes, scales, dst_table, stream=None) -> None:
+    _check(_lib.rs_unpack_f32(plan, _ptr(codes), _ptr(scales), dst_table, _stream(stream)), "rs_unpack_f32")
 
 
 def rs_copy_probe(dst, src, nbytes: int, stream=None) -> None:

@@ -348,6 +348,7 @@ int rs_tensor_table_create(const rs_plan* plan, const void* const* ptrs, rs_tens
   tab->device = plan->dev.device;
   tab->owner = plan;
   tab->n = n;
+  for (int i = 0; i < n; ++i) tab->low_bits |= unsigned(reinterpret_cast<uintptr_t>(ptrs[i]) & 15);
   if (hipMalloc(reinterpret_cast<void**>(&tab->ptrs), sizeof(void*) * n) != hipSuccess) {
     delete tab;
     return RS_ENOMEM;
@@ -631,8 +632,22 @@ int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
   if (!plan->all_quant) return RS_EUNSUPPORTED;
   if (!codes || !scales) return RS_EINVAL;
   if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3)) return RS_EALIGN;
-  return rs::launch_dequant_unpack(plan->dev, int(plan->t.size()), plan->host.n_payload_gran, codes,
-                                   scales, dst->ptrs, plan->S, plan->host.granules_per_rank,
+  return rs::launch_dequant_unpack(false, plan->dev, int(plan->t.size()), plan->host.n_payload_gran,
+                                   codes, scales, dst->ptrs, plan->S, plan->host.granules_per_rank,
+                                   static_cast<hipStream_t>(stream));
+}
+
+int rs_unpack_f32(const rs_plan* plan, const uint8_t* codes, const float* scales,
+                  const rs_tensor_table* dst, void* stream) {
+  int rc = check_device(plan);
+  if (rc == RS_OK) rc = check_table(plan, dst);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_quant) return RS_EUNSUPPORTED;
+  if (!codes || !scales) return RS_EINVAL;
+  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3) || (dst->low_bits & 3))
+    return RS_EALIGN;
+  return rs::launch_dequant_unpack(true, plan->dev, int(plan->t.size()), plan->host.n_payload_gran,
+                                   codes, scales, dst->ptrs, plan->S, plan->host.granules_per_rank,
                                    static_cast<hipStream_t>(stream));
 }
 

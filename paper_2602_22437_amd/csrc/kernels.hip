@@ -653,9 +653,9 @@ __device__ __forceinline__ int64_t scale_index(const TensorDev& t, int64_t row, 
 }
 
 constexpr int kDequantThreads = 64;
-constexpr int kDequantParts = kGranule / (kDequantThreads * 8);  // 8-code groups per lane: 4
-constexpr int kDequantStep = kDequantThreads * 8;                // 512 codes per access
 
+// kF32: the tensors are fp32 (value * scale, no further rounding) instead of bf16
+template <bool kF32>
 __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
     const int32_t* __restrict__ granules, const uint8_t* __restrict__ codes,
@@ -666,11 +666,17 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
   const int64_t d0 = k * S + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
   const int t0 = gran_first[gid];  // a payload granule: t0 < n
-  const int lane = threadIdx.x * 8;
+  // A lane converts kGroup codes per access so that its store is one 16-byte vector and a
+  // wavefront's stores are contiguous: 8 codes -> 8 bf16, or 4 codes -> 4 fp32.
+  constexpr int kGroup = kF32 ? 4 : 8;
+  constexpr int kStep = kDequantThreads * kGroup;   // codes per access of the wavefront
+  constexpr int kParts = kGranule / kStep;
+  const int lane = threadIdx.x * kGroup;
 
   {
     const TensorDev t = T[t0];
     uint16_t* out = reinterpret_cast<uint16_t*>(ptrs[t0]);
+    float* out32 = reinterpret_cast<float*>(ptrs[t0]);
     const bool inside = t.ell <= d0 && d0 + len <= t.ell + t.e;
     if (inside && (t.flags & kFlagVec) && (reinterpret_cast<uintptr_t>(out) & 15) == 0 &&
         t.cols < (int64_t(1) << 30)) {
@@ -684,15 +690,18 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
       if (col0 >= t.cols) { col0 -= t.cols; ++row0; }
       const unsigned C = unsigned(t.cols);
       const bool contig = (t.flags & kFlagContig) && !(t.flags & kFlagTile);
-      u32x2 c[kDequantParts];
-      float sc[kDequantParts];
-      bool on[kDequantParts];
+      u32x2 c[kParts];
+      float sc[kParts];
+      bool on[kParts];
 #pragma unroll
-      for (int h = 0; h < kDequantParts; ++h) {
-        const int lo = h * kDequantStep + lane;
+      for (int h = 0; h < kParts; ++h) {
+        const int lo = h * kStep + lane;
         on[h] = lo < len;
         if (!on[h]) continue;
-        c[h] = ld8(codes + d0 + lo);
+        if (kF32)
+          c[h] = u32x2{__builtin_nontemporal_load(reinterpret_cast<const unsigned*>(codes + d0 + lo)), 0};
+        else
+          c[h] = ld8(codes + d0 + lo);
         int64_t sidx;
         if (contig) {
           sidx = (first + lo) >> 7;            // blocks are consecutive runs of 128 elements
@@ -704,12 +713,20 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
         sc[h] = scales[t.scale_base + sidx];
       }
 #pragma unroll
-      for (int h = 0; h < kDequantParts; ++h) {
+      for (int h = 0; h < kParts; ++h) {
         if (!on[h]) continue;
+        if (kF32) {
+          const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(int(c[h].x), false);
+          const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(int(c[h].x), true);
+          st16(out32 + first + h * kStep + lane,
+               u32x4{__float_as_uint(a[0] * sc[h]), __float_as_uint(a[1] * sc[h]),
+                     __float_as_uint(b[0] * sc[h]), __float_as_uint(b[1] * sc[h])});
+          continue;
+        }
         unsigned o0, o1, o2, o3;
         dequant4(c[h].x, sc[h], o0, o1);
         dequant4(c[h].y, sc[h], o2, o3);
-        st16(out + first + h * kDequantStep + lane, u32x4{o0, o1, o2, o3});
+        st16(out + first + h * kStep + lane, u32x4{o0, o1, o2, o3});
       }
       return;
     }
@@ -718,10 +735,10 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
   // Granule with tensor boundaries or padding, or a tensor without 16-byte structure:
   // every element finds its tensor, row and column on its own.
   int s = t0;
-  for (int h = 0; h < kDequantParts; ++h) {
-    const int lo = h * kDequantStep + lane;
+  for (int h = 0; h < kParts; ++h) {
+    const int lo = h * kStep + lane;
     if (lo >= len) break;
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < kGroup; ++q) {
       const int64_t pos = d0 + lo + q;
       while (s < n && T[s].ell + T[s].e <= pos) ++s;
       if (s >= n || T[s].ell > pos) continue;
@@ -731,7 +748,10 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
       const int64_t col = i - row * t.cols;
       const float scale = scales[t.scale_base + scale_index(t, row, col)];
       const auto f = __builtin_amdgcn_cvt_pk_f32_fp8(int(codes[pos]), false);
-      reinterpret_cast<uint16_t*>(ptrs[s])[i] = uint16_t(bf16_rne(f[0] * scale));
+      if (kF32)
+        reinterpret_cast<float*>(ptrs[s])[i] = f[0] * scale;
+      else
+        reinterpret_cast<uint16_t*>(ptrs[s])[i] = uint16_t(bf16_rne(f[0] * scale));
     }
   }
 }
@@ -1123,13 +1143,18 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
   return launched();
 }
 
-int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_payload_gran,
+int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
                           int64_t gpr, hipStream_t st) {
   if (n_payload_gran == 0) return RS_OK;
   if (n_payload_gran < 0 || n_payload_gran > 0x7fffffffLL) return RS_EOVERFLOW;
-  dequant_unpack_kernel<<<dim3(unsigned(n_payload_gran)), dim3(kDequantThreads), 0, st>>>(
-      dev.tensors, n, dev.gran_first, dev.payload_gran, codes, scales, ptrs, S, gpr);
+  const dim3 g{unsigned(n_payload_gran)}, b{unsigned(kDequantThreads)};
+  if (f32_out)
+    dequant_unpack_kernel<true><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,
+                                                 codes, scales, ptrs, S, gpr);
+  else
+    dequant_unpack_kernel<false><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,
+                                                  codes, scales, ptrs, S, gpr);
   return launched();
 }
 

@@ -122,6 +122,7 @@ struct rs_tensor_table {
   const rs_plan* owner = nullptr;  // tables are valid for the plan they were made for only
   int device = -1;
   int n = 0;
+  unsigned low_bits = 0;  // OR of the low four address bits of all pointers
   void** ptrs = nullptr;  // device array of n pointers
 };
 

@@ -17,7 +17,7 @@ int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, in
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
                        uint8_t* codes, float* scales, void* const* batch, int batch_count,
                        int64_t elem_base, int64_t scale_off, hipStream_t st);
-int launch_dequant_unpack(const DeviceTables& dev, int n, int64_t n_payload_gran,
+int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
                           int64_t gpr, hipStream_t st);
 // fp32 constants of one 8-bit Adam step

@@ -224,3 +224,13 @@ def test_adam8_step_batch_equals_per_unit_steps():
         diff(a["am"][0].cpu().numpy().view(np.uint32), am.view(np.uint32), "batch m absmax vs oracle")
     finally:
         u.close()
+
+
+def test_adam8_gpt_oss_shard_with_partial_column_strips():
+    """Rank 0's shard of the GPT-OSS-shaped unit (W = 128, 25 M elements): 2880 columns leave a
+    64-column strip at the end of every row of tiles, so full and masked items alternate."""
+    u = Unit.from_workload(WORKLOADS[4])
+    try:
+        run_steps(u, 0, 1400, hypers(2, lr=3e-4), "gpt-oss rank 0")
+    finally:
+        u.close()

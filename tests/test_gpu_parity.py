@@ -1,6 +1,7 @@
 """GPU parity: every kernel of the HIP library against the CPU oracle, element by element, on
 the same seeded inputs, through the C ABI.  Bit-exact for pack / unpack / FP8 codes / scales;
-|err| <= 1e-5 * sum_w |x_w| per element for shard_reduce."""
+|err| <= 1e-5 * sum_w |x_w| per element for shard_reduce against the float64 definition, and
+bit for bit against the fp32 sum in the stated order."""
 import numpy as np
 import pytest
 import torch
@@ -65,6 +66,9 @@ def check_reduce(u: Unit, rank, partial_bits, label, poison_padding=True):
     assert np.all(got[~pay] == 0), f"reduce padding not zero ({label})"
     assert not np.any(np.isnan(got))
     assert np.all(err[pay] <= bound[pay]), f"reduce error above bound ({label}): {err.max()}"
+    # and bit for bit the fp32 sum in the library's stated order
+    ordered = OD.shard_reduce_f32_ordered(partial_bits, segs)
+    assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), f"reduce order differs ({label})"
     return got
 
 
@@ -106,6 +110,20 @@ def check_dequant_unpack(u: Unit, codes, scales, want_codes, want_scales, label)
     want = OF.dequant_unpack(u.oracle, want_codes, want_scales)
     for i, (o, w) in enumerate(zip(outs, want)):
         assert np.array_equal(bits_of(o), w), f"dequant_unpack tensor {i} differs ({label})"
+    say(f"unpack_f32 {label}")
+    holders = [torch.full((s.e + 3,), float("nan"), dtype=torch.float32, device="cuda") for s in u.specs]
+    outs32 = [h[1:1 + s.e] for h, s in zip(holders, u.specs)]          # 4-byte aligned views only
+    B.rs_unpack_f32(u.plan, codes, scales, u.table(outs32))
+    torch.cuda.synchronize()
+    for i, (o, w, h) in enumerate(zip(outs32, OF.dequant_unpack_f32(u.oracle, want_codes, want_scales), holders)):
+        assert np.array_equal(o.cpu().numpy().view(np.uint32), w.view(np.uint32)), f"unpack_f32 tensor {i} ({label})"
+        edge = h.cpu().numpy()
+        assert np.isnan(edge[0]) and np.all(np.isnan(edge[1 + w.size:]))
+    aligned = [torch.full((s.e,), float("nan"), dtype=torch.float32, device="cuda") for s in u.specs]
+    B.rs_unpack_f32(u.plan, codes, scales, u.table(aligned))
+    torch.cuda.synchronize()
+    for i, (o, o1) in enumerate(zip(aligned, outs32)):
+        assert torch.equal(o.view(torch.int32), o1.contiguous().view(torch.int32)), f"unpack_f32 aligned {i} ({label})"
 
 
 # ---------------------------------------------------------------------------------------------
@@ -313,6 +331,8 @@ def test_reduce_row_stride_and_large_magnitudes():
         want = OD.shard_reduce(big[:3], u.oracle.rank_segments(1))
         bound = REDUCE_TOL * OD.shard_reduce_abs_sum(big[:3])
         assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - want) <= bound)
+        ordered = OD.shard_reduce_f32_ordered(big[:3], u.oracle.rank_segments(1))
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ordered.view(np.uint32))
     finally:
         u.close()
 

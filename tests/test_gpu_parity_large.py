@@ -81,6 +81,8 @@ def test_config2_reduce(cfg2, rank):
     assert np.all(got[~pay] == 0)
     err = np.abs(got.astype(np.float64) - want)
     assert np.all(err <= REDUCE_TOL * OD.shard_reduce_abs_sum(parts))
+    ordered = OD.shard_reduce_f32_ordered(parts, segs)
+    assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), "fp32 summation order differs"
 
 
 def test_config2_quantize_all_and_by_rank(cfg2):
@@ -121,6 +123,14 @@ def test_config2_dequant_unpack(cfg2):
         want = OF.dequantise_tensor(cfg2.want_codes[l:l + spec.e],
                                     cfg2.want_scales[sb:sb + spec.num_blocks], spec)
         assert np.array_equal(bits_of(outs[i]), want), f"tensor {i}"
+    say("config 2: unpack_f32")
+    outs32 = [torch.empty(p.size, dtype=torch.float32, device="cuda") for p in cfg2.params]
+    B.rs_unpack_f32(u.plan, cfg2.codes, cfg2.scales, u.table(outs32))
+    torch.cuda.synchronize()
+    for i, (spec, l, sb) in enumerate(zip(u.specs, u.oracle.offsets, u.oracle.scale_bases())):
+        want = OF.dequantise_tensor_f32(cfg2.want_codes[l:l + spec.e],
+                                        cfg2.want_scales[sb:sb + spec.num_blocks], spec)
+        assert np.array_equal(outs32[i].cpu().numpy().view(np.uint32), want.view(np.uint32)), f"fp32 tensor {i}"
 
 
 # ---------------------------------------------------------------------------------------------
@@ -211,6 +221,8 @@ def check_reduce_windows(u, wl, rank, partials, out, windows):
         assert np.all(got[~pay] == 0)
         err = np.abs(got.astype(np.float64) - want)
         assert np.all(err <= REDUCE_TOL * OD.shard_reduce_abs_sum(sub)), f"window {a}:{b}"
+        ordered = OD.shard_reduce_f32_ordered(sub, local)
+        assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), f"window {a}:{b} order"
 
 
 def reduce_windows(u, rank, count, width):

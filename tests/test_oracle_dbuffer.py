@@ -83,3 +83,32 @@ def test_reduce_special_cases():
     vals = np.array([[0x3F80], [0x4000], [0x4040], [0x40C0]], dtype=np.uint16)
     assert D.shard_reduce(vals, [(0, 0, 0, 1)])[0] == 3.0
     assert D.shard_reduce_abs_sum(vals)[0] == 12.0
+
+
+def test_ordered_fp32_reduce_stays_within_the_stated_tolerance_and_follows_its_order():
+    from fractions import Fraction
+    wl, pl = toy()
+    for W in (1, 3, 8, 13, 64):
+        S = 4096
+        parts = np.stack([gen_partial(wl, 5, w, S) for w in range(W)])
+        segs = [(0, 0, 0, 1000), (1, 0, 1024, 3000)]
+        exact = D.shard_reduce(parts, segs)
+        got = D.shard_reduce_f32_ordered(parts, segs)
+        bound = 1e-5 * D.shard_reduce_abs_sum(parts)
+        assert np.all(np.abs(got.astype(np.float64) - exact.astype(np.float64)) <= bound)
+        assert np.all(got[1000:1024] == 0) and np.all(got[4024:] == 0)
+        # the order, element by element on a sample, with exact rationals rounded to fp32 at every step
+        def rn(q):
+            return Fraction(float(np.float32(float(q)))) if q != 0 else q   # double holds the exact sum of two fp32
+        for i in (0, 17, 999, 1024, 2500, 4023):
+            sums = [Fraction(0)] * 8
+            for w in range(W):
+                x = Fraction(float(D.bf16_bits_to_f32(parts[w, i:i + 1])[0]))
+                sums[w % 8] = rn(sums[w % 8] + x)
+            tot = rn(rn(rn(sums[0] + sums[1]) + rn(sums[2] + sums[3])) + rn(rn(sums[4] + sums[5]) + rn(sums[6] + sums[7])))
+            inv = Fraction(float(np.float32(1.0) / np.float32(W)))
+            want = np.float32(float(tot * inv))
+            assert got[i] == want, (W, i)
+    # W <= 8 with equal partials and W a power of two: the value itself
+    same = np.repeat(parts[:1], 8, axis=0)
+    assert np.array_equal(D.shard_reduce_f32_ordered(same, [(0, 0, 0, S)]), D.bf16_bits_to_f32(same[0]))

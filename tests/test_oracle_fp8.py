@@ -213,3 +213,27 @@ def test_dequantise_against_library():
         sc = torch.from_numpy(scales[sb + (r // bh) * nbc + c // bw])
         lib = (v * sc).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
         assert np.array_equal(out, lib)
+
+
+def test_dequantise_f32_against_library_and_exact_products():
+    wl, pl = toy_plan()
+    db = ragged_pack(gen_params(wl, seed=6), pl.offsets, pl.total)
+    codes, scales = F.block_quant_all(pl, db)
+    outs32 = F.dequant_unpack_f32(pl, codes, scales)
+    outs16 = F.dequant_unpack(pl, codes, scales)
+    tab = [F.e4m3_value(c) for c in range(256)]
+    for spec, l, sb, o32, o16 in zip(pl.specs, pl.offsets, pl.scale_bases(), outs32, outs16):
+        R, C, bh, bw = F._as_2d(spec)
+        nbc = -(-C // bw)
+        r, c = np.divmod(np.arange(spec.e), C)
+        sidx = sb + (r // bh) * nbc + c // bw
+        # library decode and multiply
+        v = torch.from_numpy(codes[l:l + spec.e].copy()).view(torch.float8_e4m3fn).to(torch.float32)
+        lib = (v * torch.from_numpy(scales[sidx])).numpy()
+        assert o32.dtype == np.float32 and np.array_equal(o32.view(np.uint32), lib.view(np.uint32))
+        # the product of a 4-bit and a 24-bit significand is exact in double: one rounding to fp32
+        val = np.array([tab[k] for k in codes[l:l + spec.e]], dtype=np.float64)
+        once = (val * scales[sidx].astype(np.float64)).astype(np.float32)
+        assert np.array_equal(o32.view(np.uint32), once.view(np.uint32))
+        # rounding it to bf16 gives the bf16 form
+        assert np.array_equal(F.f32_to_bf16_bits(o32), o16)
