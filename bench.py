@@ -31,9 +31,9 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 
 # HBM bytes per launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE), each scaled by what the counter reads for the plain copy launch of known size
-# (fetch x 1.99991, write x 0.99984).  Offline measurements: they cannot be taken inside this
+# (fetch x 1.99991, write x 0.99987).  Offline measurements: they cannot be taken inside this
 # process, so they are recorded here next to the algorithmic bytes they are compared with.
-PMC_TRAFFIC_CONFIG2 = {"ragged_pack": 920.1e6, "shard_reduce": 418.9e6, "block_quant": 10.16e6,
+PMC_TRAFFIC_CONFIG2 = {"ragged_pack": 920.2e6, "shard_reduce": 418.9e6, "block_quant": 319.5e6,
                        "dequant_unpack": 668.5e6}
 
 
