@@ -447,3 +447,81 @@ def test_reordered_plans_all_ops(order):
         check_dequant_unpack(u, c, s, wc, ws, f"order{order}")
     finally:
         u.close()
+
+
+def test_whole_path_replays_from_a_hip_graph():
+    """Device calls neither allocate nor synchronise, so the whole path (pack, reduce, quantise,
+    unpack, Adam step) can be captured once and replayed: three replays on fresh inputs, with eager
+    work and synchronisations in between, each compared with the eager result of the same inputs."""
+    tensors = [(512, 256, MODE_128x128), (300, 0, MODE_1x128), (257, 136, MODE_128x128), (128, 384, MODE_128x128)]
+    W, rank = 4, 1
+    u = Unit(tensors, W)
+    try:
+        S, total = u.S, u.total
+        nb = B.rs_plan_num_scales(u.plan)
+        lo, hi = B.rs_plan_state_range(u.plan, rank)
+
+        def buffers():
+            return dict(
+                src=[torch.zeros(s.e, dtype=torch.bfloat16, device="cuda") for s in u.specs],
+                dst=[torch.zeros(s.e, dtype=torch.bfloat16, device="cuda") for s in u.specs],
+                dbuf=torch.zeros(total, dtype=torch.bfloat16, device="cuda"),
+                parts=torch.zeros(W * S, dtype=torch.bfloat16, device="cuda"),
+                grad=torch.zeros(S, dtype=torch.float32, device="cuda"),
+                codes=torch.zeros(total, dtype=torch.uint8, device="cuda"),
+                scales=torch.zeros(nb, dtype=torch.float32, device="cuda"),
+                master=torch.zeros(S, dtype=torch.float32, device="cuda"),
+                param=torch.zeros(S, dtype=torch.bfloat16, device="cuda"),
+                mc=torch.zeros(S, dtype=torch.int8, device="cuda"), vc=torch.zeros(S, dtype=torch.uint8, device="cuda"),
+                am=torch.zeros(max(hi - lo, 1), dtype=torch.float32, device="cuda"),
+                av=torch.zeros(max(hi - lo, 1), dtype=torch.float32, device="cuda"))
+
+        def path(b, tab_src, tab_dst, stream=None):
+            B.rs_pack(u.plan, tab_src, b["dbuf"], stream)
+            B.rs_reduce(u.plan, rank, b["parts"], S, b["grad"], stream)
+            B.rs_adam8_step(u.plan, rank, (1e-3, 0.9, 0.95, 1e-8, 0.01, 3), b["grad"], b["master"], b["param"],
+                            b["mc"], b["vc"], b["am"], b["av"], stream)
+            B.rs_quantize(u.plan, -1, b["dbuf"], b["codes"], b["scales"], stream)
+            B.rs_unpack(u.plan, b["codes"], b["scales"], tab_dst, stream)
+
+        g_buf, e_buf = buffers(), buffers()
+        g_src, g_dst = u.table(g_buf["src"]), u.table(g_buf["dst"])
+        e_src, e_dst = u.table(e_buf["src"]), u.table(e_buf["dst"])
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            path(g_buf, g_src, g_dst, side)          # warm-up outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        say("capturing the path into a HIP graph")
+        with torch.cuda.graph(graph):
+            path(g_buf, g_src, g_dst)
+        for rep in range(3):
+            params = [normal_bf16(40, rep, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+            parts = np.stack([normal_bf16(40, rep, 1, w, S, 1e-3) for w in range(W)])
+            for b in (g_buf, e_buf):
+                for t, p in zip(b["src"], params):
+                    t.copy_(to_dev_bf16(p))
+                b["parts"].copy_(to_dev_bf16(parts.reshape(-1)))
+                for k in ("master", "mc", "vc", "am", "av"):
+                    b[k].zero_()
+                b["master"].add_(0.01 * (rep + 1))
+            torch.cuda.synchronize()
+            say(f"replay {rep}")
+            graph.replay()
+            path(e_buf, e_src, e_dst)
+            torch.cuda.synchronize()
+            for k in ("dbuf", "grad", "codes", "scales", "master", "param", "mc", "vc", "am", "av"):
+                a, c = g_buf[k], e_buf[k]
+                if a.dtype == torch.bfloat16:
+                    a, c = a.view(torch.int16), c.view(torch.int16)
+                elif a.dtype == torch.float32:
+                    a, c = a.view(torch.int32), c.view(torch.int32)
+                assert torch.equal(a, c), f"{k} differs on replay {rep}"
+            for a, c in zip(g_buf["dst"], e_buf["dst"]):
+                assert torch.equal(a.view(torch.int16), c.view(torch.int16)), f"unpacked tensor differs on replay {rep}"
+            # and the eager result is the oracle's (pack only: the other ops are checked elsewhere)
+            assert np.array_equal(bits_of(e_buf["dbuf"]), OD.ragged_pack(params, u.oracle.offsets, total))
+    finally:
+        u.close()
