@@ -1,0 +1,96 @@
+// Device-side helpers shared by the kernel files: 16-byte vector accesses, the XCD-aware block
+// index remap, bf16 packing, and exact division by a shared divisor.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "rs_internal.h"
+#include "rs_launch.h"
+
+namespace rs {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x4 ld16(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ void st16(void* p, u32x4 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ u32x2 ld8(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+}
+__device__ __forceinline__ void st8(void* p, u32x2 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by block index.  This turns the block index
+// into a work index such that each XCD takes runs of `chunk` consecutive work items (work that is
+// adjacent in memory then shares an XCD's L2 and DRAM pages).  The grid must be a multiple of
+// 8 * chunk; indices at or past the real count are skipped by the caller.
+constexpr int kXcdChunk = 16;  // measured best of 4..256 for block_quant and shard_reduce
+
+__device__ __forceinline__ int64_t xcd_chunked(int64_t block, int chunk) {
+  const int64_t x = block % 8, q = block / 8;
+  return ((q / chunk) * 8 + x) * chunk + q % chunk;
+}
+
+// grid size for `count` work items under xcd_chunked(.., kXcdChunk)
+static inline int64_t xcd_grid(int64_t count) {
+  const int64_t unit = 8 * kXcdChunk;
+  return (count + unit - 1) / unit * unit;
+}
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+__device__ __forceinline__ float bf16_lo(unsigned packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// The divisor of a block (its scale) is shared by all its elements, so the correctly rounded
+// quotient x / scale is obtained without a per-element IEEE division sequence:
+//   r  = RN(1 / b)                      one true division per block
+//   q0 = RN(a * r)                      within 1.5 ulp of a / b
+//   q1 = RN(q0 + RN(a - b * q0) * r)    a faithful rounding of a / b
+//   q2 = RN(q1 + (a - b * q1) * r)      = RN(a / b): from a faithful q1 the residual is exact
+//                                         in an FMA and this last step rounds correctly (Markstein)
+// This holds while no intermediate under- or overflows; whoever builds a Divisor sets `fast`
+// only where that is guaranteed for every quotient that matters, and the plain division is
+// taken otherwise.
+// The sign is re-applied at the end because the corrections turn -0 into +0.
+struct Divisor {
+  float b, r;
+  bool fast;
+};
+
+__device__ __forceinline__ float divide(float a, const Divisor& d) {
+  if (!d.fast) return a / d.b;
+  float q = a * d.r;
+  float e = __builtin_fmaf(-q, d.b, a);
+  q = __builtin_fmaf(e, d.r, q);
+  e = __builtin_fmaf(-q, d.b, a);
+  q = __builtin_fmaf(e, d.r, q);
+  return __builtin_copysignf(q, a);
+}
+
+// A divisor shared by many dividends, with the exact-division shortcut described at `divide`
+// above.  It is taken while the divisor lies in [2^-60, 2^60]: every dividend used with it here
+// is either at most a few hundred times the divisor in magnitude or a square root (never
+// subnormal unless zero), so no intermediate of a quotient that matters under- or overflows.
+__device__ __forceinline__ Divisor shared_divisor(float b) {
+  Divisor d;
+  d.b = b;
+  const unsigned e = (__float_as_uint(b) >> 23) & 0xffu;
+  d.fast = e >= 67u && e < 187u;
+  d.r = d.fast ? 1.0f / b : 0.0f;
+  return d;
+}
+
+// status of the launch just enqueued
+static inline int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }
+
+}  // namespace rs

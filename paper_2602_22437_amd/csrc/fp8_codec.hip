@@ -1,0 +1,460 @@
+// block_quant and dequant_unpack: block-wise FP8 E4M3 of the local shard and its inverse into
+// per-tensor storage (gfx950, wave64; hardware OCP FP8 converts).
+#include "device_util.h"
+
+namespace rs {
+
+constexpr float kE4M3Max = 448.0f;
+
+// -------------------------------------------------------------------------------------------
+// block_quant work-item geometry.
+// A workgroup of 512 lanes owns 128 "row slots" of up to 128 elements: the 128 rows of one
+// 128x128 tile, or 128 consecutive 1x128 blocks.  Lane (r_in, cg) = (tid / 16, tid % 16) handles
+// elements [8*cg, 8*cg + 8) of slots r_in + 32*i, i = 0..3, so one access instruction covers 32
+// slots of 256 contiguous bytes each and a lane keeps four 16-byte vectors in flight.
+// -------------------------------------------------------------------------------------------
+constexpr int kQuantThreads = 512;
+constexpr int kQuantLoads = kItemSlots * 16 / kQuantThreads;  // 4
+constexpr int kQuantRowStep = kQuantThreads / 16;             // 32
+static_assert(kQuantLoads == 4, "the lean path combines exactly four per-lane maxima");
+
+struct Slot {
+  int64_t off;   // element offset inside the tensor of this lane's 8 elements
+  int64_t blk;   // scale index relative to the tensor (1x128 runs only)
+  int ncol;      // how many of the 8 elements exist (0 = nothing to do)
+};
+
+__device__ __forceinline__ Slot tile_slot(const TensorDev& t, int64_t br, int bc, int slot, int col0) {
+  Slot s;
+  const int64_t row = br * 128 + slot;
+  const int64_t col = int64_t(bc) * 128 + col0;
+  s.off = row * t.cols + col;
+  s.blk = 0;
+  const int64_t left = t.cols - col;
+  s.ncol = (row < t.rows && left > 0) ? int(min(int64_t(8), left)) : 0;
+  return s;
+}
+
+__device__ __forceinline__ Slot run_slot(const TensorDev& t, int64_t b0, int count, int slot, int col0) {
+  Slot s;
+  s.blk = b0 + slot;
+  s.off = 0;
+  s.ncol = 0;
+  if (slot >= count) return s;
+  int64_t left;
+  if (t.flags & kFlagContig) {
+    s.off = s.blk * 128 + col0;
+    left = t.e - s.off;
+  } else {
+    const int64_t r = s.blk / t.nbc;
+    const int64_t col = (s.blk - r * t.nbc) * 128 + col0;
+    s.off = r * t.cols + col;
+    left = t.cols - col;
+  }
+  s.ncol = left > 0 ? int(min(int64_t(8), left)) : 0;
+  return s;
+}
+
+__device__ __forceinline__ unsigned abs_max_bits(unsigned m, unsigned packed) {
+  // bf16 magnitudes order like their 15-bit patterns
+  m = max(m, packed & 0x7fffu);
+  return max(m, (packed >> 16) & 0x7fffu);
+}
+
+// The divisor of a block is its scale; see Divisor in device_util.h.  The exact shortcut is taken
+// while kDivFastLo <= amax < kDivFastHi, which rules out under- and overflow of every
+// intermediate for all elements whose quotient is not far below the smallest E4M3 subnormal
+// (those give a zero code either way); blocks outside that range take the plain division.
+constexpr unsigned kDivFastLo = 67u << 7;    // amax >= 2^-60 (bf16 bit pattern)
+constexpr unsigned kDivFastHi = 188u << 7;   // amax <  2^61
+
+__device__ __forceinline__ Divisor make_divisor(unsigned amax_bits) {
+  Divisor d;
+  d.b = __uint_as_float(amax_bits << 16) / kE4M3Max;
+  d.fast = amax_bits >= kDivFastLo && amax_bits < kDivFastHi;
+  d.r = d.fast ? 1.0f / d.b : 0.0f;
+  return d;
+}
+
+__device__ __forceinline__ unsigned quant_pair(unsigned packed, const Divisor& d) {
+  // two bf16 -> two E4M3 codes in the low 16 bits
+  const float a = divide(__uint_as_float(packed << 16), d);
+  const float b = divide(__uint_as_float(packed & 0xffff0000u), d);
+  const float ca = __builtin_amdgcn_fmed3f(a, -kE4M3Max, kE4M3Max);
+  const float cb = __builtin_amdgcn_fmed3f(b, -kE4M3Max, kE4M3Max);
+  return unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xffffu;
+}
+
+__device__ __forceinline__ void zero_fill_bytes(uint8_t* dst, int count, int nthreads) {
+  // dst need not be aligned: bytes up to the first 16-byte line, vectors, bytes after
+  const int head = min(count, int((16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15));
+  const int nvec = (count - head) >> 4;
+  const int tail = (count - head) & 15;
+  const int tid = threadIdx.x;
+  if (tid < head) dst[tid] = 0;
+  for (int v = tid; v < nvec; v += nthreads) st16(dst + head + (v << 4), u32x4{0, 0, 0, 0});
+  if (tid < tail) dst[head + (nvec << 4) + tid] = 0;
+}
+
+// One full work item whose rows are 16-byte structured: 128 slots of exactly 128 elements,
+// slot s at x + s * pitch.  kTile: one scale for the whole item (a 128x128 tile);
+// otherwise one scale per slot (128 consecutive 1x128 blocks), written to scales[slot].
+template <bool kTile>
+__device__ __forceinline__ void quant_full_item(const uint16_t* __restrict__ x,
+                                                uint8_t* __restrict__ codes, int64_t pitch,
+                                                float* __restrict__ scales, unsigned* wave_max) {
+  const int tid = threadIdx.x;
+  const int64_t lane_off = int64_t(tid >> 4) * pitch + (tid & 15) * 8;
+  const int64_t step = int64_t(kQuantRowStep) * pitch;
+  u32x4 v[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) v[i] = ld16(x + lane_off + i * step);
+  unsigned m[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    unsigned a = abs_max_bits(0, v[i].x);
+    a = abs_max_bits(a, v[i].y);
+    a = abs_max_bits(a, v[i].z);
+    m[i] = abs_max_bits(a, v[i].w);
+  }
+  if (kTile) {
+    unsigned a = max(max(m[0], m[1]), max(m[2], m[3]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    __syncthreads();
+    a = wave_max[0];
+#pragma unroll
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
+    if (tid == 0) scales[0] = __uint_as_float(a << 16) / kE4M3Max;
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) m[i] = a;
+  } else {
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) {
+      unsigned a = m[i];
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+      m[i] = a;
+      if ((tid & 15) == 0) scales[(tid >> 4) + kQuantRowStep * i] = __uint_as_float(a << 16) / kE4M3Max;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    u32x2 c{0, 0};
+    if (m[i] != 0) {
+      const Divisor d = make_divisor(m[i]);
+      c.x = quant_pair(v[i].x, d) | (quant_pair(v[i].y, d) << 16);
+      c.y = quant_pair(v[i].z, d) | (quant_pair(v[i].w, d) << 16);
+    }
+    st8(codes + lane_off + i * step, c);
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// block_quant: amax per block (wavefront shuffles, LDS across the 8 waves of a tile),
+// scale = amax / 448, codes = E4M3(clamp(x / scale)) with the hardware RNE convert.
+// x / codes are addressed relative to elem_base (0 or rank * S), scales to scale_off.
+// -------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
+    const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
+    const uint16_t* __restrict__ x_one, uint8_t* __restrict__ codes_one,
+    float* __restrict__ scales_one, void* const* __restrict__ batch, int batch_count,
+    int64_t elem_base, int64_t scale_off, int64_t item_count) {
+  __shared__ unsigned wave_max[kQuantThreads / 64];
+  // batched launch: batch = [shards | codes | scales] pointers of batch_count units
+  const uint16_t* __restrict__ x = x_one;
+  uint8_t* __restrict__ codes = codes_one;
+  float* __restrict__ scales = scales_one;
+  // adjacent tiles of a row of tiles share DRAM pages and cache lines: keep them on one XCD
+  int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
+  if (batch) {
+    // the units' item ranges are laid end to end in one flat grid: no idle tail per unit
+    const int64_t u = idx / item_count;
+    if (u >= batch_count) return;
+    idx -= u * item_count;
+    x = static_cast<const uint16_t*>(batch[u]);
+    codes = static_cast<uint8_t*>(batch[batch_count + u]);
+    scales = static_cast<float*>(batch[2 * batch_count + u]);
+  } else if (idx >= item_count) {
+    return;
+  }
+  const Item it = items[item_off + idx];
+  if (it.tensor < 0) {
+    zero_fill_bytes(codes + (it.first - elem_base), it.count, kQuantThreads);
+    return;
+  }
+  const TensorDev t = T[it.tensor];
+  const bool tile = (t.flags & kFlagTile) != 0;
+  const bool vec = (t.flags & kFlagVec) != 0;
+  const int tid = threadIdx.x;
+  const int r_in = tid >> 4, col0 = (tid & 15) * 8;
+  const int64_t base = t.ell - elem_base;
+
+  // Full, 16-byte-structured items (nearly all of them) take the lean path: no per-slot
+  // bookkeeping, straight-line loads, one reduction, straight-line stores.
+  if (vec) {
+    if (tile) {
+      if ((it.first + 1) * 128 <= t.rows && int64_t(it.count + 1) * 128 <= t.cols) {
+        const int64_t off = base + it.first * 128 * t.cols + int64_t(it.count) * 128;
+        quant_full_item<true>(x + off, codes + off, t.cols,
+                              scales + (t.scale_base + it.first * t.nbc + it.count - scale_off),
+                              wave_max);
+        return;
+      }
+    } else if ((t.flags & kFlagContig) && it.count == kItemSlots &&
+               (it.first + kItemSlots) * 128 <= t.e) {
+      const int64_t off = base + it.first * 128;
+      quant_full_item<false>(x + off, codes + off, 128,
+                             scales + (t.scale_base + it.first - scale_off), wave_max);
+      return;
+    }
+  }
+
+  Slot sl[kQuantLoads];
+  u32x4 v[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    sl[i] = tile ? tile_slot(t, it.first, it.count, r_in + kQuantRowStep * i, col0)
+                 : run_slot(t, it.first, it.count, r_in + kQuantRowStep * i, col0);
+    v[i] = u32x4{0, 0, 0, 0};
+    if (sl[i].ncol == 0) continue;
+    const uint16_t* src = x + base + sl[i].off;
+    if (vec) {
+      v[i] = ld16(src);
+      if (sl[i].ncol < 8) {  // drop what belongs to the next row / lies past the tensor
+        unsigned w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          if (q >= sl[i].ncol) w[q >> 1] &= (q & 1) ? 0x0000ffffu : 0xffff0000u;
+        v[i] = u32x4{w[0], w[1], w[2], w[3]};
+      }
+    } else {
+      unsigned w[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q < sl[i].ncol) w[q >> 1] |= unsigned(src[q]) << ((q & 1) * 16);
+      v[i] = u32x4{w[0], w[1], w[2], w[3]};
+    }
+  }
+
+  // per-slot amax over this lane's 8 elements, then over the 16 lanes of the slot
+  unsigned m[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    unsigned a = 0;
+    a = abs_max_bits(a, v[i].x);
+    a = abs_max_bits(a, v[i].y);
+    a = abs_max_bits(a, v[i].z);
+    a = abs_max_bits(a, v[i].w);
+    m[i] = a;
+  }
+  if (tile) {
+    unsigned a = m[0];
+#pragma unroll
+    for (int i = 1; i < kQuantLoads; ++i) a = max(a, m[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    __syncthreads();
+    a = wave_max[0];
+#pragma unroll
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) m[i] = a;
+    if (tid == 0) {
+      const int64_t sidx = t.scale_base + it.first * t.nbc + it.count - scale_off;
+      scales[sidx] = __uint_as_float(a << 16) / kE4M3Max;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kQuantLoads; ++i) {
+      unsigned a = m[i];
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+      m[i] = a;
+      if ((tid & 15) == 0 && r_in + kQuantRowStep * i < it.count)
+        scales[t.scale_base + sl[i].blk - scale_off] = __uint_as_float(a << 16) / kE4M3Max;
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) {
+    if (sl[i].ncol == 0) continue;
+    u32x2 c{0, 0};
+    if (m[i] != 0) {
+      const Divisor d = make_divisor(m[i]);
+      c.x = quant_pair(v[i].x, d) | (quant_pair(v[i].y, d) << 16);
+      c.y = quant_pair(v[i].z, d) | (quant_pair(v[i].w, d) << 16);
+    }
+    uint8_t* dst = codes + base + sl[i].off;
+    if (vec && sl[i].ncol == 8) {
+      st8(dst, c);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q < sl[i].ncol) dst[q] = uint8_t((q < 4 ? c.x : c.y) >> ((q & 3) * 8));
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// dequant_unpack: codes of the gathered unit -> per-tensor bf16, value(code) * scale then RNE.
+// Buffer-driven like ragged_pack: one single-wavefront workgroup per granule that holds
+// payload; a lane converts 8 codes (one 8-byte load, one 16-byte store) in each quarter of the
+// granule.  No block-wide step is needed, only the block's scale.
+// -------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned bf16_rne(float f) {
+  const unsigned u = __float_as_uint(f);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ void dequant4(unsigned word, float scale, unsigned& lo, unsigned& hi) {
+  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), false);  // bytes 0, 1
+  const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(int(word), true);   // bytes 2, 3
+  lo = pack_bf16(a[0] * scale, a[1] * scale);
+  hi = pack_bf16(b[0] * scale, b[1] * scale);
+}
+
+// scale index (relative to the tensor) of the element at (row, col)
+__device__ __forceinline__ int64_t scale_index(const TensorDev& t, int64_t row, int64_t col) {
+  return ((t.flags & kFlagTile) ? (row >> 7) : row) * t.nbc + (col >> 7);
+}
+
+constexpr int kDequantThreads = 64;
+
+// kF32: the tensors are fp32 (value * scale, no further rounding) instead of bf16
+template <bool kF32>
+__global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
+    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
+    const int32_t* __restrict__ granules, const uint8_t* __restrict__ codes,
+    const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr) {
+  const int64_t gid = granules[blockIdx.x];
+  const int64_t k = gid / gpr;
+  const int64_t i0 = (gid - k * gpr) * kGranule;
+  const int64_t d0 = k * S + i0;
+  const int len = int(min(int64_t(kGranule), S - i0));
+  const int t0 = gran_first[gid];  // a payload granule: t0 < n
+  // A lane converts kGroup codes per access so that its store is one 16-byte vector and a
+  // wavefront's stores are contiguous: 8 codes -> 8 bf16, or 4 codes -> 4 fp32.
+  constexpr int kGroup = kF32 ? 4 : 8;
+  constexpr int kStep = kDequantThreads * kGroup;   // codes per access of the wavefront
+  constexpr int kParts = kGranule / kStep;
+  const int lane = threadIdx.x * kGroup;
+
+  {
+    const TensorDev t = T[t0];
+    uint16_t* out = reinterpret_cast<uint16_t*>(ptrs[t0]);
+    float* out32 = reinterpret_cast<float*>(ptrs[t0]);
+    const bool inside = t.ell <= d0 && d0 + len <= t.ell + t.e;
+    if (inside && (t.flags & kFlagVec) && (reinterpret_cast<uintptr_t>(out) & 15) == 0 &&
+        t.cols < (int64_t(1) << 30)) {
+      // The whole granule lies in one tensor whose rows keep every 8-element group inside one
+      // row and one block.  (row, col) of the granule's first element once per workgroup
+      // (exact: a double holds any element index below 2^53), then 32-bit steps per lane.
+      const int64_t first = d0 - t.ell;
+      int64_t row0 = int64_t(double(first) / double(t.cols));
+      int64_t col0 = first - row0 * t.cols;
+      if (col0 < 0) { col0 += t.cols; --row0; }
+      if (col0 >= t.cols) { col0 -= t.cols; ++row0; }
+      const unsigned C = unsigned(t.cols);
+      const bool contig = (t.flags & kFlagContig) && !(t.flags & kFlagTile);
+      u32x2 c[kParts];
+      float sc[kParts];
+      bool on[kParts];
+#pragma unroll
+      for (int h = 0; h < kParts; ++h) {
+        const int lo = h * kStep + lane;
+        on[h] = lo < len;
+        if (!on[h]) continue;
+        if (kF32)
+          c[h] = u32x2{__builtin_nontemporal_load(reinterpret_cast<const unsigned*>(codes + d0 + lo)), 0};
+        else
+          c[h] = ld8(codes + d0 + lo);
+        int64_t sidx;
+        if (contig) {
+          sidx = (first + lo) >> 7;            // blocks are consecutive runs of 128 elements
+        } else {
+          const unsigned cc = unsigned(col0) + unsigned(lo);
+          const unsigned dr = cc / C;
+          sidx = scale_index(t, row0 + dr, cc - dr * C);
+        }
+        sc[h] = scales[t.scale_base + sidx];
+      }
+#pragma unroll
+      for (int h = 0; h < kParts; ++h) {
+        if (!on[h]) continue;
+        if (kF32) {
+          const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(int(c[h].x), false);
+          const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(int(c[h].x), true);
+          st16(out32 + first + h * kStep + lane,
+               u32x4{__float_as_uint(a[0] * sc[h]), __float_as_uint(a[1] * sc[h]),
+                     __float_as_uint(b[0] * sc[h]), __float_as_uint(b[1] * sc[h])});
+          continue;
+        }
+        unsigned o0, o1, o2, o3;
+        dequant4(c[h].x, sc[h], o0, o1);
+        dequant4(c[h].y, sc[h], o2, o3);
+        st16(out + first + h * kStep + lane, u32x4{o0, o1, o2, o3});
+      }
+      return;
+    }
+  }
+
+  // Granule with tensor boundaries or padding, or a tensor without 16-byte structure:
+  // every element finds its tensor, row and column on its own.
+  int s = t0;
+  for (int h = 0; h < kParts; ++h) {
+    const int lo = h * kStep + lane;
+    if (lo >= len) break;
+    for (int q = 0; q < kGroup; ++q) {
+      const int64_t pos = d0 + lo + q;
+      while (s < n && T[s].ell + T[s].e <= pos) ++s;
+      if (s >= n || T[s].ell > pos) continue;
+      const TensorDev t = T[s];
+      const int64_t i = pos - t.ell;
+      const int64_t row = i / t.cols;
+      const int64_t col = i - row * t.cols;
+      const float scale = scales[t.scale_base + scale_index(t, row, col)];
+      const auto f = __builtin_amdgcn_cvt_pk_f32_fp8(int(codes[pos]), false);
+      if (kF32)
+        reinterpret_cast<float*>(ptrs[s])[i] = f[0] * scale;
+      else
+        reinterpret_cast<uint16_t*>(ptrs[s])[i] = uint16_t(bf16_rne(f[0] * scale));
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// launchers (host)
+// -------------------------------------------------------------------------------------------
+int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
+                       uint8_t* codes, float* scales, void* const* batch, int batch_count,
+                       int64_t elem_base, int64_t scale_off, hipStream_t st) {
+  if (item_count == 0 || (batch && batch_count == 0)) return RS_OK;
+  if (item_count < 0 || item_count > 0x7fffffffLL || batch_count < 0 || batch_count > 65535)
+    return RS_EOVERFLOW;
+  const int64_t work = item_count * (batch ? batch_count : 1);
+  if (work > 0x7fffff00LL) return RS_EOVERFLOW;
+  block_quant_kernel<<<dim3(unsigned(xcd_grid(work))), dim3(kQuantThreads), 0, st>>>(
+      dev.tensors, dev.items, item_off, static_cast<const uint16_t*>(x), codes, scales, batch,
+      batch_count, elem_base, scale_off, item_count);
+  return launched();
+}
+
+int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
+                          const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
+                          int64_t gpr, hipStream_t st) {
+  if (n_payload_gran == 0) return RS_OK;
+  if (n_payload_gran < 0 || n_payload_gran > 0x7fffffffLL) return RS_EOVERFLOW;
+  const dim3 g{unsigned(n_payload_gran)}, b{unsigned(kDequantThreads)};
+  if (f32_out)
+    dequant_unpack_kernel<true><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,
+                                                 codes, scales, ptrs, S, gpr);
+  else
+    dequant_unpack_kernel<false><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,
+                                                  codes, scales, ptrs, S, gpr);
+  return launched();
+}
+
+}  // namespace rs

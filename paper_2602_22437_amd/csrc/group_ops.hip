@@ -1,0 +1,213 @@
+// Group-level operators of the DBuffer and the plain-copy probe (gfx950, wave64).
+//
+// Common shape of the streaming kernels: one 16-byte vector per lane per access and a very large
+// grid (a plain copy on MI355X is fastest that way: no grid-stride loop, no multi-vector tiles),
+// single-wavefront workgroups for copies (measured 3-4 % faster than 256 lanes), non-temporal
+// loads/stores since nothing is reused, and one scalar table lookup per workgroup to find its
+// tensor.  No MFMA: nothing here is a contraction.
+#include "device_util.h"
+
+namespace rs {
+
+// -------------------------------------------------------------------------------------------
+// Group-level operators of the DBuffer: one launch for all tensors of the unit.
+//   pack (copy + zero), its inverse, pack with a scale factor, accumulate (axpy), scale.
+// Four single-wavefront workgroups per granule (kGranule buffer elements of one rank region)
+// that holds payload; the two pack forms add one workgroup per pure-padding granule to zero it,
+// the others never touch padding.  fp32 arithmetic, one rounding to bf16 (nearest even).
+// -------------------------------------------------------------------------------------------
+constexpr int kCopyThreads = 64;
+constexpr int kCopyParts = kGranule / (kCopyThreads * 8);  // workgroups per granule: 4
+
+// d = bf16(d * alpha) / d = bf16(d + alpha * s) on a packed pair; separate multiply and add
+__device__ __forceinline__ unsigned scale_pair(unsigned d, float alpha) {
+  return pack_bf16(bf16_lo(d) * alpha, bf16_hi(d) * alpha);
+}
+__device__ __forceinline__ unsigned axpy_pair(unsigned d, unsigned s, float alpha) {
+  const float lo = alpha * bf16_lo(s), hi = alpha * bf16_hi(s);
+  return pack_bf16(bf16_lo(d) + lo, bf16_hi(d) + hi);
+}
+__device__ __forceinline__ u32x4 scale8(u32x4 d, float alpha) {
+  return u32x4{scale_pair(d.x, alpha), scale_pair(d.y, alpha), scale_pair(d.z, alpha),
+               scale_pair(d.w, alpha)};
+}
+__device__ __forceinline__ u32x4 axpy8(u32x4 d, u32x4 s, float alpha) {
+  return u32x4{axpy_pair(d.x, s.x, alpha), axpy_pair(d.y, s.y, alpha), axpy_pair(d.z, s.z, alpha),
+               axpy_pair(d.w, s.w, alpha)};
+}
+
+template <int kOp>
+__global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
+    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
+    const int32_t* __restrict__ granules, const int32_t* __restrict__ padding,
+    unsigned n_copy_groups, void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S,
+    int64_t gpr, float alpha) {
+  constexpr bool kFillsPadding = kOp == kGroupPack || kOp == kGroupPackScaled;
+  constexpr bool kReadsBuffer = kOp == kGroupUnpack || kOp == kGroupAdd || kOp == kGroupScale;
+  constexpr bool kUsesTensors = kOp != kGroupScale;
+  if (kFillsPadding && blockIdx.x >= n_copy_groups) {
+    // a granule of nothing but padding: this wavefront zeroes all of it
+    const int64_t gid = padding[blockIdx.x - n_copy_groups];
+    const int64_t k = gid / gpr;
+    const int64_t i0 = (gid - k * gpr) * kGranule;
+    const int len = int(min(int64_t(kGranule), S - i0));
+#pragma unroll
+    for (int h = 0; h < kCopyParts; ++h) {
+      const int lo = (h * kCopyThreads + int(threadIdx.x)) * 8;
+      if (lo < len) st16(dbuf + k * S + i0 + lo, u32x4{0, 0, 0, 0});
+    }
+    return;
+  }
+  const unsigned slot = blockIdx.x / kCopyParts, part = blockIdx.x % kCopyParts;
+  const int64_t bid = granules[slot];
+  const int64_t k = bid / gpr;
+  const int64_t i0 = (bid - k * gpr) * kGranule;
+  const int64_t d0 = k * S + i0;
+  const int len = int(min(int64_t(kGranule), S - i0));
+  const int lane_off = (int(part) * kCopyThreads + int(threadIdx.x)) * 8;
+  if (lane_off >= len) return;
+  const int64_t d = d0 + lane_off;
+  const int t0 = gran_first[bid];
+
+  bool empty = t0 >= n;
+  if (!empty) {
+    const int64_t ell = T[t0].ell, end = ell + T[t0].e;
+    if (ell <= d0 && d0 + len <= end) {
+      // the whole granule lies inside tensor t0 (the common case by far)
+      if (!kUsesTensors) {
+        st16(dbuf + d, scale8(ld16(dbuf + d), alpha));
+        return;
+      }
+      uint16_t* base = reinterpret_cast<uint16_t*>(ptrs[t0]) + (d0 - ell);
+      if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
+        if (kOp == kGroupUnpack)
+          st16(base + lane_off, ld16(dbuf + d));
+        else if (kOp == kGroupPack)
+          st16(dbuf + d, ld16(base + lane_off));
+        else if (kOp == kGroupPackScaled)
+          st16(dbuf + d, scale8(ld16(base + lane_off), alpha));
+        else
+          st16(dbuf + d, axpy8(ld16(dbuf + d), ld16(base + lane_off), alpha));
+        return;
+      }
+    }
+    empty = ell >= d0 + len;
+  }
+  if (empty) {  // nothing but padding here
+    if (kFillsPadding) st16(dbuf + d, u32x4{0, 0, 0, 0});
+    return;
+  }
+
+  // Mixed granule (tensor boundaries, padding, or a source that is not 16-byte aligned):
+  // resolve every element on its own.
+  int s = t0;
+  uint16_t vals[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (kReadsBuffer) {
+    const u32x4 v = ld16(dbuf + d);
+    vals[0] = uint16_t(v.x); vals[1] = uint16_t(v.x >> 16);
+    vals[2] = uint16_t(v.y); vals[3] = uint16_t(v.y >> 16);
+    vals[4] = uint16_t(v.z); vals[5] = uint16_t(v.z >> 16);
+    vals[6] = uint16_t(v.w); vals[7] = uint16_t(v.w >> 16);
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int64_t pos = d + q;
+    while (s < n && T[s].ell + T[s].e <= pos) ++s;
+    const bool inside = s < n && T[s].ell <= pos;
+    if (!inside) continue;   // padding keeps what it holds (+0 for the pack forms)
+    if (kOp == kGroupScale) {
+      vals[q] = uint16_t(scale_pair(vals[q], alpha));
+      continue;
+    }
+    uint16_t* elem = reinterpret_cast<uint16_t*>(ptrs[s]) + (pos - T[s].ell);
+    if (kOp == kGroupUnpack)
+      *elem = vals[q];
+    else if (kOp == kGroupPack)
+      vals[q] = *elem;
+    else if (kOp == kGroupPackScaled)
+      vals[q] = uint16_t(scale_pair(*elem, alpha));
+    else
+      vals[q] = uint16_t(axpy_pair(vals[q], *elem, alpha));
+  }
+  if (kOp != kGroupUnpack) {
+    u32x4 v;
+    v.x = vals[0] | (uint32_t(vals[1]) << 16);
+    v.y = vals[2] | (uint32_t(vals[3]) << 16);
+    v.z = vals[4] | (uint32_t(vals[5]) << 16);
+    v.w = vals[6] | (uint32_t(vals[7]) << 16);
+    st16(dbuf + d, v);
+  }
+}
+
+// Pure writes want 256-lane workgroups with one vector per lane (measured 6.9 TB/s against
+// 4.8 TB/s for single-wavefront workgroups and 6.4 TB/s for 4 vectors per lane), the opposite
+// of what copies want.
+constexpr int kFillThreads = 256;
+
+// every element of a buffer of nvec 16-byte vectors becomes +0
+__global__ __launch_bounds__(kFillThreads) void fill_zero_kernel(u32x4* __restrict__ dst, int64_t nvec) {
+  const int64_t i = int64_t(blockIdx.x) * kFillThreads + threadIdx.x;
+  if (i < nvec) dst[i] = u32x4{0, 0, 0, 0};
+}
+
+// -------------------------------------------------------------------------------------------
+// plain copy: the measured ceiling and the counter calibration launch
+// -------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kCopyThreads) void copy_probe_kernel(const u32x4* __restrict__ src,
+                                                                 u32x4* __restrict__ dst,
+                                                                 int64_t nvec) {
+  const int64_t i = int64_t(blockIdx.x) * kCopyThreads + threadIdx.x;
+  if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// -------------------------------------------------------------------------------------------
+// launchers (host)
+// -------------------------------------------------------------------------------------------
+int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf, float alpha,
+                    int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
+                    hipStream_t st) {
+  const bool fills = op == kGroupPack || op == kGroupPackScaled;
+  uint16_t* db = static_cast<uint16_t*>(dbuf);
+  const int64_t copy_groups = n_payload_gran * kCopyParts;
+  // padding is zeroed by extra workgroups of the same launch (a separate fill launch was
+  // measured slower even where padding is 88 % of the buffer)
+  const int64_t grid = copy_groups + (fills ? n_padding_gran : 0);
+  if (grid == 0) return RS_OK;
+  if (grid < 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  const dim3 g{unsigned(grid)}, b{unsigned(kCopyThreads)};
+#define RS_GROUP_OP(OP)                                                                         \
+  group_op_kernel<OP><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,       \
+                                       dev.padding_gran, unsigned(copy_groups), ptrs, db, S,   \
+                                       gpr, alpha)
+  switch (op) {
+    case kGroupPack: RS_GROUP_OP(kGroupPack); break;
+    case kGroupUnpack: RS_GROUP_OP(kGroupUnpack); break;
+    case kGroupPackScaled: RS_GROUP_OP(kGroupPackScaled); break;
+    case kGroupAdd: RS_GROUP_OP(kGroupAdd); break;
+    case kGroupScale: RS_GROUP_OP(kGroupScale); break;
+    default: return RS_EINVAL;
+  }
+#undef RS_GROUP_OP
+  return launched();
+}
+
+int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st) {
+  const int64_t nvec = bytes / 16;
+  const int64_t grid = (nvec + kFillThreads - 1) / kFillThreads;
+  if (grid == 0) return RS_OK;
+  if (grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  fill_zero_kernel<<<dim3(unsigned(grid)), dim3(kFillThreads), 0, st>>>(static_cast<u32x4*>(dst), nvec);
+  return launched();
+}
+
+int launch_copy_probe(void* dst, const void* src, int64_t bytes, hipStream_t st) {
+  const int64_t nvec = bytes / 16;
+  const int64_t grid = (nvec + kCopyThreads - 1) / kCopyThreads;
+  if (grid == 0) return RS_OK;
+  if (grid > 0x7fffffffLL) return RS_EOVERFLOW;
+  copy_probe_kernel<<<dim3(unsigned(grid)), dim3(kCopyThreads), 0, st>>>(
+      static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
+  return launched();
+}
+
+}  // namespace rs

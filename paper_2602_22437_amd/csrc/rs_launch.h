@@ -1,4 +1,4 @@
-// Kernel launchers (kernels.hip) as seen by the C ABI layer.
+// Kernel launchers (the .hip files) as seen by the C ABI layer.
 #pragma once
 #include <hip/hip_runtime_api.h>
 
