@@ -237,6 +237,69 @@ def reduce_windows(u, rank, count, width):
     return [(p, min(S, p + width)) for p in sorted(pts)]
 
 
+def test_config2_batched_quantize_and_adam_as_the_bench_launches_them(cfg2):
+    """The launch shapes bench.py times on config 2 besides the per-unit ones: rank 0's shard of
+    32 units in ONE block_quant launch, and the same for the 8-bit Adam step; every unit's
+    outputs against the oracle (quantise) or against the per-unit launch (Adam)."""
+    from workloads import normal_bf16
+    u, wl = cfg2.unit, WORKLOADS[2]
+    rank, n_units, S = wl.rank, wl.units, cfg2.unit.S
+    lo, hi = u.oracle.scale_range(rank)
+    say(f"config 2: {n_units} rank-{rank} shards on the host")
+    host = [normal_bf16(77, 2, 0, unit, S, 0.02) for unit in range(n_units)]
+    pay = np.zeros(S, dtype=bool)
+    for _, _, d, n in u.oracle.rank_segments(rank):
+        pay[d:d + n] = True
+    for h in host:
+        h[~pay] = 0                           # a packed buffer holds +0 on padding
+    shards = [to_dev_bf16(h) for h in host]
+    codes = [torch.full((S,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(n_units)]
+    scales = [torch.full((hi - lo,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_units)]
+    batch = B.rs_shard_batch_create(u.plan, rank, shards, codes, scales)
+    say("config 2: quantize_batch")
+    B.rs_quantize_batch(u.plan, batch)
+    torch.cuda.synchronize()
+    B.rs_shard_batch_destroy(batch)
+    for unit in range(n_units):
+        oc, os_ = OF.block_quant_shard(u.oracle, rank, host[unit])
+        assert np.array_equal(codes[unit].cpu().numpy(), oc), f"unit {unit} codes"
+        assert np.array_equal(scales[unit].cpu().numpy().view(np.uint32), os_.view(np.uint32)), f"unit {unit} scales"
+
+    slo, shi = B.rs_plan_state_range(u.plan, rank)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(99)
+
+    def state():
+        return dict(
+            g=[torch.empty(S, dtype=torch.float32, device="cuda").normal_(0, 1e-3, generator=gen) for _ in range(n_units)],
+            w=[torch.empty(S, dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=gen) for _ in range(n_units)],
+            p=[torch.zeros(S, dtype=torch.bfloat16, device="cuda") for _ in range(n_units)],
+            mc=[torch.zeros(S, dtype=torch.int8, device="cuda") for _ in range(n_units)],
+            vc=[torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(n_units)],
+            am=[torch.zeros(shi - slo, dtype=torch.float32, device="cuda") for _ in range(n_units)],
+            av=[torch.zeros(shi - slo, dtype=torch.float32, device="cuda") for _ in range(n_units)])
+    a = state()
+    b = {k: [t.clone() for t in v] for k, v in a.items()}
+    ab = B.rs_adam8_batch_create(u.plan, rank, a["g"], a["w"], a["p"], a["mc"], a["vc"], a["am"], a["av"])
+    for step in (1, 2):
+        hyper = (3e-4, 0.9, 0.95, 1e-8, 0.1, step)
+        say(f"config 2: adam8_step_batch, step {step}")
+        B.rs_adam8_step_batch(u.plan, ab, hyper)
+        for i in range(n_units):
+            B.rs_adam8_step(u.plan, rank, hyper, b["g"][i], b["w"][i], b["p"][i], b["mc"][i], b["vc"][i],
+                            b["am"][i], b["av"][i])
+        torch.cuda.synchronize()
+        for k in ("w", "p", "mc", "vc", "am", "av"):
+            for i in range(n_units):
+                x, y = a[k][i], b[k][i]
+                if x.dtype == torch.bfloat16:
+                    x, y = x.view(torch.int16), y.view(torch.int16)
+                elif x.dtype == torch.float32:
+                    x, y = x.view(torch.int32), y.view(torch.int32)
+                assert torch.equal(x, y), f"{k} of unit {i} differs at step {step}"
+    B.rs_adam8_batch_destroy(ab)
+
+
 # ---------------------------------------------------------------------------------------------
 # config 3: whole-matrix sharding (Muon / Shampoo style), W = 32, bf16 only
 # ---------------------------------------------------------------------------------------------
