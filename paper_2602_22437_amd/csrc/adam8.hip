@@ -270,7 +270,7 @@ __global__ __launch_bounds__(kStateThreads) void adam8_step_kernel(
   if (batch) {
     // the same shard of batch_count units, their item ranges end to end in one flat grid;
     // batch = [grad | master | param | m codes | v codes | m absmax | v absmax] pointers
-    const int64_t u = idx / item_count;
+    const int64_t u = unsigned(idx) / unsigned(item_count);   // both below 2^31: a 32-bit division
     if (u >= batch_count) return;
     idx -= u * item_count;
     g = static_cast<const float*>(batch[u]);

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
   int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
   if (batch) {
     // the units' item ranges are laid end to end in one flat grid: no idle tail per unit
-    const int64_t u = idx / item_count;
+    const int64_t u = unsigned(idx) / unsigned(item_count);   // both below 2^31: a 32-bit division
     if (u >= batch_count) return;
     idx -= u * item_count;
     x = static_cast<const uint16_t*>(batch[u]);
