@@ -216,9 +216,11 @@ int rs_unpack_f32(const rs_plan* plan, const uint8_t* codes, const float* scales
 /* ---- block-wise 8-bit optimiser state on the local shard (Section 6.3, "8-bit Adam") ---------
  * The two Adam moments of rank's shard are held as 8-bit codes in blocks that never cross a
  * rank boundary, so a rank updates and re-quantises its state with no communication.
- * State blocks: 32x32 tiles (edge tiles partial) of every 2-D tensor, which must be in
- * RS_BLOCK_32x32 or RS_BLOCK_128x128 mode; runs of 128 elements of every 1-D tensor, which must
- * be in RS_BLOCK_32x32 or RS_BLOCK_1x128 mode; otherwise RS_EUNSUPPORTED.  Blocks are numbered
+ * State blocks are the finest blocks that are whole on a rank: 32x32 tiles (edge tiles partial)
+ * of a 2-D tensor in RS_BLOCK_32x32 or RS_BLOCK_128x128 mode; runs of 128 along each row (the
+ * last run of a row short) of a 2-D tensor in RS_BLOCK_1x128 mode; runs of 128 elements of a
+ * 1-D tensor in RS_BLOCK_32x32 or RS_BLOCK_1x128 mode.  A plan holding any other tensor has no
+ * 8-bit state: RS_EUNSUPPORTED.  Blocks are numbered
  * like FP8 scales: tensor-major in buffer order, block row, block column; a rank owns a
  * contiguous range.  Codes: first moment m, int8, step a/127 (a = the block's max |m|),
  * code = rint(m / step); second moment v >= 0, uint8, step a/255; all-zero block: a = 0,

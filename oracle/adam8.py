@@ -8,7 +8,9 @@ communication.  The paper fixes the block shape and nothing else; the reading ta
 
   state blocks   2-D tensor whose granularity is a multiple of 32 rows (32x32 or 128x128 mode):
                  32x32 tiles, edge tiles partial.  1-D tensor of granularity 128 (32x32 or
-                 1x128 mode): runs of 128 elements.  Other tensors have none.  A rank's
+                 1x128 mode): runs of 128 elements.  2-D tensor of one-row granularity (1x128
+                 mode): runs of 128 along each row, the last run of a row short - the finest
+                 blocks that are whole on a rank there.  Other tensors have none.  A rank's
                  blocks are contiguous in the flat per-unit block order (tensor-major in
                  buffer order, then block row, then block column).
   code maps      linear absmax (the non-linear code book of the cited 8-bit optimiser paper
@@ -43,13 +45,22 @@ from .plan import BLOCK_128x128, BLOCK_1x128, BLOCK_32x32, Plan, TensorSpec, cei
 F = np.float32
 
 
+def state_runs(spec: TensorSpec) -> bool:
+    """True where the state blocks are runs of 128 along each row, False where they are tiles."""
+    if spec.cols == 0 and spec.mode in (BLOCK_1x128, BLOCK_32x32):
+        return True
+    if spec.cols > 0 and spec.mode == BLOCK_1x128:
+        return True
+    if spec.cols > 0 and spec.mode in (BLOCK_128x128, BLOCK_32x32):
+        return False
+    raise ValueError("no 8-bit state blocks for this sharding granularity")
+
+
 def state_grid(spec: TensorSpec) -> Tuple[int, int]:
     """(rows of state blocks, state blocks per row of blocks) of one tensor."""
-    if spec.cols == 0 and spec.mode in (BLOCK_1x128, BLOCK_32x32):
-        return ceil_div(spec.rows, 128), 1
-    if spec.cols > 0 and spec.mode in (BLOCK_128x128, BLOCK_32x32):
-        return ceil_div(spec.rows, 32), ceil_div(spec.cols, 32)
-    raise ValueError("no 8-bit state blocks for this sharding granularity")
+    if state_runs(spec):
+        return (ceil_div(spec.rows, 128), 1) if spec.cols == 0 else (spec.rows, ceil_div(spec.cols, 128))
+    return ceil_div(spec.rows, 32), ceil_div(spec.cols, 32)
 
 
 def state_bases(plan: Plan) -> List[int]:
@@ -74,16 +85,20 @@ def state_range(plan: Plan, k: int) -> Tuple[int, int]:
                 n += ceil_div(have, 128)
             else:
                 assert have % s.cols == 0           # rank boundaries fall between rows
-                n += ceil_div(have // s.cols, 32) * nbc
+                rows = have // s.cols
+                n += rows * nbc if state_runs(s) else ceil_div(rows, 32) * nbc
         return n
     return before(k * plan.S), before((k + 1) * plan.S)
 
 
 def _blocks(R: int, C: int, one_d: bool):
-    """Yields (block index, row slice, col slice) of the state blocks of an (R, C) matrix."""
+    """Yields (block index, row slice, col slice) of the state blocks of an (R, C) matrix:
+    runs of 128 along each row (one_d; a 1-D tensor is the matrix (1, n)), else 32x32 tiles."""
     if one_d:
-        for b in range(ceil_div(C, 128)):
-            yield b, slice(0, 1), slice(b * 128, min(C, (b + 1) * 128))
+        per_row = ceil_div(C, 128)
+        for r in range(R):
+            for b in range(per_row):
+                yield r * per_row + b, slice(r, r + 1), slice(b * 128, min(C, (b + 1) * 128))
         return
     nbc = ceil_div(C, 32)
     for br in range(ceil_div(R, 32)):
@@ -96,7 +111,7 @@ def quantise_state(x: np.ndarray, one_d: bool, signed: bool) -> Tuple[np.ndarray
     R, C = x.shape
     levels = F(127.0) if signed else F(255.0)
     codes = np.zeros((R, C), dtype=np.int16)
-    nblk = ceil_div(C, 128) if one_d else ceil_div(R, 32) * ceil_div(C, 32)
+    nblk = R * ceil_div(C, 128) if one_d else ceil_div(R, 32) * ceil_div(C, 32)
     amax = np.zeros(nblk, dtype=np.float32)
     for b, rs, cs in _blocks(R, C, one_d):
         blk = x[rs, cs].astype(np.float32)
@@ -180,13 +195,16 @@ def adam8_step_shard(plan: Plan, k: int, g, w, param_bits, mc, vc, am, av, h: Hy
     cursor = 0
     for t, src_off, dst_off, n in plan.rank_segments(k):
         spec = plan.specs[t]
-        one_d = spec.cols == 0
-        if one_d:
+        one_d = state_runs(spec)
+        if spec.cols == 0:
             assert src_off % 128 == 0
             R, C = 1, n
             nblk = ceil_div(n, 128)
+        elif one_d:
+            assert src_off % spec.cols == 0 and n % spec.cols == 0
+            R, C = n // spec.cols, spec.cols
+            nblk = R * ceil_div(C, 128)
         else:
-            state_grid(spec)
             assert src_off % (32 * spec.cols) == 0 and n % spec.cols == 0
             R, C = n // spec.cols, spec.cols
             nblk = ceil_div(R, 32) * ceil_div(C, 32)

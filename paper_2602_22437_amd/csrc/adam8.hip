@@ -6,8 +6,8 @@ namespace rs {
 // -------------------------------------------------------------------------------------------
 // adam8_step: AdamW on the local shard with block-wise 8-bit moments.
 // A workgroup of 1024 lanes owns one state work item: 32 rows x 256 columns of a 2-D tensor (a
-// row of eight 32x32 state tiles), or 64 runs of 128 elements of a 1-D tensor seen as 32 rows of
-// 256 elements.  Lane (cq, rw) = (tid % 64, tid / 64) handles the 4 elements at column 4 * cq of
+// row of eight 32x32 state tiles), or 64 runs of 128 elements (1-D tensors, matrices of one-row
+// granularity) seen as 32 rows of 256 elements.  Lane (cq, rw) = (tid % 64, tid / 64) handles the 4 elements at column 4 * cq of
 // rows rw and rw + 16, so one access instruction of a wavefront covers one row (1 KiB of fp32)
 // and a lane's two slots lie in one tile.  (Measured: 256 columns per item beat 512 and 1024,
 // and beat one tile per wavefront by far - narrow row pieces waste DRAM pages; 1024 lanes beat
@@ -44,13 +44,24 @@ __device__ __forceinline__ StateSlot state_slot(const TensorDev& t, const Item& 
       s.blk = int(t.state_base + it.first * t.sbc + (col >> 5) - state_off);
     }
   } else {
-    const int run = 2 * row_in + (cq >> 5);
-    const int64_t elem = (it.first + run) * 128 + 4 * (cq & 31);
-    const int64_t left = t.e - elem;
-    if (run < it.count && left > 0) {
-      s.nv = int(min(int64_t(4), left));
-      s.off = base + elem;
-      s.blk = int(t.state_base + it.first + run - state_off);
+    const int run = 2 * row_in + (cq >> 5);   // run within the item; the item's 32 "rows" hold two each
+    if (run < it.count) {
+      const int64_t q = it.first + run;       // run index within the tensor
+      int64_t elem, left;
+      if (t.flags & kFlagContig) {            // 1-D, or rows that are whole runs: runs are back to back
+        elem = q * 128 + 4 * (cq & 31);
+        left = t.e - elem;
+      } else {                                // the last run of every row is short
+        const int64_t row = q / t.sbc;
+        const int64_t col = (q - row * t.sbc) * 128 + 4 * (cq & 31);
+        elem = row * t.cols + col;
+        left = t.cols - col;
+      }
+      if (left > 0) {
+        s.nv = int(min(int64_t(4), left));
+        s.off = base + elem;
+        s.blk = int(t.state_base + q - state_off);
+      }
     }
   }
   return s;
@@ -285,7 +296,7 @@ __global__ __launch_bounds__(kStateThreads) void adam8_step_kernel(
   }
   const Item it = items[item_off + idx];
   const TensorDev t = T[it.tensor];
-  if (t.flags & kFlagOneD)
+  if (t.flags & kFlagStateRuns)
     adam8_item<false, false>(t, it, g, w, p, mc, vc, am, av, elem_base, state_off, c, tile_max);
   else if ((t.flags & kFlagVec4) && (it.first + 1) * 32 <= t.rows &&
            int64_t(it.count + 1) * kStateCols <= t.cols)

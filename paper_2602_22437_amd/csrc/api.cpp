@@ -73,10 +73,12 @@ int64_t state_blocks_in_front(const rs_plan& plan, int64_t x) {
   for (const rs::TensorHost& h : plan.t) {
     if (!h.state || x <= h.ell) continue;
     const int64_t have = x - h.ell < h.e ? x - h.ell : h.e;
-    if (h.cols > 0)
-      cnt += (have / h.cols + 31) / 32 * h.sbc;
-    else
+    if (h.cols == 0)
       cnt += (have + 127) / 128;
+    else if (h.state_runs)
+      cnt += have / h.cols * h.sbc;
+    else
+      cnt += (have / h.cols + 31) / 32 * h.sbc;
   }
   return cnt;
 }

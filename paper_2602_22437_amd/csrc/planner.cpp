@@ -120,14 +120,19 @@ int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>
       default:
         return RS_EINVAL;
     }
-    // 8-bit optimiser-state blocks: 32x32 tiles where the granularity is whole rows of such
-    // tiles, runs of 128 on 1-D tensors whose granularity is 128
+    // 8-bit optimiser-state blocks, the finest that stay whole on a rank: 32x32 tiles where the
+    // granularity is whole rows of such tiles; runs of 128 along each row where it is one row,
+    // and on 1-D tensors whose granularity is 128
     if (d.cols > 0 && (d.block_mode == RS_BLOCK_32x32 || d.block_mode == RS_BLOCK_128x128)) {
       h.state = true;
       h.sbr = (d.rows + 31) / 32;
       h.sbc = (d.cols + 31) / 32;
+    } else if (d.cols > 0 && d.block_mode == RS_BLOCK_1x128) {
+      h.state = h.state_runs = true;
+      h.sbr = d.rows;
+      h.sbc = (d.cols + 127) / 128;
     } else if (d.cols == 0 && (d.block_mode == RS_BLOCK_32x32 || d.block_mode == RS_BLOCK_1x128)) {
-      h.state = true;
+      h.state = h.state_runs = true;
       h.sbr = (d.rows + 127) / 128;
       h.sbc = 1;
     }

@@ -27,7 +27,7 @@ enum : int32_t {
   kFlagContig = 8,   // 1x128 blocks are back to back in memory (1-D, or C % 128 == 0)
   kFlagState = 16,   // tensor has 8-bit optimiser-state blocks
   kFlagVec4 = 32,    // every row starts 4-element aligned in the buffer (16-byte fp32 vectors)
-  kFlagOneD = 64     // 1-D tensor (state blocks are runs of 128 elements)
+  kFlagStateRuns = 64  // state blocks are runs of 128 along each row (1-D tensors, one-row granularity)
 };
 
 // Per-tensor record on the device (64 bytes).
@@ -49,7 +49,8 @@ struct Item {
   int64_t first;   // tile: block row br;  runs: first block index;  fill: buffer element offset
   int32_t tensor;  // -1 marks a zero-fill item
   int32_t count;   // tile: block column bc;  runs: blocks in this item (<= kItemSlots);  fill: elements
-                   // state items: first = row of 32x32 tiles / first run; count = column strip / runs
+                   // state items: first = row of 32x32 tiles / first run (tensor-wide run index);
+                   //              count = column strip / runs in this item (<= kStateRuns)
 };
 
 struct TensorHost {
@@ -61,7 +62,8 @@ struct TensorHost {
   int64_t scale_base;
   bool quant;
   bool state;          // 8-bit optimiser-state blocks are defined (and whole on a rank)
-  int64_t sbr, sbc;    // state block grid: 32x32 tiles, or (runs of 128) x 1 for 1-D
+  bool state_runs;     // they are runs of 128 along each row (else 32x32 tiles)
+  int64_t sbr, sbc;    // state block grid: rows of blocks x blocks per row
   int64_t state_base;
 };
 

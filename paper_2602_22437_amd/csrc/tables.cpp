@@ -42,7 +42,7 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
     if (one_d || d.cols % 128 == 0) f |= kFlagContig;
     if (h.state) f |= kFlagState;
     if (h.ell % 4 == 0 && (one_d || d.cols % 4 == 0)) f |= kFlagVec4;
-    if (one_d) f |= kFlagOneD;
+    if (h.state_runs) f |= kFlagStateRuns;
     d.flags = f;
     d.state_base = h.state_base;
     d.sbc = int32_t(h.sbc);
@@ -93,7 +93,7 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
       for (int i = first; i < n && t[i].ell < hi; ++i) {
         const TensorHost& h = t[i];
         const int64_t a = std::max(h.ell, lo) - h.ell, b = std::min(h.ell + h.e, hi) - h.ell;
-        if (h.cols > 0) {
+        if (!h.state_runs) {
           const int64_t br_a = a / h.cols / 32, br_b = (b / h.cols + 31) / 32;
           const int64_t strips = (h.cols + kStateCols - 1) / kStateCols;
           for (int64_t br = br_a; br < br_b; ++br)
@@ -105,7 +105,9 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
               out->state_items.push_back(it);
             }
         } else {
-          const int64_t q_a = a / 128, q_b = (b + 127) / 128;
+          // runs of the rank: whole rows of runs (2-D), or runs of a 1-D tensor
+          const int64_t q_a = h.cols > 0 ? a / h.cols * h.sbc : a / 128;
+          const int64_t q_b = h.cols > 0 ? b / h.cols * h.sbc : (b + 127) / 128;
           for (int64_t q = q_a; q < q_b; q += kStateRuns) {
             Item it{};
             it.first = q;

@@ -44,6 +44,10 @@ int main(int argc, char** argv) {
         if (kind < 3) {
           d.rows = pick(1, 3000);
           d.block_mode = kind == 0 ? RS_BLOCK_1x128 : RS_BLOCK_32x32;
+        } else if (kind == 3) {
+          d.rows = pick(1, 90);
+          d.cols = widths[pick(0, 11)];
+          d.block_mode = RS_BLOCK_1x128;
         } else {
           d.rows = pick(1, 300);
           d.cols = widths[pick(0, 11)];
@@ -161,7 +165,7 @@ int main(int argc, char** argv) {
           const rs::Item& it = h.state_items[size_t(q)];
           REQUIRE(it.tensor >= 0 && it.tensor < n);
           const rs::TensorHost& x = t[size_t(it.tensor)];
-          if (x.cols > 0) {
+          if (!x.state_runs) {
             REQUIRE(it.first >= 0 && it.first < x.sbr);
             const int64_t c0 = int64_t(it.count) * rs::kStateCols;
             REQUIRE(c0 < x.cols);
@@ -170,10 +174,22 @@ int main(int argc, char** argv) {
             for (int64_t bc = c0 / 32; bc < std::min<int64_t>(x.sbc, c0 / 32 + rs::kStateCols / 32); ++bc)
               ++seen[size_t(x.state_base + it.first * x.sbc + bc)];
           } else {
-            REQUIRE(it.count > 0 && it.count <= rs::kStateRuns && it.first + it.count <= x.sbr);
-            REQUIRE(x.ell + it.first * 128 >= k * S);
-            REQUIRE(x.ell + std::min(x.e, (it.first + it.count) * 128) <= (k + 1) * S);
-            for (int64_t r = it.first; r < it.first + it.count; ++r) ++seen[size_t(x.state_base + r)];
+            REQUIRE(it.count > 0 && it.count <= rs::kStateRuns && it.first >= 0);
+            REQUIRE(it.first + it.count <= x.sbr * x.sbc);
+            for (int64_t r = it.first; r < it.first + it.count; ++r) {
+              // first and last element of run r
+              int64_t lo, hi;
+              if (x.cols > 0) {
+                const int64_t row = r / x.sbc, bc = r % x.sbc;
+                lo = row * x.cols + bc * 128;
+                hi = row * x.cols + std::min(x.cols, (bc + 1) * 128);
+              } else {
+                lo = r * 128;
+                hi = std::min(x.e, (r + 1) * 128);
+              }
+              REQUIRE(lo < hi && x.ell + lo >= k * S && x.ell + hi <= (k + 1) * S);
+              ++seen[size_t(x.state_base + r)];
+            }
           }
         }
       for (int v : seen) REQUIRE(v == 1);

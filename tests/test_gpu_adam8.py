@@ -86,6 +86,9 @@ UNITS = [
     ([(64, 36, MODE_32x32), (100, 0, MODE_32x32), (37, 35, MODE_32x32)], 3, 1),
     ([(64, 64, MODE_32x32)], 5, 0),                      # most ranks empty
     ([(64, 1100, MODE_32x32), (16384, 0, MODE_32x32)], 2, 0),   # 5 column strips, the last partial; many runs
+    # matrices of one-row granularity: runs of 128 along each row, back to back (256) or with a short last run
+    ([(40, 200, MODE_1x128), (128, 256, MODE_128x128), (33, 136, MODE_1x128), (70, 256, MODE_1x128), (500, 0, MODE_1x128)], 3, 0),
+    ([(19, 130, MODE_1x128), (7, 33, MODE_1x128)], 2, 1),       # A = 1, pitch not a multiple of 4
 ]
 
 
@@ -232,5 +235,21 @@ def test_adam8_gpt_oss_shard_with_partial_column_strips():
     u = Unit.from_workload(WORKLOADS[4])
     try:
         run_steps(u, 0, 1400, hypers(2, lr=3e-4), "gpt-oss rank 0")
+    finally:
+        u.close()
+
+
+def test_adam8_deepseek_shared_expert_rows():
+    """Config 5 (W = 1024): the ranks that hold the shared expert's matrices, whose granularity is
+    one row and whose state blocks are therefore runs of 128 along each row, next to the last
+    routed expert's 32x32 tiles."""
+    wl = WORKLOADS[5]
+    u = Unit.from_workload(wl)
+    try:
+        first_shared = len(wl.tensors) - 3
+        l = u.oracle.offsets[first_shared]
+        ranks = sorted({l // u.S - 1, l // u.S, (u.oracle.offsets[-1] + u.specs[-1].e - 1) // u.S})
+        for k in ranks:
+            run_steps(u, int(k), 1500 + int(k), hypers(2, lr=3e-4), f"deepseek rank {k}")
     finally:
         u.close()

@@ -219,8 +219,10 @@ def test_state_block_layout_matches_oracle():
                 tensors.append((rnd.randint(1, 1500), 0, rnd.choice([B.RS_BLOCK_32x32, B.RS_BLOCK_1x128])))
             elif kind < 0.8:
                 tensors.append((rnd.randint(1, 300), rnd.choice([8, 30, 32, 40, 100, 256, 300, 1100]), B.RS_BLOCK_32x32))
-            else:
+            elif kind < 0.9:
                 tensors.append((rnd.randint(1, 300), rnd.choice([24, 128, 130, 256]), B.RS_BLOCK_128x128))
+            else:
+                tensors.append((rnd.randint(1, 80), rnd.choice([8, 40, 128, 200, 384]), B.RS_BLOCK_1x128))
         world = rnd.choice([1, 2, 3, 4, 7, 16, 33])
         specs = [P.TensorSpec(*t) for t in tensors]
         want = P.make_plan(specs, world, 16, 1)
@@ -233,7 +235,7 @@ def test_state_block_layout_matches_oracle():
                 assert B.rs_plan_state_range(plan, k) == OA.state_range(want, k)
         finally:
             B.rs_plan_destroy(plan)
-    for bad in ([(64, 256, B.RS_BLOCK_1x128)], [(64, 64, B.RS_BLOCK_WHOLE)], [(512, 0, B.RS_BLOCK_EXPLICIT, 128)]):
+    for bad in ([(64, 64, B.RS_BLOCK_WHOLE)], [(512, 0, B.RS_BLOCK_EXPLICIT, 128)]):
         plan = B.rs_plan_create(bad, 2, 16, 1)
         try:
             with pytest.raises(B.RaggedShardError) as e:

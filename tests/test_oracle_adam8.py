@@ -191,6 +191,7 @@ UNITS = [
       (1000, 0, P.BLOCK_32x32)], 4),
     ([(256, 128, P.BLOCK_128x128), (300, 0, P.BLOCK_1x128), (257, 130, P.BLOCK_128x128)], 3),
     ([(64, 64, P.BLOCK_32x32)], 5),
+    ([(40, 200, P.BLOCK_1x128), (128, 256, P.BLOCK_128x128), (33, 136, P.BLOCK_1x128), (500, 0, P.BLOCK_1x128)], 3),
 ]
 
 
@@ -206,7 +207,7 @@ def test_state_ranges_by_brute_force_ownership(unit):
     bases = A.state_bases(pl)
     owner_of_block = {}
     for t, (s, l) in enumerate(zip(specs, pl.offsets)):
-        R, C, one_d = (1, s.rows, True) if s.cols == 0 else (s.rows, s.cols, False)
+        R, C, one_d = (1, s.rows, True) if s.cols == 0 else (s.rows, s.cols, A.state_runs(s))
         for b, rs, cs in A._blocks(R, C, one_d):
             owners = set()
             for r in range(rs.start, rs.stop):
@@ -221,9 +222,17 @@ def test_state_ranges_by_brute_force_ownership(unit):
 
 
 def test_unsupported_granularity_is_refused():
-    specs = [P.TensorSpec(64, 256, P.BLOCK_1x128)]
-    with pytest.raises(ValueError):
-        A.state_grid(specs[0])
+    for spec in (P.TensorSpec(64, 256, P.BLOCK_WHOLE), P.TensorSpec(640, 0, P.BLOCK_EXPLICIT, 128)):
+        with pytest.raises(ValueError):
+            A.state_grid(spec)
+
+
+def test_row_runs_are_blocks_of_one_row():
+    y = np.zeros((3, 300), dtype=np.float32)
+    y[0, 127], y[0, 128], y[1, 299], y[2, 0] = 7, 8, 9, -3
+    _, amax = A.quantise_state(y, True, True)
+    assert amax.tolist() == [7, 8, 0, 0, 0, 9, 3, 0, 0]
+    assert A.state_grid(P.TensorSpec(3, 300, P.BLOCK_1x128)) == (3, 3)
 
 
 @pytest.mark.parametrize("unit", UNITS)
@@ -238,7 +247,7 @@ def test_rank_local_step_equals_whole_tensor_step(unit):
     AM, AV = np.zeros(bases[-1], np.float32), np.zeros(bases[-1], np.float32)
     want = dict(W=W.copy(), Pb=np.zeros(tot, np.uint16), MC=MC.copy(), VC=VC.copy(), AM=AM.copy(), AV=AV.copy())
     for t, (s, l) in enumerate(zip(specs, pl.offsets)):
-        R, C, one_d = (1, s.rows, True) if s.cols == 0 else (s.rows, s.cols, False)
+        R, C, one_d = (1, s.rows, True) if s.cols == 0 else (s.rows, s.cols, A.state_runs(s))
         g = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
         w = (rng.standard_normal((R, C)) * 0.02).astype(np.float32)
         mc, am = A.quantise_state((rng.standard_normal((R, C)) * 1e-3).astype(np.float32), one_d, True)
