@@ -230,6 +230,19 @@ int64_t rs_plan_num_state_blocks(const rs_plan* plan);   /* whole unit; RS_EUNSU
 int rs_plan_state_bases(const rs_plan* plan, int64_t* out, int cap);
 int rs_plan_state_range(const rs_plan* plan, int rank, int64_t* lo, int64_t* hi);
 
+/* The codec on its own over rank's shard, one launch each (state initialised from, or exported to,
+ * fp32 moments).  is_unsigned = 0: the first-moment map (int8, step a/127, a = max |x| of the
+ * block); 1: the second-moment map (uint8, step a/255, a = max x, inputs >= 0).
+ *   rs_state_quantize    codes = rint(src / step), absmax = a per block  (all-zero block: 0, codes 0)
+ *   rs_state_dequantize  dst = code * (absmax / levels), one fp32 division per block, one multiply
+ * src / dst: device fp32, S elements at the region's element offsets; codes: device, S bytes;
+ * absmax: device fp32, the rank's slice of the block array.  Bases 16-byte aligned (absmax: 4).
+ * Padding positions are neither read nor written. */
+int rs_state_quantize(const rs_plan* plan, int rank, const float* src, int is_unsigned, void* codes,
+                      float* absmax, void* stream);
+int rs_state_dequantize(const rs_plan* plan, int rank, const void* codes, const float* absmax,
+                        int is_unsigned, float* dst, void* stream);
+
 typedef struct rs_adam8_hyper {
   double lr, beta1, beta2, eps, weight_decay;
   int64_t step;        /* 1 for the first update */

@@ -136,6 +136,49 @@ def dequantise_state(codes: np.ndarray, amax: np.ndarray, one_d: bool, signed: b
     return out
 
 
+def _segments(plan: Plan, k: int):
+    """(dst_off, n, R, C, runs, blocks) of every segment of rank k's region: a segment is a run of
+    whole granules of one tensor, i.e. a matrix of whole state blocks."""
+    out = []
+    for t, src_off, dst_off, n in plan.rank_segments(k):
+        spec = plan.specs[t]
+        runs = state_runs(spec)
+        if spec.cols == 0:
+            assert src_off % 128 == 0
+            R, C, nblk = 1, n, ceil_div(n, 128)
+        else:
+            assert n % spec.cols == 0 and src_off % (spec.cols if runs else 32 * spec.cols) == 0
+            R, C = n // spec.cols, spec.cols
+            nblk = R * ceil_div(C, 128) if runs else ceil_div(R, 32) * ceil_div(C, 32)
+        out.append((dst_off, n, R, C, runs, nblk))
+    return out
+
+
+def quantise_shard(plan: Plan, k: int, x: np.ndarray, codes: np.ndarray, signed: bool):
+    """The codec on its own over rank k's region: x (S,) fp32 -> (codes, absmax slice).
+    `codes` gives the array's padding contents (they are kept); int8 when signed, else uint8."""
+    codes = codes.copy()
+    amax = []
+    for dst_off, n, R, C, runs, _ in _segments(plan, k):
+        c, a = quantise_state(x[dst_off:dst_off + n].reshape(R, C), runs, signed)
+        codes[dst_off:dst_off + n] = c.reshape(-1).astype(codes.dtype)
+        amax.append(a)
+    return codes, (np.concatenate(amax).astype(np.float32) if amax else np.zeros(0, np.float32))
+
+
+def dequantise_shard(plan: Plan, k: int, codes: np.ndarray, amax: np.ndarray, out: np.ndarray, signed: bool):
+    """Inverse map over rank k's region: value(code) = code * (absmax / levels); `out` gives the
+    fp32 array's padding contents (they are kept)."""
+    out = out.copy()
+    cursor = 0
+    for dst_off, n, R, C, runs, nblk in _segments(plan, k):
+        c = codes[dst_off:dst_off + n].astype(np.int16).reshape(R, C)
+        out[dst_off:dst_off + n] = dequantise_state(c, amax[cursor:cursor + nblk], runs, signed).reshape(-1)
+        cursor += nblk
+    assert cursor == amax.size
+    return out
+
+
 @dataclass
 class Hyper:
     lr: float

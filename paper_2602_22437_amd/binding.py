@@ -26,6 +26,7 @@ EXPORTS = [
     "rs_pack_scaled", "rs_group_add", "rs_group_scale", "rs_group_zero",
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
+    "rs_state_quantize", "rs_state_dequantize",
 ]
 
 
@@ -104,6 +105,8 @@ _lib.rs_plan_num_state_blocks.restype = C.c_int64
 _lib.rs_plan_state_bases.argtypes = [_P, C.POINTER(C.c_int64), C.c_int]
 _lib.rs_plan_state_range.argtypes = [_P, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 _lib.rs_adam8_step.argtypes = [_P, C.c_int, C.POINTER(rs_adam8_hyper), _P, _P, _P, _P, _P, _P, _P, _P]
+_lib.rs_state_quantize.argtypes = [_P, C.c_int, _P, C.c_int, _P, _P, _P]
+_lib.rs_state_dequantize.argtypes = [_P, C.c_int, _P, _P, C.c_int, _P, _P]
 _lib.rs_adam8_batch_create.argtypes = [_P, C.c_int, C.c_int] + [C.POINTER(_P)] * 7 + [C.POINTER(_P)]
 _lib.rs_adam8_batch_destroy.argtypes = [_P]
 _lib.rs_adam8_batch_destroy.restype = None
@@ -340,6 +343,16 @@ def rs_plan_state_range(plan, rank: int) -> Tuple[int, int]:
     lo, hi = C.c_int64(), C.c_int64()
     _check(_lib.rs_plan_state_range(plan, int(rank), C.byref(lo), C.byref(hi)), "rs_plan_state_range")
     return lo.value, hi.value
+
+
+def rs_state_quantize(plan, rank: int, src, is_unsigned: bool, codes, absmax, stream=None) -> None:
+    _check(_lib.rs_state_quantize(plan, int(rank), _ptr(src), int(bool(is_unsigned)), _ptr(codes), _ptr(absmax),
+                                  _stream(stream)), "rs_state_quantize")
+
+
+def rs_state_dequantize(plan, rank: int, codes, absmax, is_unsigned: bool, dst, stream=None) -> None:
+    _check(_lib.rs_state_dequantize(plan, int(rank), _ptr(codes), _ptr(absmax), int(bool(is_unsigned)), _ptr(dst),
+                                    _stream(stream)), "rs_state_dequantize")
 
 
 def _hyper(hyper) -> rs_adam8_hyper:

@@ -306,6 +306,134 @@ __global__ __launch_bounds__(kStateThreads) void adam8_step_kernel(
 }
 
 // -------------------------------------------------------------------------------------------
+// The 8-bit codec on its own, same work items and lane mapping as the step:
+//   kQuant:  fp32 -> codes + absmax (the block maximum by shuffles and LDS, as in the step)
+//   else:    codes + absmax -> fp32
+// is_unsigned selects the second-moment map (0..255) instead of the first-moment one (-127..127).
+// -------------------------------------------------------------------------------------------
+template <bool kQuant, bool kTile>
+__device__ __forceinline__ void state_codec_item(const TensorDev& t, const Item& it,
+                                                 float* __restrict__ x, uint8_t* __restrict__ codes,
+                                                 float* __restrict__ absmax, bool is_unsigned,
+                                                 int64_t elem_base, int64_t state_off,
+                                                 float (*tile_max)[kStateCols / 32]) {
+  const int tid = threadIdx.x;
+  const int cq = tid & 63, rw = tid >> 6;
+  const bool vec = (t.flags & kFlagVec4) != 0;
+  const int64_t base = t.ell - elem_base;
+  const float levels = is_unsigned ? 255.0f : 127.0f;
+
+  StateSlot sl[kStateSlots];
+  float v[kStateSlots][4];
+  float vmax[kStateSlots];
+#pragma unroll
+  for (int i = 0; i < kStateSlots; ++i) {
+    sl[i] = state_slot<kTile>(t, it, rw + kStateWaves * i, cq, base, state_off);
+    vmax[i] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[i][j] = 0.0f;
+    if (sl[i].nv == 0) continue;
+    if (kQuant) {
+      if (vec && sl[i].nv == 4) {
+        const u32x4 q = ld16(x + sl[i].off);
+        v[i][0] = __uint_as_float(q.x);
+        v[i][1] = __uint_as_float(q.y);
+        v[i][2] = __uint_as_float(q.z);
+        v[i][3] = __uint_as_float(q.w);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (j < sl[i].nv) v[i][j] = x[sl[i].off + j];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) vmax[i] = fmaxf(vmax[i], is_unsigned ? v[i][j] : __builtin_fabsf(v[i][j]));
+    } else {
+      unsigned c = 0;
+      if (vec && sl[i].nv == 4) {
+        c = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(codes + sl[i].off));
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (j < sl[i].nv) c |= unsigned(codes[sl[i].off + j]) << (8 * j);
+      }
+      const float step = quant_step(absmax[sl[i].blk], levels);
+      float out[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const unsigned b = (c >> (8 * j)) & 0xffu;
+        out[j] = (is_unsigned ? float(b) : float(int(int8_t(b)))) * step;
+      }
+      if (vec && sl[i].nv == 4) {
+        st16(x + sl[i].off, u32x4{__float_as_uint(out[0]), __float_as_uint(out[1]),
+                                  __float_as_uint(out[2]), __float_as_uint(out[3])});
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (j < sl[i].nv) x[sl[i].off + j] = out[j];
+      }
+    }
+  }
+  if (!kQuant) return;
+
+  if (kTile) {
+    float a = vmax[0];
+#pragma unroll
+    for (int i = 1; i < kStateSlots; ++i) a = fmaxf(a, vmax[i]);
+#pragma unroll
+    for (int off = 1; off <= 4; off <<= 1) a = fmaxf(a, __shfl_xor(a, off));
+    if ((cq & 7) == 0) tile_max[rw][cq >> 3] = a;
+    __syncthreads();
+    a = tile_max[0][cq >> 3];
+#pragma unroll
+    for (int q = 1; q < kStateWaves; ++q) a = fmaxf(a, tile_max[q][cq >> 3]);
+    if (rw == 0 && (cq & 7) == 0 && sl[0].nv > 0) absmax[sl[0].blk] = a;
+#pragma unroll
+    for (int i = 0; i < kStateSlots; ++i) vmax[i] = a;
+  } else {
+#pragma unroll
+    for (int i = 0; i < kStateSlots; ++i) {
+      float a = vmax[i];
+#pragma unroll
+      for (int off = 1; off <= 16; off <<= 1) a = fmaxf(a, __shfl_xor(a, off));
+      vmax[i] = a;
+      if ((cq & 31) == 0 && sl[i].nv > 0) absmax[sl[i].blk] = a;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kStateSlots; ++i) {
+    if (sl[i].nv == 0) continue;
+    const Divisor step = shared_divisor(quant_step(vmax[i], levels));
+    const float lo = is_unsigned ? 0.0f : -127.0f;
+    unsigned c = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c |= (unsigned(state_code(v[i][j], vmax[i], step, lo, levels)) & 0xffu) << (8 * j);
+    if (vec && sl[i].nv == 4) {
+      __builtin_nontemporal_store(c, reinterpret_cast<unsigned*>(codes + sl[i].off));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (j < sl[i].nv) codes[sl[i].off + j] = uint8_t(c >> (8 * j));
+    }
+  }
+}
+
+template <bool kQuant>
+__global__ __launch_bounds__(kStateThreads) void state_codec_kernel(
+    const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
+    int64_t item_count, float* __restrict__ x, uint8_t* __restrict__ codes,
+    float* __restrict__ absmax, int is_unsigned, int64_t elem_base, int64_t state_off) {
+  __shared__ float tile_max[kStateWaves][kStateCols / 32];
+  const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
+  if (idx >= item_count) return;
+  const Item it = items[item_off + idx];
+  const TensorDev t = T[it.tensor];
+  if (t.flags & kFlagStateRuns)
+    state_codec_item<kQuant, false>(t, it, x, codes, absmax, is_unsigned != 0, elem_base, state_off, tile_max);
+  else
+    state_codec_item<kQuant, true>(t, it, x, codes, absmax, is_unsigned != 0, elem_base, state_off, tile_max);
+}
+
+// -------------------------------------------------------------------------------------------
 // launcher (host)
 // -------------------------------------------------------------------------------------------
 int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_count, const float* grad,
@@ -320,6 +448,21 @@ int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_co
       dev.tensors, dev.state_items, item_off, item_count, grad, master,
       static_cast<uint16_t*>(param_bf16), reinterpret_cast<uint8_t*>(m_codes), v_codes, m_absmax,
       v_absmax, batch, batch_count, elem_base, state_off, c);
+  return launched();
+}
+
+int launch_state_codec(bool quantise, const DeviceTables& dev, int64_t item_off, int64_t item_count,
+                       float* x, uint8_t* codes, float* absmax, bool is_unsigned, int64_t elem_base,
+                       int64_t state_off, hipStream_t st) {
+  if (item_count == 0) return RS_OK;
+  if (item_count < 0 || item_count > 0x7fffff00LL) return RS_EOVERFLOW;
+  const dim3 g{unsigned(xcd_grid(item_count))}, b{unsigned(kStateThreads)};
+  if (quantise)
+    state_codec_kernel<true><<<g, b, 0, st>>>(dev.tensors, dev.state_items, item_off, item_count, x,
+                                              codes, absmax, is_unsigned ? 1 : 0, elem_base, state_off);
+  else
+    state_codec_kernel<false><<<g, b, 0, st>>>(dev.tensors, dev.state_items, item_off, item_count, x,
+                                               codes, absmax, is_unsigned ? 1 : 0, elem_base, state_off);
   return launched();
 }
 

@@ -503,6 +503,35 @@ int rs_adam8_step(const rs_plan* plan, int rank, const rs_adam8_hyper* hyper, co
                                static_cast<hipStream_t>(stream));
 }
 
+static int state_codec(bool quantise, const rs_plan* plan, int rank, float* x, void* codes,
+                       float* absmax, int is_unsigned, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_state) return RS_EUNSUPPORTED;
+  if (!x || !codes || rank < 0 || rank >= plan->world || (is_unsigned != 0 && is_unsigned != 1))
+    return RS_EINVAL;
+  const int64_t nblk = plan->state_begin[size_t(rank) + 1] - plan->state_begin[size_t(rank)];
+  if (nblk > 0 && !absmax) return RS_EINVAL;
+  if (!aligned16(x) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(absmax) & 3)) return RS_EALIGN;
+  const std::vector<int64_t>& ib = plan->host.state_item_begin;
+  return rs::launch_state_codec(quantise, plan->dev, ib[size_t(rank)],
+                                ib[size_t(rank) + 1] - ib[size_t(rank)], x,
+                                static_cast<uint8_t*>(codes), absmax, is_unsigned != 0,
+                                int64_t(rank) * plan->S, plan->state_begin[size_t(rank)],
+                                static_cast<hipStream_t>(stream));
+}
+
+int rs_state_quantize(const rs_plan* plan, int rank, const float* src, int is_unsigned, void* codes,
+                      float* absmax, void* stream) {
+  return state_codec(true, plan, rank, const_cast<float*>(src), codes, absmax, is_unsigned, stream);
+}
+
+int rs_state_dequantize(const rs_plan* plan, int rank, const void* codes, const float* absmax,
+                        int is_unsigned, float* dst, void* stream) {
+  return state_codec(false, plan, rank, dst, const_cast<void*>(codes), const_cast<float*>(absmax),
+                     is_unsigned, stream);
+}
+
 int rs_adam8_batch_create(const rs_plan* plan, int rank, int count, const float* const* grads,
                           float* const* masters, void* const* params_bf16, int8_t* const* m_codes,
                           uint8_t* const* v_codes, float* const* m_absmax, float* const* v_absmax,

@@ -28,6 +28,10 @@ int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_co
                       float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,
                       float* m_absmax, float* v_absmax, void* const* batch, int batch_count,
                       int64_t elem_base, int64_t state_off, const Adam8Consts& c, hipStream_t st);
+// the 8-bit codec on its own: fp32 -> codes + absmax (quantise) or back (x is then the output)
+int launch_state_codec(bool quantise, const DeviceTables& dev, int64_t item_off, int64_t item_count,
+                       float* x, uint8_t* codes, float* absmax, bool is_unsigned, int64_t elem_base,
+                       int64_t state_off, hipStream_t st);
 int launch_copy_probe(void* dst, const void* src, int64_t bytes, hipStream_t st);
 
 }  // namespace rs

@@ -253,3 +253,73 @@ def test_adam8_deepseek_shared_expert_rows():
             run_steps(u, int(k), 1500 + int(k), hypers(2, lr=3e-4), f"deepseek rank {k}")
     finally:
         u.close()
+
+
+@pytest.mark.parametrize("case", range(len(UNITS)))
+def test_state_codec_units_every_rank(case):
+    """rs_state_quantize / rs_state_dequantize against the oracle's codec, both maps, bit for bit."""
+    tensors, world, A = UNITS[case]
+    u = Unit(tensors, world, 16, 1, A)
+    try:
+        S = u.S
+        for k in range(world):
+            pay = np.zeros(S, dtype=bool)
+            for _, _, d, n in u.oracle.rank_segments(k):
+                pay[d:d + n] = True
+            lo, hi = OA.state_range(u.oracle, k)
+            rng = np.random.default_rng(7000 + 10 * case + k)
+            for unsigned in (False, True):
+                x = (rng.standard_normal(S) * 1e-3).astype(np.float32)
+                if unsigned:
+                    x = x * x
+                x[pay & (rng.random(S) < 0.02)] = 0.0
+                x[~pay] = np.nan
+                pad_codes = np.full(S, 0x55, np.uint8 if unsigned else np.int8)
+                say(f"state codec unit{case} rank {k} unsigned={unsigned}")
+                d_codes = torch.from_numpy(pad_codes.copy()).cuda()
+                d_am = torch.full((hi - lo + 1,), 7.0, dtype=torch.float32, device="cuda")
+                B.rs_state_quantize(u.plan, k, torch.from_numpy(x).cuda(), unsigned, d_codes, d_am)
+                torch.cuda.synchronize()
+                want_c, want_a = OA.quantise_shard(u.oracle, k, x, pad_codes, not unsigned)
+                diff(d_codes.cpu().numpy(), want_c, "codes")
+                diff(d_am.cpu().numpy()[:hi - lo].view(np.uint32), want_a.view(np.uint32), "absmax")
+                assert d_am.cpu().numpy()[hi - lo] == 7.0
+                d_out = torch.full((S,), 9.0, dtype=torch.float32, device="cuda")
+                B.rs_state_dequantize(u.plan, k, d_codes, d_am, unsigned, d_out)
+                torch.cuda.synchronize()
+                want = OA.dequantise_shard(u.oracle, k, want_c, want_a, np.full(S, 9.0, np.float32), not unsigned)
+                diff(d_out.cpu().numpy().view(np.uint32), want.view(np.uint32), "dequantised")
+    finally:
+        u.close()
+
+
+def test_state_codec_feeds_the_adam_step():
+    """Moments quantised by rs_state_quantize are the state rs_adam8_step continues from."""
+    u = Unit(UNITS[0][0], UNITS[0][1])
+    try:
+        S, k = u.S, 2
+        lo, hi = OA.state_range(u.oracle, k)
+        rng = np.random.default_rng(8123)
+        m0 = (rng.standard_normal(S) * 1e-3).astype(np.float32)
+        v0 = ((rng.standard_normal(S) * 1e-3) ** 2).astype(np.float32)
+        g = (rng.standard_normal(S) * 1e-3).astype(np.float32)
+        w = (rng.standard_normal(S) * 0.02).astype(np.float32)
+        mc, vc = torch.zeros(S, dtype=torch.int8, device="cuda"), torch.zeros(S, dtype=torch.uint8, device="cuda")
+        am, av = (torch.zeros(hi - lo, dtype=torch.float32, device="cuda") for _ in range(2))
+        B.rs_state_quantize(u.plan, k, torch.from_numpy(m0).cuda(), False, mc, am)
+        B.rs_state_quantize(u.plan, k, torch.from_numpy(v0).cuda(), True, vc, av)
+        d_w = torch.from_numpy(w).cuda()
+        d_p = torch.zeros(S, dtype=torch.bfloat16, device="cuda")
+        h = OA.Hyper(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, step=5)
+        B.rs_adam8_step(u.plan, k, (h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step),
+                        torch.from_numpy(g).cuda(), d_w, d_p, mc, vc, am, av)
+        torch.cuda.synchronize()
+        omc, oam = OA.quantise_shard(u.oracle, k, m0, np.zeros(S, np.int8), True)
+        ovc, oav = OA.quantise_shard(u.oracle, k, v0, np.zeros(S, np.uint8), False)
+        ow, opb, omc, ovc, oam, oav = OA.adam8_step_shard(u.oracle, k, g, w, np.zeros(S, np.uint16), omc, ovc, oam, oav, h)
+        diff(d_w.cpu().numpy().view(np.uint32), ow.view(np.uint32), "master")
+        diff(mc.cpu().numpy(), omc, "m codes")
+        diff(vc.cpu().numpy(), ovc, "v codes")
+        diff(am.cpu().numpy().view(np.uint32), oam.view(np.uint32), "m absmax")
+    finally:
+        u.close()

@@ -267,3 +267,40 @@ def test_rank_local_step_equals_whole_tensor_step(unit):
         assert np.array_equal(w2, want["W"][r]) and np.array_equal(pb, want["Pb"][r])
         assert np.array_equal(mc2, want["MC"][r]) and np.array_equal(vc2, want["VC"][r])
         assert np.array_equal(am2, want["AM"][lo:hi]) and np.array_equal(av2, want["AV"][lo:hi])
+
+
+@pytest.mark.parametrize("unit", UNITS)
+def test_rank_local_codec_equals_whole_tensor_codec_and_inverts_within_half_a_step(unit):
+    specs, pl = make(unit)
+    rng = np.random.default_rng(37)
+    bases = A.state_bases(pl)
+    X = np.zeros(pl.total, np.float32)
+    want_c, want_a = np.zeros(pl.total, np.int16), np.zeros(bases[-1], np.float32)
+    for t, (s, l) in enumerate(zip(specs, pl.offsets)):
+        R, C, runs = (1, s.rows, True) if s.cols == 0 else (s.rows, s.cols, A.state_runs(s))
+        x = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
+        X[l:l + s.e] = x.reshape(-1)
+        c, a = A.quantise_state(x, runs, True)
+        want_c[l:l + s.e], want_a[bases[t]:bases[t] + a.size] = c.reshape(-1), a
+    for k in range(pl.m):
+        r = slice(k * pl.S, (k + 1) * pl.S)
+        lo, hi = A.state_range(pl, k)
+        pad = np.full(pl.S, 0x55, np.int8)
+        codes, amax = A.quantise_shard(pl, k, X[r], pad, True)
+        pay = np.zeros(pl.S, dtype=bool)
+        for _, _, d, n in pl.rank_segments(k):
+            pay[d:d + n] = True
+        assert np.array_equal(codes[pay], want_c[r][pay].astype(np.int8)) and np.all(codes[~pay] == 0x55)
+        assert np.array_equal(amax, want_a[lo:hi])
+        back = A.dequantise_shard(pl, k, codes, amax, np.full(pl.S, 9.0, np.float32), True)
+        assert np.all(back[~pay] == 9.0)
+        # every element within half a quantisation step of its block
+        step = np.zeros(pl.S)
+        cur = 0
+        for dst, n, R, C, runs, nblk in A._segments(pl, k):
+            st = np.zeros((R, C))
+            for b, rs, cs in A._blocks(R, C, runs):
+                st[rs, cs] = float(amax[cur + b]) / 127
+            step[dst:dst + n] = st.reshape(-1)
+            cur += nblk
+        assert np.all(np.abs(back[pay].astype(np.float64) - X[r][pay]) <= step[pay] * (0.5 + 1e-5))
