@@ -16,6 +16,8 @@
  *     calls enqueue exactly one kernel, never synchronise and never allocate.
  *   - Every function returning int returns RS_OK (0) or a negative RS_E* code and
  *     never aborts; rs_strerror() names the code.
+ *   - An uploaded plan and its tables are read-only: any number of threads and streams may
+ *     use them at once.  Creating, uploading and destroying an object are for one thread.
  *   - bf16 = 2-byte bfloat16, codes = 1-byte OCP FP8 E4M3 ("fn": bias 7, no inf,
  *     max 448), scales = fp32.
  */

@@ -99,7 +99,7 @@ int build_plan(const rs_tensor_desc* descs, int n, int world, int align_bytes, i
 
 extern "C" {
 
-int rs_version(void) { return 100; }
+int rs_version(void) { return 120; }
 
 const char* rs_strerror(int code) {
   switch (code) {
