@@ -38,6 +38,52 @@ def unpack_bf16(db: np.ndarray, offsets: Sequence[int], sizes: Sequence[int]) ->
     return [db[l:l + e].copy() for l, e in zip(offsets, sizes)]
 
 
+def strided_region_starts(m: int, S: int, groups: int, group: int) -> List[int]:
+    """Where the m rank regions of one DBuffer sit inside a buffer gathered over a 2-D device
+    mesh (Section 4, composing RaggedShard with Shard(0) of expert / tensor parallelism: the
+    parameter is first split over `groups` devices of the other mesh dimension, then each part is
+    ragged-sharded over m devices).  Reading taken for the "stride metadata" of StridedRaggedShard:
+    the gathered buffer holds the regions device-major, FSDP rank outermost, so region k of group
+    `group` starts at element (k * groups + group) * S - a regular stride of groups * S."""
+    return [(k * groups + group) * S for k in range(m)]
+
+
+def unpack_bf16_strided(buf: np.ndarray, offsets: Sequence[int], sizes: Sequence[int], S: int,
+                        starts: Sequence[int]) -> List[np.ndarray]:
+    """Tensor t = the elements at logical buffer positions [l_t, l_t + e_t), where logical position
+    x lives at buf[starts[x // S] + x % S]: the reshuffle that materialises the tensors of one
+    group from the mesh-ordered gathered buffer."""
+    out = []
+    for l, e in zip(offsets, sizes):
+        t = np.empty(e, dtype=np.uint16)
+        x = l
+        while x < l + e:
+            k, j = divmod(x, S)
+            n = min(S - j, l + e - x)
+            t[x - l:x - l + n] = buf[starts[k] + j:starts[k] + j + n]
+            x += n
+        out.append(t)
+    return out
+
+
+def ragged_pack_strided(buf: np.ndarray, srcs: Sequence[np.ndarray], offsets: Sequence[int], S: int,
+                        starts: Sequence[int]) -> np.ndarray:
+    """The inverse placement into a copy of `buf`: every region listed in `starts` is zeroed and
+    then receives its part of the tensors; the rest of the buffer (other groups' regions) is kept."""
+    out = np.array(buf, dtype=np.uint16, copy=True)
+    for st in starts:
+        out[st:st + S] = 0
+    for src, l in zip(srcs, offsets):
+        flat = np.asarray(src, dtype=np.uint16).reshape(-1)
+        x = l
+        while x < l + flat.size:
+            k, j = divmod(x, S)
+            n = min(S - j, l + flat.size - x)
+            out[starts[k] + j:starts[k] + j + n] = flat[x - l:x - l + n]
+            x += n
+    return out
+
+
 def shard_reduce(partials: np.ndarray, segments: Sequence[Tuple[int, int, int, int]]) -> np.ndarray:
     """out[i] = (1/W) * sum_w P[w][i] on the payload of the region, 0 on its padding.
 

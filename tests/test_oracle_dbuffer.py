@@ -112,3 +112,39 @@ def test_ordered_fp32_reduce_stays_within_the_stated_tolerance_and_follows_its_o
     # W <= 8 with equal partials and W a power of two: the value itself
     same = np.repeat(parts[:1], 8, axis=0)
     assert np.array_equal(D.shard_reduce_f32_ordered(same, [(0, 0, 0, S)]), D.bf16_bits_to_f32(same[0]))
+
+
+def test_strided_regions_against_reshape_and_per_element_gather():
+    """A buffer gathered over a (m x groups) mesh, FSDP rank outermost: the logical buffer of one
+    group is a strided slice; unpacking it equals plain unpack of that slice (numpy reshape as the
+    independent formulation) and a per-element gather; pack is the inverse and leaves other
+    groups' regions alone."""
+    wl, pl = toy()
+    m, S, groups = pl.m, pl.S, 3
+    sizes = [s.e for s in pl.specs]
+    rng = np.random.default_rng(9)
+    gathered = rng.integers(0, 1 << 16, size=m * groups * S, dtype=np.uint16)
+    for grp in range(groups):
+        starts = D.strided_region_starts(m, S, groups, grp)
+        assert starts == [(k * groups + grp) * S for k in range(m)]
+        logical = gathered.reshape(m, groups, S)[:, grp, :].reshape(-1)
+        want = D.unpack_bf16(logical, pl.offsets, sizes)
+        got = D.unpack_bf16_strided(gathered, pl.offsets, sizes, S, starts)
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+        t, l = 3, pl.offsets[3]
+        for i in (0, 1, sizes[t] // 2, sizes[t] - 1):
+            x = l + i
+            assert got[t][i] == gathered[((x // S) * groups + grp) * S + x % S]
+        # pack back: the group's regions hold the packed unit, the others are untouched
+        packed = D.ragged_pack_strided(gathered, got, pl.offsets, S, starts)
+        back = packed.reshape(m, groups, S)
+        assert np.array_equal(back[:, grp, :].reshape(-1), D.ragged_pack(got, pl.offsets, pl.total))
+        for other in range(groups):
+            if other != grp:
+                assert np.array_equal(back[:, other, :], gathered.reshape(m, groups, S)[:, other, :])
+    # one group is the plain layout
+    starts = D.strided_region_starts(m, S, 1, 0)
+    flat = gathered[:pl.total]
+    for a, b in zip(D.unpack_bf16_strided(flat, pl.offsets, sizes, S, starts), D.unpack_bf16(flat, pl.offsets, sizes)):
+        assert np.array_equal(a, b)
