@@ -154,6 +154,21 @@ int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* s
 /* Inverse group copy: dst_t[i] = dbuf[l_t + i] (bf16 DBuffer -> per-tensor bf16). */
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream);
 
+/* ---- regions gathered over a 2-D device mesh (Section 4: RaggedShard composed with the Shard(0)
+ * of expert or tensor parallelism; the stride metadata of StridedRaggedShard) ---------------------
+ * The same two copies on a buffer in which rank k's region starts at element k * region_stride
+ * instead of k * S.  When a parameter is first split over G devices of the other mesh dimension
+ * and each part is ragged-sharded over `world` devices, the buffer gathered over the whole mesh
+ * holds the regions device-major (FSDP rank outermost): part g's regions are read with
+ * dbuf + g * S and region_stride = G * S, and a tensor table over the g-th slices of the full
+ * tensors - G launches materialise the full tensors, no intermediate copy.
+ * region_stride >= S (RS_EINVAL), a multiple of 8 elements (RS_EALIGN); rs_pack_strided zeroes
+ * the padding of the regions it addresses and touches nothing between them. */
+int rs_pack_strided(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, int64_t region_stride,
+                    void* stream);
+int rs_unpack_bf16_strided(const rs_plan* plan, const void* dbuf, int64_t region_stride,
+                           const rs_tensor_table* dst, void* stream);
+
 /* ---- the other group-level operators of the DBuffer (Section 5: the add, scale, zero and copy
  * kernels that each tensor would launch around a collective, fused across the group) ----------
  * alpha is an fp32 factor (finite, else RS_EINVAL); every product and sum is one fp32

@@ -26,7 +26,7 @@ EXPORTS = [
     "rs_pack_scaled", "rs_group_add", "rs_group_scale", "rs_group_zero",
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
-    "rs_state_quantize", "rs_state_dequantize",
+    "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
 ]
 
 
@@ -86,6 +86,8 @@ _lib.rs_tensor_table_destroy.argtypes = [_P]
 _lib.rs_tensor_table_destroy.restype = None
 _lib.rs_pack.argtypes = [_P, _P, _P, _P]
 _lib.rs_unpack_bf16.argtypes = [_P, _P, _P, _P]
+_lib.rs_pack_strided.argtypes = [_P, _P, _P, C.c_int64, _P]
+_lib.rs_unpack_bf16_strided.argtypes = [_P, _P, C.c_int64, _P, _P]
 _lib.rs_pack_scaled.argtypes = [_P, _P, C.c_float, _P, _P]
 _lib.rs_group_add.argtypes = [_P, _P, C.c_float, _P, _P]
 _lib.rs_group_scale.argtypes = [_P, C.c_float, _P, _P]
@@ -271,6 +273,15 @@ def rs_pack(plan, src_table, dbuf, stream=None) -> None:
 
 def rs_unpack_bf16(plan, dbuf, dst_table, stream=None) -> None:
     _check(_lib.rs_unpack_bf16(plan, _ptr(dbuf), dst_table, _stream(stream)), "rs_unpack_bf16")
+
+
+def rs_pack_strided(plan, src_table, dbuf, region_stride: int, stream=None) -> None:
+    _check(_lib.rs_pack_strided(plan, src_table, _ptr(dbuf), int(region_stride), _stream(stream)), "rs_pack_strided")
+
+
+def rs_unpack_bf16_strided(plan, dbuf, region_stride: int, dst_table, stream=None) -> None:
+    _check(_lib.rs_unpack_bf16_strided(plan, _ptr(dbuf), int(region_stride), dst_table, _stream(stream)),
+           "rs_unpack_bf16_strided")
 
 
 def rs_pack_scaled(plan, src_table, alpha: float, dbuf, stream=None) -> None:

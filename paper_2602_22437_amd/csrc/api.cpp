@@ -375,16 +375,19 @@ void rs_tensor_table_destroy(rs_tensor_table* table) {
 
 // shared body of the group-level operators on the bf16 DBuffer
 static int group_op(int op, const rs_plan* plan, const rs_tensor_table* tab, const void* dbuf,
-                    float alpha, void* stream) {
+                    float alpha, void* stream, int64_t region_stride = 0) {
   int rc = check_device(plan);
   if (rc == RS_OK && op != rs::kGroupScale) rc = check_table(plan, tab);
   if (rc != RS_OK) return rc;
   if (!dbuf) return RS_EINVAL;
   if (!aligned16(dbuf)) return RS_EALIGN;
   if (alpha != alpha || alpha - alpha != 0.0f) return RS_EINVAL;  // NaN or infinite factor
+  if (region_stride == 0) region_stride = plan->S;
+  if (region_stride < plan->S) return RS_EINVAL;
+  if (region_stride % 8 != 0) return RS_EALIGN;
   return rs::launch_group_op(op, plan->dev, int(plan->t.size()), tab ? tab->ptrs : nullptr,
                              const_cast<void*>(dbuf), alpha, plan->S, plan->host.granules_per_rank,
-                             plan->host.n_payload_gran, plan->host.n_padding_gran,
+                             region_stride, plan->host.n_payload_gran, plan->host.n_padding_gran,
                              static_cast<hipStream_t>(stream));
 }
 
@@ -394,6 +397,18 @@ int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* s
 
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream) {
   return group_op(rs::kGroupUnpack, plan, dst, dbuf, 1.0f, stream);
+}
+
+int rs_pack_strided(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, int64_t region_stride,
+                    void* stream) {
+  if (region_stride <= 0) return RS_EINVAL;
+  return group_op(rs::kGroupPack, plan, src, dbuf, 1.0f, stream, region_stride);
+}
+
+int rs_unpack_bf16_strided(const rs_plan* plan, const void* dbuf, int64_t region_stride,
+                           const rs_tensor_table* dst, void* stream) {
+  if (region_stride <= 0) return RS_EINVAL;
+  return group_op(rs::kGroupUnpack, plan, dst, dbuf, 1.0f, stream, region_stride);
 }
 
 int rs_pack_scaled(const rs_plan* plan, const rs_tensor_table* src, float alpha, void* dbuf,

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
     const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
     const int32_t* __restrict__ granules, const int32_t* __restrict__ padding,
     unsigned n_copy_groups, void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S,
-    int64_t gpr, float alpha) {
+    int64_t gpr, int64_t region_stride, float alpha) {
   constexpr bool kFillsPadding = kOp == kGroupPack || kOp == kGroupPackScaled;
   constexpr bool kReadsBuffer = kOp == kGroupUnpack || kOp == kGroupAdd || kOp == kGroupScale;
   constexpr bool kUsesTensors = kOp != kGroupScale;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
 #pragma unroll
     for (int h = 0; h < kCopyParts; ++h) {
       const int lo = (h * kCopyThreads + int(threadIdx.x)) * 8;
-      if (lo < len) st16(dbuf + k * S + i0 + lo, u32x4{0, 0, 0, 0});
+      if (lo < len) st16(dbuf + k * region_stride + i0 + lo, u32x4{0, 0, 0, 0});
     }
     return;
   }
@@ -66,7 +66,9 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
   const int len = int(min(int64_t(kGranule), S - i0));
   const int lane_off = (int(part) * kCopyThreads + int(threadIdx.x)) * 8;
   if (lane_off >= len) return;
-  const int64_t d = d0 + lane_off;
+  const int64_t d = d0 + lane_off;          // logical buffer position: what the tables speak of
+  // where it lives: rank regions are region_stride elements apart (S in a plain DBuffer)
+  uint16_t* const at = dbuf + k * region_stride + i0 + lane_off;
   const int t0 = gran_first[bid];
 
   bool empty = t0 >= n;
@@ -75,26 +77,26 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
     if (ell <= d0 && d0 + len <= end) {
       // the whole granule lies inside tensor t0 (the common case by far)
       if (!kUsesTensors) {
-        st16(dbuf + d, scale8(ld16(dbuf + d), alpha));
+        st16(at, scale8(ld16(at), alpha));
         return;
       }
       uint16_t* base = reinterpret_cast<uint16_t*>(ptrs[t0]) + (d0 - ell);
       if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
         if (kOp == kGroupUnpack)
-          st16(base + lane_off, ld16(dbuf + d));
+          st16(base + lane_off, ld16(at));
         else if (kOp == kGroupPack)
-          st16(dbuf + d, ld16(base + lane_off));
+          st16(at, ld16(base + lane_off));
         else if (kOp == kGroupPackScaled)
-          st16(dbuf + d, scale8(ld16(base + lane_off), alpha));
+          st16(at, scale8(ld16(base + lane_off), alpha));
         else
-          st16(dbuf + d, axpy8(ld16(dbuf + d), ld16(base + lane_off), alpha));
+          st16(at, axpy8(ld16(at), ld16(base + lane_off), alpha));
         return;
       }
     }
     empty = ell >= d0 + len;
   }
   if (empty) {  // nothing but padding here
-    if (kFillsPadding) st16(dbuf + d, u32x4{0, 0, 0, 0});
+    if (kFillsPadding) st16(at, u32x4{0, 0, 0, 0});
     return;
   }
 
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
   int s = t0;
   uint16_t vals[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (kReadsBuffer) {
-    const u32x4 v = ld16(dbuf + d);
+    const u32x4 v = ld16(at);
     vals[0] = uint16_t(v.x); vals[1] = uint16_t(v.x >> 16);
     vals[2] = uint16_t(v.y); vals[3] = uint16_t(v.y >> 16);
     vals[4] = uint16_t(v.z); vals[5] = uint16_t(v.z >> 16);
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
     v.y = vals[2] | (uint32_t(vals[3]) << 16);
     v.z = vals[4] | (uint32_t(vals[5]) << 16);
     v.w = vals[6] | (uint32_t(vals[7]) << 16);
-    st16(dbuf + d, v);
+    st16(at, v);
   }
 }
 
@@ -164,8 +166,8 @@ __global__ __launch_bounds__(kCopyThreads) void copy_probe_kernel(const u32x4* _
 // launchers (host)
 // -------------------------------------------------------------------------------------------
 int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf, float alpha,
-                    int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
-                    hipStream_t st) {
+                    int64_t S, int64_t gpr, int64_t region_stride, int64_t n_payload_gran,
+                    int64_t n_padding_gran, hipStream_t st) {
   const bool fills = op == kGroupPack || op == kGroupPackScaled;
   uint16_t* db = static_cast<uint16_t*>(dbuf);
   const int64_t copy_groups = n_payload_gran * kCopyParts;
@@ -178,7 +180,7 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
 #define RS_GROUP_OP(OP)                                                                         \
   group_op_kernel<OP><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,       \
                                        dev.padding_gran, unsigned(copy_groups), ptrs, db, S,   \
-                                       gpr, alpha)
+                                       gpr, region_stride, alpha)
   switch (op) {
     case kGroupPack: RS_GROUP_OP(kGroupPack); break;
     case kGroupUnpack: RS_GROUP_OP(kGroupUnpack); break;

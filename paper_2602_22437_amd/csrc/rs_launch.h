@@ -8,9 +8,10 @@ namespace rs {
 
 // group-level operators on the bf16 DBuffer; `op` is one of the values below
 enum : int { kGroupPack = 0, kGroupUnpack = 1, kGroupPackScaled = 2, kGroupAdd = 3, kGroupScale = 4 };
+// rank k's region starts region_stride elements after rank k-1's (S in a plain DBuffer)
 int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf, float alpha,
-                    int64_t S, int64_t gpr, int64_t n_payload_gran, int64_t n_padding_gran,
-                    hipStream_t st);
+                    int64_t S, int64_t gpr, int64_t region_stride, int64_t n_payload_gran,
+                    int64_t n_padding_gran, hipStream_t st);
 int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st);
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
                         float* out, int64_t S, int64_t gpr, int rank, int world, hipStream_t st);

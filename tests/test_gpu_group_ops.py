@@ -192,3 +192,58 @@ def test_group_op_argument_errors():
         assert not bits_of(dbuf).any()      # no failing call wrote anything
     finally:
         u.close()
+
+
+@pytest.mark.parametrize("groups,gap", [(1, 0), (3, 0), (2, 24)])
+def test_strided_regions_of_a_2d_mesh(groups, gap):
+    """A buffer gathered over a (world x groups) device mesh, FSDP rank outermost (the stride
+    metadata of StridedRaggedShard, Section 4): `groups` strided unpacks materialise the full
+    tensors with no intermediate copy; strided packs are the inverse and leave everything
+    between the addressed regions alone."""
+    tensors = [(257, 136, MODE_128x128), (300, 0, MODE_1x128), (128, 384, MODE_128x128), (33, 7, MODE_1x128)]
+    W = 4
+    u = Unit(tensors, W)
+    try:
+        S = u.S
+        stride = groups * S + gap                       # gap: unrelated data between rank rows
+        sizes = [s.e for s in u.specs]
+        rng = np.random.default_rng(70 + groups)
+        gathered = rng.integers(0, 1 << 16, size=W * stride, dtype=np.uint16)
+        # bf16 patterns are arbitrary bit patterns here: the copies must keep them bit for bit
+        d_gathered = to_dev_bf16(gathered)
+        full = [torch.full((groups * e,), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.bfloat16) for e in sizes]
+        for g in range(groups):
+            say(f"unpack_bf16_strided: group {g} of {groups}, stride {stride}")
+            starts = [k * stride + g * S for k in range(W)]
+            if gap == 0:
+                assert starts == OD.strided_region_starts(W, S, groups, g)
+            views = [f[g * e:(g + 1) * e] for f, e in zip(full, sizes)]
+            B.rs_unpack_bf16_strided(u.plan, d_gathered[g * S:], stride, u.table(views))
+            torch.cuda.synchronize()
+            want = OD.unpack_bf16_strided(gathered, u.oracle.offsets, sizes, S, starts)
+            for i, (v, w_) in enumerate(zip(views, want)):
+                first_diff(bits_of(v), w_, f"strided unpack tensor {i} group {g}")
+        # inverse: pack every group's slices into a buffer full of a marker
+        marker = np.full(W * stride, 0x4300, dtype=np.uint16)
+        d_out = to_dev_bf16(marker)
+        want_buf = marker
+        host_full = [bits_of(f) for f in full]
+        for g in range(groups):
+            say(f"pack_strided: group {g} of {groups}")
+            starts = [k * stride + g * S for k in range(W)]
+            views = [f[g * e:(g + 1) * e] for f, e in zip(full, sizes)]
+            B.rs_pack_strided(u.plan, u.table(views), d_out[g * S:], stride)
+            torch.cuda.synchronize()
+            want_buf = OD.ragged_pack_strided(want_buf, [h[g * e:(g + 1) * e] for h, e in zip(host_full, sizes)],
+                                              u.oracle.offsets, S, starts)
+            first_diff(bits_of(d_out), want_buf, f"strided pack after group {g}")
+        if gap:
+            got = bits_of(d_out).reshape(W, stride)
+            assert np.all(got[:, groups * S:] == 0x4300)
+        P = C.c_void_p
+        assert B.raw_call("rs_unpack_bf16_strided", P(u.plan), P(d_gathered.data_ptr()), C.c_int64(S - 8),
+                          P(u.tables[0]), P(0)) == B.RS_EINVAL
+        assert B.raw_call("rs_pack_strided", P(u.plan), P(u.tables[0]), P(d_out.data_ptr()), C.c_int64(S + 4),
+                          P(0)) == B.RS_EALIGN
+    finally:
+        u.close()
