@@ -44,7 +44,7 @@ enum {
 
 /* Sharding granularity of one tensor (Section 4: the atomic non-shardable block).
  * Row-wise RaggedShard makes 2-D tiles contiguous: 128 whole rows hold a row of 128x128 tiles
- * (Section 6.4, "128-row setting"). */
+ * (Section 6.4: granularity of 128 rows). */
 enum {
   RS_BLOCK_1x128 = 0,    /* 1-D: g = 128 elements; 2-D: g = one row; FP8 blocks are 1x128 runs per row */
   RS_BLOCK_128x128 = 1,  /* 2-D only: g = 128 rows; FP8 blocks are 128x128 tiles, edge tiles partial */

@@ -53,8 +53,8 @@ def size_and_granularity(rows: int, cols: int, mode: int, g_explicit: int = 0) -
     """(e_t, g_t) of one tensor.  cols == 0 means a 1-D tensor of `rows` elements.
 
     Row-wise RaggedShard (Section 4): the granularity is k whole rows, which is how
-    2-D quantisation tiles become contiguous runs (Section 6.3 "32-row block
-    granularity", Section 6.4 "128-row setting reproduces 128x128 tiling")."""
+    2-D quantisation tiles become contiguous runs (Section 6.3: granularity of 32 rows for
+    32x32 blocks; Section 6.4: 128 rows give 128x128 tiles)."""
     if rows <= 0 or cols < 0:
         raise ValueError("empty or negative tensor shape")
     e = rows * cols if cols > 0 else rows

@@ -1,7 +1,7 @@
 """Offline padding study with the library's planner (host only, no GPU needed).
 
-The paper picks the FSDP group size "by offline simulation to minimize LCM-induced rounding"
-and reports the padding overhead of the plan against the FSDP size for row granularities
+The paper chooses the FSDP group size by simulating layouts offline so that rounding to block
+multiples costs least, and reports the padding overhead of the plan against the FSDP size for row granularities
 1x / 16x / 128x of the expert-MLP matrices (Section 6.4, padding figure).  This tool runs that
 sweep on synthetic units shaped like the two models the section uses.
 

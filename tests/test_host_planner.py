@@ -153,7 +153,7 @@ def test_planner_runtime_on_largest_config():
     plan = B.rs_plan_create([(t.rows, t.cols, t.mode) for t in wl.tensors], wl.world)
     dt = time.time() - t0
     B.rs_plan_destroy(plan)
-    assert dt < 0.3           # "less than 0.3 seconds" (Section 6.4)
+    assert dt < 0.3           # the planning-time bound reported in Section 6.4
 
 
 @pytest.mark.parametrize("order", [B.RS_ORDER_DEFAULT, B.RS_ORDER_BLOCK_SIZE, B.RS_ORDER_SHAPE, B.RS_ORDER_BEST])
