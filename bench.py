@@ -99,6 +99,50 @@ def cpu_baseline(wl, seed=1):
     }
 
 
+def cpu_baseline_all_cores(wl, seed=1):
+    """The same sample through the C / OpenMP statement of the oracle on every host core the
+    process may use: context for the single-thread numpy figure, not a target."""
+    import numpy as np
+    from oracle import c_oracle as OC
+    from oracle import plan as OP
+    from workloads import gen_param, gen_partial
+
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    OC.set_num_threads(cores)
+    specs = [OP.TensorSpec(t.rows, t.cols, t.mode) for t in wl.tensors]
+    plan = OP.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize)
+    params = [gen_param(wl, seed, t) for t in range(len(specs))]
+    parts = np.stack([gen_partial(wl, seed, w, plan.S) for w in range(wl.world)])
+    segs = plan.rank_segments(wl.rank)
+    payload_red = sum(s[3] for s in segs)
+    E = plan.payload
+
+    def shape(s):
+        return ((1, s.rows, 1, 128) if s.cols == 0 else
+                (s.rows, s.cols, 128, 128) if s.mode == OP.BLOCK_128x128 else (s.rows, s.cols, 1, 128))
+    t0 = time.perf_counter()
+    db = OC.ragged_pack(params, plan.offsets, plan.total)
+    t1 = time.perf_counter()
+    OC.shard_reduce(parts, segs)
+    t2 = time.perf_counter()
+    q = []
+    for s, l in zip(specs, plan.offsets):
+        R, C, bh, bw = shape(s)
+        q.append(OC.quantise_matrix(db[l:l + s.e].reshape(R, C), bh, bw) + (bh, bw))
+    t3 = time.perf_counter()
+    for c, sc, bh, bw in q:
+        OC.dequantise_matrix(c, sc, bh, bw)
+    t4 = time.perf_counter()
+    nb = sum(s.num_blocks for s in specs)
+    moved = {"ragged_pack": 2 * E + 2 * plan.total, "shard_reduce": 2 * wl.world * payload_red + 4 * plan.S,
+             "block_quant": 3 * E + 4 * nb, "dequant_unpack": 3 * E + 4 * nb}
+    secs = {"ragged_pack": t1 - t0, "shard_reduce": t2 - t1, "block_quant": t3 - t2, "dequant_unpack": t4 - t3}
+    return {"value": round(sum(moved.values()) / sum(secs.values()) / 1e9, 3), "unit": "GB/s", "cores": cores,
+            "kind": "oracle (plain C with OpenMP, the numpy oracle's cross-check)",
+            "sample": f"the same sample as cpu_baseline; {sum(secs.values()):.2f} s",
+            "per_op_GBps": {k: round(moved[k] / secs[k] / 1e9, 3) for k in moved}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -394,6 +438,10 @@ def main():
         result["graph_GBps"] = round(step_bytes / (graph_ms * 1e-3) / 1e9, 1)
     if not args.no_cpu and wl.index == 2:
         result["cpu_baseline"] = cpu_baseline(wl)
+        try:
+            result["cpu_baseline_all_cores"] = cpu_baseline_all_cores(wl)
+        except Exception as exc:       # no C compiler on the box: the numpy figure stands alone
+            result["cpu_baseline_all_cores"] = {"error": str(exc)[:200]}
     print(json.dumps(result), flush=True)
 
     if batch:
