@@ -291,24 +291,26 @@ def main():
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
 
-    kern_ms = {n: 0.0 for n in names}
+    samples = {n: [] for n in names}          # event-to-event ms of every timed launch
     for ev in events:
         for i, n in enumerate(per_unit_names):
-            kern_ms[n] += ev[i].elapsed_time(ev[i + 1])
+            samples[n].append(ev[i].elapsed_time(ev[i + 1]))
     launches = len(events)
-    kern_ms = {n: v / launches for n, v in kern_ms.items()}
     launch_bytes = dict(per_unit)
     if quant:   # one launch covers all units
-        kern_ms["block_quant"] = sum(a.elapsed_time(b) for a, b in qevents) / len(qevents)
+        samples["block_quant"] = [a.elapsed_time(b) for a, b in qevents]
         launch_bytes["block_quant"] = units * per_unit["block_quant"]
+    kern_ms = {n: sum(v) / len(v) for n, v in samples.items()}
     step_bytes = units * sum(per_unit.values())
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     kernels = {}
     for n in names:
         gbps = launch_bytes[n] / (kern_ms[n] * 1e-3) / 1e9
+        ordered = sorted(samples[n])
         kernels[n] = {"ms": round(kern_ms[n], 4), "bytes": launch_bytes[n], "GBps": round(gbps, 1),
-                      "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+                      "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4), "launches_timed": len(ordered),
+                      "median_ms": round(ordered[len(ordered) // 2], 4), "min_ms": round(ordered[0], 4)}
     if quant:
         kernels["block_quant"]["note"] = f"one launch over rank {rank}'s shard of all {units} unit(s)"
 
