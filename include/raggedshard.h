@@ -108,7 +108,33 @@ int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_byte
  * every query and pointer table; only their positions in the buffer change. */
 int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int align_bytes,
                            int min_itemsize, int tensor_align_elems, int order, rs_plan** out);
+/* The buffer of a group placed RaggedShard(r_t): every block of tensor t on device roots[t]
+ * (Section 4: arbitrary sharding distribution; the redistribute target of Algorithm 2, where
+ * only the root holds the full matrix).  Device k's region holds the tensors rooted at k in the
+ * caller's order, each start a multiple of tensor_align_elems; S is the largest region's extent
+ * rounded up to g_coll.  roots: host array of n values in [0, world), else RS_EINVAL.  The plan
+ * answers every query and drives every device call like one made by rs_plan_create. */
+int rs_plan_create_rooted(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                          int min_itemsize, int tensor_align_elems, const int32_t* roots,
+                          rs_plan** out);
 void rs_plan_destroy(rs_plan* plan);
+
+/* SelectRoot of Algorithm 2 (distributed Muon, Section 6.3), which the paper leaves at "load
+ * balancing": longest-processing-time-first.  2-D tensors in descending cost (equal costs in
+ * index order) each go to the device with the least accumulated cost, the lowest such device.
+ * Cost of an R x C matrix = one quintic Newton-Schulz iteration, a*a*(2b + a) with
+ * a = min(R, C), b = max(R, C).  roots (host, n values) receives the device, -1 for 1-D
+ * tensors; loads (host, world values, may be NULL) the accumulated cost of every device.
+ * block_mode and g_explicit of the descriptors are not used beyond validation. */
+int rs_select_roots(const rs_tensor_desc* descs, int n, int world, int32_t* roots, double* loads);
+
+/* Composition with an even Shard(dim > 0) of another placement (Section 4, composing with
+ * existing sharding formats): the ragged granularity of the row-major local tensor `shape`
+ * (ndim sizes) that never cuts into dimension dim, 0 < dim < ndim:
+ * *g_out = lcm(shape[dim] * ... * shape[ndim-1], g_user) elements, for use as g_explicit of an
+ * RS_BLOCK_EXPLICIT descriptor.  Errors: RS_EINVAL, RS_EOVERFLOW. */
+int rs_shard_dim_granularity(const int64_t* shape, int ndim, int dim, int64_t g_user,
+                             int64_t* g_out);
 
 /* CheckValidShard(S) of Algorithm 1 on its own: 1 feasible, 0 infeasible, <0 error.
  * S must be a positive multiple of tensor_align_elems (0 = g_coll). */

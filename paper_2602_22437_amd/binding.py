@@ -27,6 +27,7 @@ EXPORTS = [
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
+    "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity",
 ]
 
 
@@ -64,6 +65,12 @@ _lib.rs_plan_create.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c
                                 C.POINTER(_P)]
 _lib.rs_plan_create_ordered.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int,
                                         C.c_int, C.c_int, C.POINTER(_P)]
+_lib.rs_plan_create_rooted.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.c_int, C.c_int,
+                                       C.c_int, C.POINTER(C.c_int32), C.POINTER(_P)]
+_lib.rs_select_roots.argtypes = [C.POINTER(rs_tensor_desc), C.c_int, C.c_int, C.POINTER(C.c_int32),
+                                 C.POINTER(C.c_double)]
+_lib.rs_shard_dim_granularity.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int, C.c_int64,
+                                          C.POINTER(C.c_int64)]
 _lib.rs_plan_order.argtypes = [_P, C.POINTER(C.c_int32), C.c_int]
 _lib.rs_plan_destroy.argtypes = [_P]
 _lib.rs_plan_destroy.restype = None
@@ -168,6 +175,36 @@ def rs_plan_create_ordered(tensors: Sequence[Tuple], world: int, align_bytes: in
     _check(_lib.rs_plan_create_ordered(_descs(tensors), len(tensors), int(world), int(align_bytes),
                                        int(min_itemsize), int(tensor_align_elems), int(order),
                                        C.byref(out)), "rs_plan_create_ordered")
+    return out.value
+
+
+def rs_plan_create_rooted(tensors: Sequence[Tuple], world: int, roots: Sequence[int],
+                          align_bytes: int = 16, min_itemsize: int = 1,
+                          tensor_align_elems: int = 0) -> int:
+    if len(roots) != len(tensors):
+        raise ValueError("one root per tensor")
+    out = _P()
+    arr = (C.c_int32 * max(1, len(roots)))(*[int(r) for r in roots])
+    _check(_lib.rs_plan_create_rooted(_descs(tensors), len(tensors), int(world), int(align_bytes),
+                                      int(min_itemsize), int(tensor_align_elems), arr, C.byref(out)),
+           "rs_plan_create_rooted")
+    return out.value
+
+
+def rs_select_roots(tensors: Sequence[Tuple], world: int) -> Tuple[List[int], List[float]]:
+    """(root of every tensor, accumulated cost of every device)."""
+    roots = (C.c_int32 * max(1, len(tensors)))()
+    loads = (C.c_double * max(1, int(world)))()
+    _check(_lib.rs_select_roots(_descs(tensors), len(tensors), int(world), roots, loads),
+           "rs_select_roots")
+    return list(roots)[:len(tensors)], list(loads)[:max(0, int(world))]
+
+
+def rs_shard_dim_granularity(shape: Sequence[int], dim: int, g_user: int) -> int:
+    arr = (C.c_int64 * max(1, len(shape)))(*[int(d) for d in shape])
+    out = C.c_int64()
+    _check(_lib.rs_shard_dim_granularity(arr, len(shape), int(dim), int(g_user), C.byref(out)),
+           "rs_shard_dim_granularity")
     return out.value
 
 

@@ -3,6 +3,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <memory>
 #include <new>
 
 #include "raggedshard.h"
@@ -95,11 +96,37 @@ int build_plan(const rs_tensor_desc* descs, int n, int world, int align_bytes, i
   return rs::describe_tensors(descs, n, t);
 }
 
+// Fills in what follows from the starts (given in buffer order): scale and state-block numbering
+// and the per-rank ranges of both.
+void finish_plan(rs_plan* p, const std::vector<int64_t>& starts) {
+  int64_t sb = 0, stb = 0;
+  p->all_quant = true;
+  p->all_state = true;
+  for (size_t i = 0; i < p->t.size(); ++i) {
+    p->t[i].ell = starts[i];
+    p->t[i].scale_base = sb;
+    sb += p->t[i].nbr * p->t[i].nbc;
+    p->t[i].state_base = stb;
+    stb += p->t[i].sbr * p->t[i].sbc;
+    p->payload += p->t[i].e;
+    p->all_quant = p->all_quant && p->t[i].quant;
+    p->all_state = p->all_state && p->t[i].state;
+  }
+  p->num_scales = sb;
+  p->num_state_blocks = stb;
+  p->scale_begin.resize(size_t(p->world) + 1);
+  p->state_begin.assign(size_t(p->world) + 1, 0);
+  for (int64_t k = 0; k <= p->world; ++k) {
+    p->scale_begin[size_t(k)] = scales_in_front(*p, k * p->S);
+    if (p->all_state) p->state_begin[size_t(k)] = state_blocks_in_front(*p, k * p->S);
+  }
+}
+
 }  // namespace
 
 extern "C" {
 
-int rs_version(void) { return 120; }
+int rs_version(void) { return 130; }
 
 const char* rs_strerror(int code) {
   switch (code) {
@@ -133,55 +160,23 @@ int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int al
       orders = {RS_ORDER_DEFAULT, RS_ORDER_BLOCK_SIZE, RS_ORDER_SHAPE};
     else
       orders = {order};
-    rs_plan* best = nullptr;
+    std::unique_ptr<rs_plan> best;
     for (int o : orders) {
-      rs_plan* p = new rs_plan();
+      std::unique_ptr<rs_plan> p(new rs_plan());
       rs::order_tensors(listed, o, &p->orig);
       for (int32_t i : p->orig) p->t.push_back(listed[size_t(i)]);
       p->world = world;
       p->g_coll = g_coll;
       p->A = A;
       rc = rs::solve_shard_size(p->t, p->world, p->g_coll, p->A, &p->S);
-      if (rc != RS_OK) {
-        delete p;
-        delete best;
-        return rc;
-      }
-      if (best && best->S <= p->S) {
-        delete p;
-      } else {
-        delete best;
-        best = p;
-      }
+      if (rc != RS_OK) return rc;
+      if (!best || p->S < best->S) best = std::move(p);
     }
-    rs_plan* p = best;
+    std::unique_ptr<rs_plan>& p = best;
     std::vector<int64_t> starts;
-    if (!rs::check_valid_shard(p->t, p->world, p->S, p->A, &starts)) {
-      delete p;
-      return RS_EINVAL;
-    }
-    int64_t sb = 0, stb = 0;
-    p->all_quant = true;
-    p->all_state = true;
-    for (size_t i = 0; i < p->t.size(); ++i) {
-      p->t[i].ell = starts[i];
-      p->t[i].scale_base = sb;
-      sb += p->t[i].nbr * p->t[i].nbc;
-      p->t[i].state_base = stb;
-      stb += p->t[i].sbr * p->t[i].sbc;
-      p->payload += p->t[i].e;
-      p->all_quant = p->all_quant && p->t[i].quant;
-      p->all_state = p->all_state && p->t[i].state;
-    }
-    p->num_scales = sb;
-    p->num_state_blocks = stb;
-    p->scale_begin.resize(size_t(world) + 1);
-    p->state_begin.assign(size_t(world) + 1, 0);
-    for (int k = 0; k <= world; ++k) {
-      p->scale_begin[size_t(k)] = scales_in_front(*p, int64_t(k) * p->S);
-      if (p->all_state) p->state_begin[size_t(k)] = state_blocks_in_front(*p, int64_t(k) * p->S);
-    }
-    *out = p;
+    if (!rs::check_valid_shard(p->t, p->world, p->S, p->A, &starts)) return RS_EINVAL;
+    finish_plan(p.get(), starts);
+    *out = p.release();
     return RS_OK;
   } catch (const std::bad_alloc&) {
     return RS_ENOMEM;
@@ -192,6 +187,52 @@ int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_byte
                    int tensor_align_elems, rs_plan** out) {
   return rs_plan_create_ordered(descs, n, world, align_bytes, min_itemsize, tensor_align_elems,
                                 RS_ORDER_DEFAULT, out);
+}
+
+int rs_plan_create_rooted(const rs_tensor_desc* descs, int n, int world, int align_bytes,
+                          int min_itemsize, int tensor_align_elems, const int32_t* roots,
+                          rs_plan** out) {
+  if (!out) return RS_EINVAL;
+  *out = nullptr;
+  if (!roots) return RS_EINVAL;
+  try {
+    std::vector<rs::TensorHost> listed;
+    int64_t g_coll = 0, A = 0;
+    int rc = build_plan(descs, n, world, align_bytes, min_itemsize, tensor_align_elems, &listed,
+                        &g_coll, &A);
+    if (rc != RS_OK) return rc;
+    std::unique_ptr<rs_plan> p(new rs_plan());
+    p->world = world;
+    p->g_coll = g_coll;
+    p->A = A;
+    std::vector<int64_t> starts;
+    rc = rs::rooted_layout(listed, world, g_coll, A, roots, &p->orig, &starts, &p->S);
+    if (rc != RS_OK) return rc;
+    for (int32_t i : p->orig) p->t.push_back(listed[size_t(i)]);
+    finish_plan(p.get(), starts);
+    *out = p.release();
+    return RS_OK;
+  } catch (const std::bad_alloc&) {
+    return RS_ENOMEM;
+  }
+}
+
+int rs_select_roots(const rs_tensor_desc* descs, int n, int world, int32_t* roots, double* loads) {
+  if (!descs || !roots || n <= 0 || world <= 0) return RS_EINVAL;
+  try {
+    std::vector<rs::TensorHost> t;
+    const int rc = rs::describe_tensors(descs, n, &t);
+    if (rc != RS_OK) return rc;
+    rs::select_roots(t, world, roots, loads);
+    return RS_OK;
+  } catch (const std::bad_alloc&) {
+    return RS_ENOMEM;
+  }
+}
+
+int rs_shard_dim_granularity(const int64_t* shape, int ndim, int dim, int64_t g_user,
+                             int64_t* g_out) {
+  return rs::shard_dim_granularity(shape, ndim, dim, g_user, g_out);
 }
 
 void rs_plan_destroy(rs_plan* plan) {

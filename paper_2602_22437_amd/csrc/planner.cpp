@@ -206,4 +206,81 @@ int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_
   return RS_OK;
 }
 
+// Composition with an even Shard(dim > 0) (Section 4): ragged boundaries must leave dimension
+// `dim` whole, i.e. fall on multiples of the extent of dimensions dim.. of the row-major tensor;
+// the granularity is the least common multiple of that extent and the caller's granularity.
+int shard_dim_granularity(const int64_t* shape, int ndim, int dim, int64_t g_user, int64_t* g_out) {
+  if (!shape || !g_out || ndim < 2 || dim <= 0 || dim >= ndim || g_user <= 0) return RS_EINVAL;
+  i128 plane = 1, elems = 1;
+  for (int d = ndim - 1; d >= 0; --d) {
+    if (shape[d] <= 0) return RS_EINVAL;
+    elems *= shape[d];
+    if (elems >= kLimit) return RS_EOVERFLOW;
+    if (d >= dim) plane = elems;
+  }
+  const i128 g = plane / gcd64(int64_t(plane), g_user) * g_user;
+  if (g >= kLimit) return RS_EOVERFLOW;
+  *g_out = int64_t(g);
+  return RS_OK;
+}
+
+// SelectRoot of Algorithm 2 as longest-processing-time-first list scheduling.  The cost of an
+// R x C matrix is one quintic Newton-Schulz iteration in units of two flops: a*a*(2b + a) with
+// a = min(R, C), b = max(R, C) (Gram matrix, its square, the update).  Costs stay below 2^95 and
+// their sums below 2^126, so 128-bit integers are exact.
+void select_roots(const std::vector<TensorHost>& t, int world, int32_t* roots, double* loads) {
+  using u128 = unsigned __int128;
+  std::vector<u128> cost(t.size(), 0), acc(size_t(world), 0);
+  std::vector<int32_t> mats;
+  for (size_t i = 0; i < t.size(); ++i) {
+    roots[i] = -1;
+    if (t[i].cols == 0) continue;
+    const u128 a = u128(std::min(t[i].rows, t[i].cols)), b = u128(std::max(t[i].rows, t[i].cols));
+    cost[i] = a * a * (2 * b + a);
+    mats.push_back(int32_t(i));
+  }
+  std::stable_sort(mats.begin(), mats.end(),
+                   [&](int32_t x, int32_t y) { return cost[size_t(x)] > cost[size_t(y)]; });
+  for (int32_t i : mats) {
+    size_t k = 0;
+    for (size_t d = 1; d < acc.size(); ++d)
+      if (acc[d] < acc[k]) k = d;
+    roots[size_t(i)] = int32_t(k);
+    acc[k] += cost[size_t(i)];
+  }
+  if (loads)
+    for (size_t d = 0; d < acc.size(); ++d) loads[d] = double(acc[d]);
+}
+
+// The buffer of a group placed RaggedShard(r_t): device k's region holds the tensors rooted at
+// k in the caller's order, starts aligned to A; S = the largest region rounded up to g_coll.
+// `t` is in the caller's order; perm receives the buffer order, starts the offsets in that order.
+int rooted_layout(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
+                  const int32_t* roots, std::vector<int32_t>* perm, std::vector<int64_t>* starts,
+                  int64_t* S_out) {
+  std::vector<i128> extent(size_t(world), 0);
+  std::vector<i128> rel(t.size(), 0);
+  i128 longest = 0;
+  for (size_t i = 0; i < t.size(); ++i) {
+    if (roots[i] < 0 || roots[i] >= world) return RS_EINVAL;
+    i128& x = extent[size_t(roots[i])];
+    rel[i] = (x + A - 1) / A * A;
+    x = rel[i] + t[i].e;
+    longest = std::max(longest, x);
+  }
+  const i128 S = (longest + g_coll - 1) / g_coll * g_coll;
+  if (S * world >= kLimit) return RS_EOVERFLOW;
+  perm->resize(t.size());
+  for (size_t i = 0; i < t.size(); ++i) (*perm)[i] = int32_t(i);
+  std::stable_sort(perm->begin(), perm->end(),
+                   [&](int32_t x, int32_t y) { return roots[x] < roots[y]; });
+  starts->resize(t.size());
+  for (size_t j = 0; j < t.size(); ++j) {
+    const size_t i = size_t((*perm)[j]);
+    (*starts)[j] = int64_t(S * roots[i] + rel[i]);
+  }
+  *S_out = int64_t(S);
+  return RS_OK;
+}
+
 }  // namespace rs

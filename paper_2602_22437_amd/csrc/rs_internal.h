@@ -100,6 +100,11 @@ int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
                      int64_t* S_out);
 void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int32_t>* perm);
+int shard_dim_granularity(const int64_t* shape, int ndim, int dim, int64_t g_user, int64_t* g_out);
+void select_roots(const std::vector<TensorHost>& t, int world, int32_t* roots, double* loads);
+int rooted_layout(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
+                  const int32_t* roots, std::vector<int32_t>* perm, std::vector<int64_t>* starts,
+                  int64_t* S_out);
 
 // ---- derived tables (tables.cpp) ----
 void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t S, bool all_quant,

@@ -56,6 +56,25 @@ int main(void) {
   CHECK(rs_adam8_step(plan, 0, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == RS_ENOTUPLOADED);
   rs_plan_destroy(plan);
   plan = NULL;
+  {
+    /* placement helpers: roots by load balancing, the rooted buffer, Shard(dim > 0) granularity */
+    int32_t roots[6];
+    double loads[4];
+    const int64_t shape[3] = {8, 64, 48};
+    int64_t g = 0;
+    CHECK(rs_select_roots(d, 6, 4, roots, loads) == RS_OK);
+    CHECK(roots[1] == -1 && roots[2] == 0 && loads[0] > 0);
+    roots[1] = 0;
+    CHECK(rs_plan_create_rooted(d, 6, 4, 16, 1, 0, roots, &plan) == RS_OK && plan != NULL);
+    CHECK(rs_plan_offsets(plan, off, 6) == RS_OK);
+    for (i = 0; i < 6; ++i) CHECK(off[i] / rs_plan_shard_elems(plan) == roots[i]);
+    rs_plan_destroy(plan);
+    plan = NULL;
+    roots[2] = 4;
+    CHECK(rs_plan_create_rooted(d, 6, 4, 16, 1, 0, roots, &plan) == RS_EINVAL && plan == NULL);
+    CHECK(rs_shard_dim_granularity(shape, 3, 1, 128, &g) == RS_OK && g == 64 * 48);
+    CHECK(rs_shard_dim_granularity(shape, 3, 0, 128, &g) == RS_EINVAL);
+  }
   d[0].block_mode = 99;
   CHECK(rs_plan_create(d, 6, 4, 16, 1, 0, &plan) == RS_EINVAL && plan == NULL);
   rs_plan_destroy(NULL);

@@ -7,6 +7,7 @@ import sys
 import numpy as np
 import torch
 
+from oracle import placement as PL
 from oracle import plan as P
 from paper_2602_22437_amd import binding as B
 
@@ -32,14 +33,21 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
 class Unit:
     """One FSDP unit planned by both sides."""
 
-    def __init__(self, tensors, world, align_bytes=16, min_itemsize=1, tensor_align=0, device=0, order=0):
+    def __init__(self, tensors, world, align_bytes=16, min_itemsize=1, tensor_align=0, device=0, order=0,
+                 roots=None):
         self.tensors = [tuple(t) for t in tensors]
         self.world = world
         self.specs = [P.TensorSpec(*t) for t in self.tensors]
-        self.oracle = P.make_plan(self.specs, world, align_bytes, min_itemsize,
-                                  tensor_align=tensor_align or None, order=order)
-        self.plan = B.rs_plan_create_ordered(self.tensors, world, align_bytes, min_itemsize, tensor_align,
-                                             order)
+        if roots is None:
+            self.oracle = P.make_plan(self.specs, world, align_bytes, min_itemsize,
+                                      tensor_align=tensor_align or None, order=order)
+            self.plan = B.rs_plan_create_ordered(self.tensors, world, align_bytes, min_itemsize,
+                                                 tensor_align, order)
+        else:       # every tensor whole on its root device
+            self.oracle = PL.rooted_plan(self.specs, world, roots, align_bytes, min_itemsize,
+                                         tensor_align or None)
+            self.plan = B.rs_plan_create_rooted(self.tensors, world, roots, align_bytes, min_itemsize,
+                                                tensor_align)
         assert B.rs_plan_shard_elems(self.plan) == self.oracle.S
         assert B.rs_plan_offsets(self.plan) == self.oracle.offsets
         B.rs_plan_upload(self.plan, device)

@@ -84,10 +84,28 @@ int main(int argc, char** argv) {
     std::vector<rs::TensorHost> t;
     REQUIRE(rs::describe_tensors(descs.data(), n, &t) == RS_OK);
     int64_t S = 0;
-    REQUIRE(rs::solve_shard_size(t, world, g_coll, A, &S) == RS_OK);
-    REQUIRE(S > 0 && S % g_coll == 0);
     std::vector<int64_t> starts;
-    REQUIRE(rs::check_valid_shard(t, world, S, A, &starts));
+    if (c % 4 == 1) {
+      // every tensor whole on a device of its own choosing; some devices stay empty
+      std::vector<int32_t> roots, perm;
+      for (int i = 0; i < n; ++i) roots.push_back(int32_t(pick(0, world - 1)));
+      REQUIRE(rs::rooted_layout(t, world, g_coll, A, roots.data(), &perm, &starts, &S) == RS_OK);
+      std::vector<rs::TensorHost> placed;
+      for (size_t j = 0; j < perm.size(); ++j) {
+        placed.push_back(t[size_t(perm[j])]);
+        const int64_t k = roots[size_t(perm[j])];
+        REQUIRE(starts[j] >= k * S && starts[j] + placed.back().e <= (k + 1) * S);
+      }
+      t = placed;
+      std::vector<int32_t> lpt(size_t(n), 0);
+      std::vector<double> loads(size_t(world), 0.0);
+      rs::select_roots(t, int(world), lpt.data(), loads.data());
+      for (int i = 0; i < n; ++i) REQUIRE(t[size_t(i)].cols == 0 ? lpt[size_t(i)] == -1 : (lpt[size_t(i)] >= 0 && lpt[size_t(i)] < world));
+    } else {
+      REQUIRE(rs::solve_shard_size(t, world, g_coll, A, &S) == RS_OK);
+      REQUIRE(rs::check_valid_shard(t, world, S, A, &starts));
+    }
+    REQUIRE(S > 0 && S % g_coll == 0);
     bool all_quant = true, all_state = true;
     int64_t sb = 0, stb = 0, prev_end = 0;
     for (size_t i = 0; i < t.size(); ++i) {

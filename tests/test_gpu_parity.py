@@ -449,6 +449,61 @@ def test_reordered_plans_all_ops(order):
         u.close()
 
 
+def test_rooted_plan_all_ops():
+    """RaggedShard(r_t): every tensor whole on its root device, some devices empty, tensors of one
+    device back to back.  All four kernels run from the same tables as for a balanced plan."""
+    tensors = [(300, 136, MODE_128x128), (200, 0, MODE_1x128), (64, 520, MODE_1x128), (129, 256, MODE_128x128),
+               (1000, 0, MODE_1x128), (40, 128, MODE_128x128), (77, 24, MODE_1x128)]
+    roots = [3, 0, 3, 1, 1, 5, 0]
+    u = Unit(tensors, 6, roots=roots)
+    try:
+        assert B.rs_plan_order(u.plan) == [1, 6, 3, 4, 0, 2, 5]
+        params = [normal_bf16(23, 0, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        _, db_bits = check_pack_unpack(u, params, "rooted")
+        for k in range(6):
+            parts = np.stack([normal_bf16(23, 0, 1, k * 8 + w, u.S, 1e-3) for w in range(6)])
+            check_reduce(u, k, parts, "rooted")
+        c, s, wc, ws = check_quant(u, db_bits, "rooted", range(6))
+        check_dequant_unpack(u, c, s, wc, ws, "rooted")
+    finally:
+        u.close()
+
+
+def test_redistribute_to_roots_and_back():
+    """Algorithm 2's data path on one device: the momentum of a unit sits in the balanced buffer
+    P; redistributing to RaggedShard(r) is the group copy-out of P into views of the rooted
+    buffer Q (one launch, no intermediate tensors), and the way back is P's copy-in from the same
+    views.  Roots come from the library's SelectRoot."""
+    wl = WORKLOADS[1]
+    tensors = [(t.rows, t.cols, MODE_WHOLE if t.cols else t.mode) for t in wl.tensors]
+    mats = [i for i, t in enumerate(tensors) if t[1] > 0]
+    roots, _ = B.rs_select_roots(tensors, 3)
+    roots = [r if r >= 0 else 0 for r in roots]            # the vectors stay with device 0
+    p = Unit([(t.rows, t.cols, t.mode) for t in wl.tensors], wl.world, 16, 2)
+    q = Unit(tensors, 3, 16, 2, roots=roots)
+    try:
+        assert len({roots[i] for i in mats}) == min(3, len(mats))
+        params = [normal_bf16(29, 1, 0, i, s.e, 0.02) for i, s in enumerate(p.specs)]
+        p_bits = OD.ragged_pack(params, p.oracle.offsets, p.total)
+        q_bits = OD.ragged_pack(params, q.oracle.offsets, q.total)
+        pbuf = to_dev_bf16(p_bits)
+        qbuf = torch.full((q.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        views = [qbuf[l:l + s.e] for l, s in zip(q.oracle.offsets, q.specs)]
+        say("redistribute P -> Q")
+        B.rs_group_zero(q.plan, qbuf)
+        B.rs_unpack_bf16(p.plan, pbuf, p.table(views))
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_of(qbuf), q_bits)
+        say("redistribute Q -> P")
+        back = torch.full((p.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        B.rs_pack(p.plan, p.table(views), back)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_of(back), p_bits)
+    finally:
+        p.close()
+        q.close()
+
+
 def test_whole_path_replays_from_a_hip_graph():
     """Device calls neither allocate nor synchronise, so the whole path (pack, reduce, quantise,
     unpack, Adam step) can be captured once and replayed: three replays on fresh inputs, with eager
