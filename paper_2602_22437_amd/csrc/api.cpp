@@ -84,6 +84,15 @@ int64_t state_blocks_in_front(const rs_plan& plan, int64_t x) {
   return cnt;
 }
 
+// Host staging array for a device pointer table; empty when the allocation fails.
+struct Staging {
+  explicit Staging(size_t n) : count(n), data(new (std::nothrow) void*[n]()) {}
+  size_t size() const { return count; }
+  void*& operator[](size_t i) { return data[i]; }
+  size_t count;
+  std::unique_ptr<void*[]> data;
+};
+
 int build_plan(const rs_tensor_desc* descs, int n, int world, int align_bytes, int min_itemsize,
                int tensor_align_elems, std::vector<rs::TensorHost>* t, int64_t* g_coll, int64_t* A) {
   if (!descs || n <= 0 || world <= 0 || align_bytes <= 0 || min_itemsize <= 0 ||
@@ -397,12 +406,19 @@ int rs_tensor_table_create(const rs_plan* plan, const void* const* ptrs, rs_tens
     return RS_ENOMEM;
   }
   // device table in buffer order, like the tensor records
-  std::vector<const void*> ordered(size_t(n), nullptr);
-  for (int j = 0; j < n; ++j) ordered[size_t(j)] = ptrs[plan->orig[size_t(j)]];
-  if (hipMemcpy(tab->ptrs, ordered.data(), sizeof(void*) * n, hipMemcpyHostToDevice) != hipSuccess) {
+  int copied = RS_ENOMEM;
+  try {
+    std::vector<const void*> ordered(size_t(n), nullptr);
+    for (int j = 0; j < n; ++j) ordered[size_t(j)] = ptrs[plan->orig[size_t(j)]];
+    copied = hipMemcpy(tab->ptrs, ordered.data(), sizeof(void*) * n, hipMemcpyHostToDevice) == hipSuccess
+                 ? RS_OK
+                 : RS_EHIP;
+  } catch (const std::bad_alloc&) {
+  }
+  if (copied != RS_OK) {
     (void)hipFree(tab->ptrs);
     delete tab;
-    return RS_EHIP;
+    return copied;
   }
   *out = tab;
   return RS_OK;
@@ -600,7 +616,8 @@ int rs_adam8_batch_create(const rs_plan* plan, int rank, int count, const float*
   if (!grads || !masters || !m_codes || !v_codes || !m_absmax || !v_absmax || count <= 0 ||
       count > 65535 || rank < 0 || rank >= plan->world)
     return RS_EINVAL;
-  std::vector<void*> host(size_t(count) * 7);
+  Staging host(size_t(count) * 7);
+  if (!host.data) return RS_ENOMEM;
   for (int u = 0; u < count; ++u) {
     void* const param = params_bf16 ? params_bf16[u] : nullptr;
     const int brc = adam8_check_buffers(plan, rank, grads[u], masters[u], param, m_codes[u], v_codes[u],
@@ -624,7 +641,7 @@ int rs_adam8_batch_create(const rs_plan* plan, int rank, int count, const float*
     delete b;
     return RS_ENOMEM;
   }
-  if (hipMemcpy(b->ptrs, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+  if (hipMemcpy(b->ptrs, host.data.get(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
     (void)hipFree(b->ptrs);
     delete b;
     return RS_EHIP;
@@ -665,7 +682,8 @@ int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* 
   if (!shards || !codes || !scales || count <= 0 || count > 65535 || rank < 0 || rank >= plan->world)
     return RS_EINVAL;
   const bool has_scales = plan->scale_begin[size_t(rank) + 1] > plan->scale_begin[size_t(rank)];
-  std::vector<void*> host(size_t(count) * 3);
+  Staging host(size_t(count) * 3);
+  if (!host.data) return RS_ENOMEM;
   for (int u = 0; u < count; ++u) {
     if (!shards[u] || !codes[u] || (!scales[u] && has_scales)) return RS_EINVAL;
     if (!aligned16(shards[u]) || !aligned16(codes[u]) || (reinterpret_cast<uintptr_t>(scales[u]) & 3))
@@ -684,7 +702,7 @@ int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* 
     delete b;
     return RS_ENOMEM;
   }
-  if (hipMemcpy(b->ptrs, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+  if (hipMemcpy(b->ptrs, host.data.get(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
     (void)hipFree(b->ptrs);
     delete b;
     return RS_EHIP;

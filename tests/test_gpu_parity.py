@@ -580,3 +580,74 @@ def test_whole_path_replays_from_a_hip_graph():
             assert np.array_equal(bits_of(e_buf["dbuf"]), OD.ragged_pack(params, u.oracle.offsets, total))
     finally:
         u.close()
+
+
+def test_one_plan_serves_two_threads_on_two_streams():
+    """An uploaded plan and its tables are read-only: two host threads, each with a stream and
+    buffers of its own, run the path at the same time and must each get the single-stream result."""
+    import threading
+
+    tensors = [(512, 256, MODE_128x128), (300, 0, MODE_1x128), (257, 136, MODE_128x128), (384, 384, MODE_128x128)]
+    W, reps = 4, 10
+    u = Unit(tensors, W)
+    try:
+        S, total = u.S, u.total
+        nb = B.rs_plan_num_scales(u.plan)
+
+        def make(seed):
+            params = [normal_bf16(70, seed, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+            parts = np.stack([normal_bf16(70, seed, 1, w, S, 1e-3) for w in range(W)])
+            b = dict(src=[to_dev_bf16(p) for p in params], parts=to_dev_bf16(parts.reshape(-1)),
+                     dst=[torch.zeros(s.e, dtype=torch.bfloat16, device="cuda") for s in u.specs],
+                     dbuf=torch.zeros(total, dtype=torch.bfloat16, device="cuda"),
+                     grad=torch.zeros(S, dtype=torch.float32, device="cuda"),
+                     codes=torch.zeros(total, dtype=torch.uint8, device="cuda"),
+                     scales=torch.zeros(nb, dtype=torch.float32, device="cuda"))
+            b["tab_src"], b["tab_dst"] = u.table(b["src"]), u.table(b["dst"])
+            return b
+
+        def path(b, rank, stream):
+            B.rs_pack(u.plan, b["tab_src"], b["dbuf"], stream)
+            B.rs_reduce(u.plan, rank, b["parts"], S, b["grad"], stream)
+            B.rs_quantize(u.plan, -1, b["dbuf"], b["codes"], b["scales"], stream)
+            B.rs_unpack(u.plan, b["codes"], b["scales"], b["tab_dst"], stream)
+
+        def snapshot(b):
+            return [b[k].clone() for k in ("dbuf", "grad", "codes", "scales")] + [t.clone() for t in b["dst"]]
+
+        work = [make(0), make(1)]
+        want = []
+        for i, b in enumerate(work):
+            path(b, i, None)
+            torch.cuda.synchronize()
+            want.append(snapshot(b))
+            for k in ("dbuf", "grad", "codes", "scales"):
+                b[k].view(torch.uint8).fill_(0x33)
+            for t in b["dst"]:
+                t.view(torch.uint8).fill_(0x33)
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        errors = []
+
+        def worker(i):
+            try:
+                torch.cuda.set_device(0)
+                for _ in range(reps):
+                    path(work[i], i, streams[i])
+            except Exception as exc:      # surfaced in the main thread
+                errors.append(exc)
+
+        say("two threads, two streams")
+        threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join(timeout=100)
+            assert not t.is_alive()
+        torch.cuda.synchronize()
+        assert not errors, errors
+        for i, b in enumerate(work):
+            for got, exp in zip(snapshot(b), want[i]):
+                assert torch.equal(got.view(torch.uint8), exp.view(torch.uint8)), f"thread {i} result differs"
+    finally:
+        u.close()
