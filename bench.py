@@ -341,6 +341,18 @@ def main():
             "ms": round(qa_ms, 4), "bytes": qa_bytes, "GBps": round(qa_bytes / qa_ms / 1e6, 1),
             "frac_of_peak": round(qa_bytes / qa_ms / 1e6 / HBM_PEAK_GBPS, 4),
             "note": "same kernel over all W shards of a unit in one launch; not part of the timed step"}
+    if quant:   # reduce and quantise fused: the fp32 mean never reaches HBM
+        rq_bytes = 2 * W * payload_r + S + 4 * (hi - lo)
+        rq_ms = timed(lambda i=0: B.rs_reduce_quantize(plan, rank, U[i % units]["partials"], S,
+                                                       U[i % units]["shard_codes"], U[i % units]["shard_scales"],
+                                                       None, stream), max(units, 8))
+        kernels["reduce_quantize"] = {
+            "ms": round(rq_ms, 4), "bytes": rq_bytes, "GBps": round(rq_bytes / rq_ms / 1e6, 1),
+            "frac_of_peak": round(rq_bytes / rq_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "note": "shard_reduce + block_quant in one launch (codes and scales out, no fp32 mean); "
+                    "not part of the timed step"}
+        for d in U:   # the timed path's codes come from the packed parameters: restore them
+            B.rs_quantize(plan, rank, d["shard"], d["shard_codes"], d["shard_scales"], stream)
     if quant:   # gathered FP8 unit straight into fp32 master copies (first 4 units: 4 bytes per element)
         f32_units = U[:min(units, 4)]
         for d in f32_units:

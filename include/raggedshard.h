@@ -244,6 +244,21 @@ int rs_shard_batch_create(const rs_plan* plan, int rank, int count, const void* 
 void rs_shard_batch_destroy(rs_shard_batch* batch);
 int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* stream);
 
+/* ---- shard_reduce and block_quant fused: the mean of the partials leaves the chip as FP8 ----
+ * A group-level fusion in the sense of Section 5: where the mean itself is what travels next
+ * (quantised gradient exchange between replicas), it is formed in registers and written as codes
+ * and scales only, which saves writing and re-reading S fp32 values.
+ *   mean[i] = rs_reduce's out[i], bit for bit (same summation order);
+ *   per block: amax = max|mean|, scale = amax/448 (fp32), code = E4M3 RNE of
+ *   clamp(mean/scale, +-448) with a correctly rounded fp32 division; a block whose scale is 0
+ *   (all zero, or amax below 2^-140) gives scale 0 and codes 0x00.  Padding codes are 0x00.
+ * partials, row_stride: as for rs_reduce.  codes: device, S uint8, 16-byte aligned; scales:
+ * device, the rank's slice [lo, hi).  mean_out: NULL, or device S fp32, 16-byte aligned, which
+ * then also receives the mean (0 on padding).  RS_EUNSUPPORTED if the plan holds a tensor
+ * without FP8 blocks. */
+int rs_reduce_quantize(const rs_plan* plan, int rank, const void* partials, int64_t row_stride,
+                       uint8_t* codes, float* scales, float* mean_out, void* stream);
+
 /* ---- dequant_unpack: gathered FP8 unit -> per-parameter bf16 --------------------------------
  * dst_t[i] = bf16_rne( value(codes[l_t + i]) * scales[block of i] ).
  * codes: device, world*S uint8, 16-byte aligned; scales: device, all of the unit's scales. */

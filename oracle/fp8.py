@@ -82,14 +82,17 @@ def _as_2d(spec: TensorSpec) -> Tuple[int, int, int, int]:
     raise ValueError("tensor is not quantised")
 
 
-def quantise_matrix(bits: np.ndarray, bh: int, bw: int) -> Tuple[np.ndarray, np.ndarray]:
-    """Steps 1-3 on an (R, C) matrix of bf16 bits with bh x bw blocks.
-    Returns codes (R, C) uint8 and scales (ceil(R/bh), ceil(C/bw)) fp32."""
-    R, C = bits.shape
+def quantise_matrix_f32(x: np.ndarray, bh: int, bw: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Steps 1-3 on an (R, C) matrix of fp32 values with bh x bw blocks.
+    Returns codes (R, C) uint8 and scales (ceil(R/bh), ceil(C/bw)) fp32.
+    A block is live when its scale is non-zero.  For bf16 inputs that is the same as amax > 0
+    (the smallest bf16 magnitude over 448 is still a non-zero fp32); an fp32 input below 2^-140
+    can have its scale underflow to zero, and such a block is stored like an all-zero one."""
+    x = np.asarray(x, dtype=np.float32)
+    R, C = x.shape
     nbr, nbc = -(-R // bh), -(-C // bw)
     codes = np.empty((R, C), dtype=np.uint8)
     scales = np.empty((nbr, nbc), dtype=np.float32)
-    x = bf16_bits_to_f32(bits)
     for br in range(nbr):
         rows = x[br * bh:(br + 1) * bh]                       # (h, C), h <= bh
         h = rows.shape[0]
@@ -99,14 +102,20 @@ def quantise_matrix(bits: np.ndarray, bh: int, bw: int) -> Tuple[np.ndarray, np.
         blk = wide.reshape(h, nbc, bw)
         amax = np.abs(blk).max(axis=(0, 2)).astype(np.float32)   # (nbc,)
         scale = amax / E4M3_MAX                                   # fp32 / fp32
-        safe = np.where(amax > 0, scale, np.float32(1.0))
+        live = scale > 0
+        safe = np.where(live, scale, np.float32(1.0))
         y = blk / safe[None, :, None]                             # fp32 / fp32
         y = np.clip(y, -E4M3_MAX, E4M3_MAX)
         c = encode_e4m3(y)
-        c = np.where((amax > 0)[None, :, None], c, np.uint8(0))
+        c = np.where(live[None, :, None], c, np.uint8(0))
         codes[br * bh:(br + 1) * bh] = c.reshape(h, nbc * bw)[:, :C]
-        scales[br] = np.where(amax > 0, scale, np.float32(0.0))
+        scales[br] = np.where(live, scale, np.float32(0.0))
     return codes, scales
+
+
+def quantise_matrix(bits: np.ndarray, bh: int, bw: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Steps 1-3 on an (R, C) matrix of bf16 bits with bh x bw blocks."""
+    return quantise_matrix_f32(bf16_bits_to_f32(bits), bh, bw)
 
 
 def quantise_tensor(bits: np.ndarray, spec: TensorSpec) -> Tuple[np.ndarray, np.ndarray]:
@@ -167,11 +176,12 @@ def block_quant_all(plan: Plan, db: np.ndarray) -> Tuple[np.ndarray, np.ndarray]
     return codes, scales
 
 
-def block_quant_shard(plan: Plan, k: int, region: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+def block_quant_shard(plan: Plan, k: int, region: np.ndarray, f32: bool = False) -> Tuple[np.ndarray, np.ndarray]:
     """Quantise rank k's region using nothing but that region (the point of keeping blocks
     whole on a rank: no scale exchange).  Each segment is a run of whole granules, i.e.
     whole rows of quantisation blocks, and is quantised as a tensor of its own.
-    Returns codes (S,) and the rank's slice of the scale array."""
+    region: bf16 bits, or (f32) fp32 values.  Returns codes (S,) and the rank's slice of the
+    scale array."""
     codes = np.zeros(plan.S, dtype=np.uint8)
     out_scales = []
     for t, src_off, dst_off, n in plan.rank_segments(k):
@@ -184,11 +194,27 @@ def block_quant_shard(plan: Plan, k: int, region: np.ndarray) -> Tuple[np.ndarra
         else:
             assert src_off % spec.g == 0 and n % spec.cols == 0
             sub = TensorSpec(n // spec.cols, spec.cols, spec.mode)
-        c, s = quantise_tensor(region[dst_off:dst_off + n], sub)
+        if f32:
+            R, C, bh, bw = _as_2d(sub)
+            c, s = quantise_matrix_f32(np.asarray(region[dst_off:dst_off + n], dtype=np.float32).reshape(R, C),
+                                       bh, bw)
+            c, s = c.reshape(-1), s.reshape(-1)
+        else:
+            c, s = quantise_tensor(region[dst_off:dst_off + n], sub)
         codes[dst_off:dst_off + n] = c
         out_scales.append(s)
     sc = np.concatenate(out_scales) if out_scales else np.zeros(0, dtype=np.float32)
     return codes, sc.astype(np.float32)
+
+
+def reduce_quant_shard(plan: Plan, k: int, partials: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """The fused form of the two steps on rank k: the fp32 mean of the partials (W, S) of bf16
+    bits in the stated summation order, zero on padding, and that mean quantised block by
+    block without passing through bf16.  Returns (codes, scales, mean)."""
+    from .dbuffer import shard_reduce_f32_ordered
+    mean = shard_reduce_f32_ordered(partials, plan.rank_segments(k))
+    codes, scales = block_quant_shard(plan, k, mean, f32=True)
+    return codes, scales, mean
 
 
 def dequant_unpack_f32(plan: Plan, codes: np.ndarray, scales: np.ndarray) -> List[np.ndarray]:

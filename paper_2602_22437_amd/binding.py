@@ -27,7 +27,7 @@ EXPORTS = [
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
-    "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity",
+    "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize",
 ]
 
 
@@ -101,6 +101,7 @@ _lib.rs_group_scale.argtypes = [_P, C.c_float, _P, _P]
 _lib.rs_group_zero.argtypes = [_P, _P, _P]
 _lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
+_lib.rs_reduce_quantize.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
 _lib.rs_unpack_f32.argtypes = [_P, _P, _P, _P, _P]
 _lib.rs_shard_batch_create.argtypes = [_P, C.c_int, C.c_int, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P),
@@ -345,6 +346,13 @@ def rs_reduce(plan, rank: int, partials, row_stride: int, out, stream=None) -> N
 def rs_quantize(plan, rank: int, shard, codes, scales, stream=None) -> None:
     _check(_lib.rs_quantize(plan, int(rank), _ptr(shard), _ptr(codes), _ptr(scales), _stream(stream)),
            "rs_quantize")
+
+
+def rs_reduce_quantize(plan, rank: int, partials, row_stride: int, codes, scales, mean_out=None,
+                       stream=None) -> None:
+    _check(_lib.rs_reduce_quantize(plan, int(rank), _ptr(partials), int(row_stride), _ptr(codes),
+                                   _ptr(scales), None if mean_out is None else _ptr(mean_out),
+                                   _stream(stream)), "rs_reduce_quantize")
 
 
 def rs_shard_batch_create(plan, rank: int, shards: Sequence, codes: Sequence, scales: Sequence) -> int:

@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libraggedshard.so")
-SOURCES = ["planner.cpp", "tables.cpp", "api.cpp", "group_ops.hip", "shard_reduce.hip", "fp8_codec.hip", "adam8.hip"]
+SOURCES = ["planner.cpp", "tables.cpp", "api.cpp", "group_ops.hip", "shard_reduce.hip", "fp8_codec.hip", "reduce_quant.hip",
+           "adam8.hip"]
 
 # packed-fp32 VALU forms are switched off for all device code; fp32 division stays IEEE
 # (correctly rounded) and denormals are kept - the FP8 codec depends on both.

@@ -135,7 +135,7 @@ void finish_plan(rs_plan* p, const std::vector<int64_t>& starts) {
 
 extern "C" {
 
-int rs_version(void) { return 130; }
+int rs_version(void) { return 140; }
 
 const char* rs_strerror(int code) {
   switch (code) {
@@ -519,6 +519,23 @@ int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes
   }
   return rs::launch_block_quant(plan->dev, first, count, shard, codes, scales, nullptr, 0, elem_base,
                                 scale_off, static_cast<hipStream_t>(stream));
+}
+
+int rs_reduce_quantize(const rs_plan* plan, int rank, const void* partials, int64_t row_stride,
+                       uint8_t* codes, float* scales, float* mean_out, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_quant) return RS_EUNSUPPORTED;
+  if (!partials || !codes || !scales || rank < 0 || rank >= plan->world || row_stride < plan->S)
+    return RS_EINVAL;
+  if (!aligned16(partials) || !aligned16(codes) || !aligned16(mean_out) || row_stride % 8 != 0 ||
+      (reinterpret_cast<uintptr_t>(scales) & 3))
+    return RS_EALIGN;
+  const std::vector<int64_t>& ib = plan->host.item_begin;
+  return rs::launch_reduce_quant(plan->dev, ib[size_t(rank)], ib[size_t(rank) + 1] - ib[size_t(rank)],
+                                 partials, row_stride, codes, scales, mean_out,
+                                 int64_t(rank) * plan->S, plan->scale_begin[size_t(rank)],
+                                 int(plan->world), static_cast<hipStream_t>(stream));
 }
 
 // checks the hyper-parameters and derives the step's fp32 constants: each is evaluated in

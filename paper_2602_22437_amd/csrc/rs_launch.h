@@ -18,6 +18,11 @@ int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, in
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
                        uint8_t* codes, float* scales, void* const* batch, int batch_count,
                        int64_t elem_base, int64_t scale_off, hipStream_t st);
+// shard_reduce and block_quant in one pass over the rank's quantisation items; mean_out may be null
+int launch_reduce_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count,
+                        const void* partials, int64_t row_stride, uint8_t* codes, float* scales,
+                        float* mean_out, int64_t elem_base, int64_t scale_off, int world,
+                        hipStream_t st);
 int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
                           int64_t gpr, hipStream_t st);

@@ -1,5 +1,6 @@
 // shard_reduce: the arithmetic of the gradient ReduceScatter as one rank sees it (gfx950, wave64).
 #include "device_util.h"
+#include "reduce_order.h"
 
 namespace rs {
 
@@ -11,30 +12,6 @@ constexpr int kThreads = 256;  // lanes per granule
 // accumulator sets (row w -> set w mod 8) that are combined pairwise at the end, so the
 // summation order is fixed and the rounding error grows with W/8 + 3, not W.
 // -------------------------------------------------------------------------------------------
-__device__ __forceinline__ void add_bf16x8(float (&acc)[8], const u32x4 v) {
-  acc[0] += __uint_as_float(v.x << 16);
-  acc[1] += __uint_as_float(v.x & 0xffff0000u);
-  acc[2] += __uint_as_float(v.y << 16);
-  acc[3] += __uint_as_float(v.y & 0xffff0000u);
-  acc[4] += __uint_as_float(v.z << 16);
-  acc[5] += __uint_as_float(v.z & 0xffff0000u);
-  acc[6] += __uint_as_float(v.w << 16);
-  acc[7] += __uint_as_float(v.w & 0xffff0000u);
-}
-
-// rows w .. w + 7 of this lane's column; rows at or past W read as +0 (they keep the row -> set rule)
-__device__ __forceinline__ void load_rows(u32x4 (&v)[8], const uint16_t* p, int64_t row_stride, int w,
-                                          int W) {
-  if (w + 8 <= W) {
-#pragma unroll
-    for (int a = 0; a < 8; ++a) v[a] = ld16(p + int64_t(w + a) * row_stride);
-  } else {
-#pragma unroll
-    for (int a = 0; a < 8; ++a)
-      v[a] = w + a < W ? ld16(p + int64_t(w + a) * row_stride) : u32x4{0, 0, 0, 0};
-  }
-}
-
 // kReduceThreads = 256: one granule per workgroup; 512: two granules (8 KiB contiguous per row).
 // kDouble keeps the next eight rows in flight while the current ones are added.  Measured on
 // regions of 4096 granules and more: 512 lanes with kDouble is the fastest shape (+5 % at
@@ -82,39 +59,10 @@ __global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
     return;
   }
 
-  const uint16_t* p = P + i0 + lane_off;
-  u32x4 v[8];
-  load_rows(v, p, row_stride, 0, W);
-  float acc[8][8];
+  float sum[8], r[8];
+  reduce_column<kDouble, true>(P + i0 + lane_off, row_stride, W, 8, sum);
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
-#pragma unroll
-    for (int q = 0; q < 8; ++q) acc[a][q] = 0.0f;
-
-  for (int w = 8;; w += 8) {   // v holds rows w - 8 .. w - 1
-    if (kDouble) {
-      u32x4 next[8];
-      if (w < W) load_rows(next, p, row_stride, w, W);
-#pragma unroll
-      for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
-      if (w >= W) break;
-#pragma unroll
-      for (int a = 0; a < 8; ++a) v[a] = next[a];
-    } else {
-#pragma unroll
-      for (int a = 0; a < 8; ++a) add_bf16x8(acc[a], v[a]);
-      if (w >= W) break;
-      load_rows(v, p, row_stride, w, W);
-    }
-  }
-  float r[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const float s01 = acc[0][q] + acc[1][q], s23 = acc[2][q] + acc[3][q];
-    const float s45 = acc[4][q] + acc[5][q], s67 = acc[6][q] + acc[7][q];
-    const float m = ((s01 + s23) + (s45 + s67)) * inv_w;
-    r[q] = (mask >> q) & 1u ? m : 0.0f;
-  }
+  for (int q = 0; q < 8; ++q) r[q] = (mask >> q) & 1u ? sum[q] * inv_w : 0.0f;
   st16(o, u32x4{__float_as_uint(r[0]), __float_as_uint(r[1]), __float_as_uint(r[2]),
                 __float_as_uint(r[3])});
   st16(o + 4, u32x4{__float_as_uint(r[4]), __float_as_uint(r[5]), __float_as_uint(r[6]),

@@ -53,6 +53,7 @@ int main(void) {
   CHECK(rs_plan_offsets(plan, off, 5) == RS_EINVAL);
   CHECK(rs_plan_scale_range(plan, 4, &lo, &hi) == RS_EINVAL);
   CHECK(rs_pack(plan, NULL, NULL, NULL) == RS_ENOTUPLOADED);
+  CHECK(rs_reduce_quantize(plan, 0, NULL, 0, NULL, NULL, NULL, NULL) == RS_ENOTUPLOADED);
   CHECK(rs_adam8_step(plan, 0, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL) == RS_ENOTUPLOADED);
   rs_plan_destroy(plan);
   plan = NULL;

@@ -81,6 +81,8 @@ def test_guard_bands_survive_every_operation():
             everything.extend(mine)
             B.rs_reduce(u.plan, k, parts, S, out.t); check_all("rs_reduce")
             B.rs_quantize(u.plan, k, dbuf.t[k * S:(k + 1) * S], kc.t, ks.t); check_all("rs_quantize rank")
+            B.rs_reduce_quantize(u.plan, k, parts, S, kc.t, ks.t); check_all("rs_reduce_quantize")
+            B.rs_reduce_quantize(u.plan, k, parts, S, kc.t, ks.t, out.t); check_all("rs_reduce_quantize + mean")
             B.rs_adam8_step(u.plan, k, (1e-3, 0.9, 0.95, 1e-8, 0.01, 1), out.t, master.t, param.t, mc.t, vc.t,
                             am.t, av.t); check_all("rs_adam8_step")
             B.rs_state_dequantize(u.plan, k, mc.t, am.t, False, out.t); check_all("rs_state_dequantize")

@@ -72,6 +72,36 @@ def check_reduce(u: Unit, rank, partial_bits, label, poison_padding=True):
     return got
 
 
+def check_reduce_quant(u: Unit, rank, partial_bits, label):
+    """The fused reduce + quantise against the oracle's composition, with and without the fp32
+    mean written out; the mean must also equal rs_reduce bit for bit."""
+    W, S = partial_bits.shape
+    say(f"reduce_quantize {label}: rank={rank} W={W} S={S}")
+    want_c, want_s, want_mean = OF.reduce_quant_shard(u.oracle, rank, partial_bits)
+    lo, hi = u.oracle.scale_range(rank)
+    dev = to_dev_bf16(partial_bits.reshape(-1))
+    for with_mean in (False, True):
+        codes = torch.full((S,), 0xEE, dtype=torch.uint8, device="cuda")
+        scales = torch.full((max(hi - lo, 1),), float("nan"), dtype=torch.float32, device="cuda")
+        mean = torch.full((S,), float("nan"), dtype=torch.float32, device="cuda") if with_mean else None
+        B.rs_reduce_quantize(u.plan, rank, dev, S, codes, scales, mean)
+        torch.cuda.synchronize()
+        got_s = scales.cpu().numpy()[:hi - lo]
+        assert np.array_equal(got_s.view(np.uint32), want_s.view(np.uint32)), f"fused scales differ ({label})"
+        got_c = codes.cpu().numpy()
+        if not np.array_equal(got_c, want_c):
+            bad = np.flatnonzero(got_c != want_c)
+            raise AssertionError(f"fused codes differ ({label}) at {bad[:8]}: got {got_c[bad[:8]]} "
+                                 f"want {want_c[bad[:8]]}")
+        if with_mean:
+            assert np.array_equal(mean.cpu().numpy().view(np.uint32), want_mean.view(np.uint32)), \
+                f"fused mean differs ({label})"
+            out = torch.empty(S, dtype=torch.float32, device="cuda")
+            B.rs_reduce(u.plan, rank, dev, S, out)
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int32), mean.view(torch.int32)), f"fused mean != rs_reduce ({label})"
+
+
 def check_quant(u: Unit, db_bits, label, ranks):
     """rank-by-rank and all-ranks quantisation against the oracle; returns device codes/scales."""
     want_codes, want_scales = OF.block_quant_all(u.oracle, db_bits)
@@ -139,6 +169,7 @@ def test_config1_all_ops():
         for k in range(wl.world):
             parts = np.stack([gen_partial(wl, 1, w, u.S, unit=k) for w in range(wl.world)])
             check_reduce(u, k, parts, "cfg1")
+            check_reduce_quant(u, k, parts, "cfg1")
         c, s, wc, ws = check_quant(u, db_bits, "cfg1", range(wl.world))
         check_dequant_unpack(u, c, s, wc, ws, "cfg1")
     finally:
@@ -224,6 +255,37 @@ def test_zero_blocks_negative_zero_and_tiny_values():
         u.close()
 
 
+def test_reduce_quantize_special_blocks():
+    """Blocks whose mean is all zero, all negative zero, tiny, or so tiny that the scale
+    underflows (amax = 2^-142 from one bf16 subnormal among 512 partials), next to ordinary ones;
+    one partial (the mean is the partial itself) and a count that is no multiple of 8."""
+    rows, cols = 260, 256
+    for W in (1, 13, 512):
+        u = Unit([(rows, cols, MODE_128x128), (700, 0, MODE_1x128)], W)      # W partials = W ranks
+        try:
+            S = u.S
+            busy = [k for k in range(W) if u.oracle.rank_segments(k)]
+            idle = [k for k in range(W) if not u.oracle.rank_segments(k)]
+            for k in busy[:4] + idle[:1]:
+                parts = np.stack([normal_bf16(31, W, k, w, S, 1e-3) for w in range(W)])
+                for t, src_off, dst_off, n in u.oracle.rank_segments(k):
+                    if t == 0:
+                        region = parts[:, dst_off:dst_off + n].reshape(W, -1, cols)
+                        assert np.shares_memory(region, parts)
+                        region[:, :, 0:128] = 0                    # zero tiles
+                        region[:, :, 128:256] = 0x8000             # negative zeros ...
+                        region[0, 0, 128] = 0x0001                 # ... and one subnormal: amax = 2^-133 / W
+                        if region.shape[1] > 128:                  # a second row of tiles keeps ordinary values
+                            region[:, 128:, :] = normal_bf16(31, W, k, 999, (region.shape[1] - 128) * cols,
+                                                             1e-3).reshape(1, -1, cols)
+                    else:
+                        parts[:, dst_off:dst_off + 256] = 0        # a zero run, and a run whose only value
+                        parts[W - 1, dst_off + 130] = 0x8001       # is a negative subnormal
+                check_reduce_quant(u, k, parts, f"special W={W}")
+        finally:
+            u.close()
+
+
 RAGGED_UNITS = [
     # (tensors, world, align_bytes, min_itemsize, tensor_align): odd pitches, partial tiles,
     # rows that are not 16-byte multiples, paper-literal A = 1 (nothing vector-aligned)
@@ -246,6 +308,7 @@ def test_ragged_units_all_ops(case):
         for k in range(world):
             parts = np.stack([normal_bf16(11, case, 1, k * 64 + w, u.S, 1e-3) for w in range(world)])
             check_reduce(u, k, parts, f"ragged{case}")
+            check_reduce_quant(u, k, parts, f"ragged{case}")
         c, s, wc, ws = check_quant(u, db_bits, f"ragged{case}", range(world))
         check_dequant_unpack(u, c, s, wc, ws, f"ragged{case}")
     finally:
@@ -443,6 +506,7 @@ def test_reordered_plans_all_ops(order):
         for k in range(5):
             parts = np.stack([normal_bf16(17, order, 1, k * 8 + w, u.S, 1e-3) for w in range(5)])
             check_reduce(u, k, parts, f"order{order}")
+            check_reduce_quant(u, k, parts, f"order{order}")
         c, s, wc, ws = check_quant(u, db_bits, f"order{order}", range(5))
         check_dequant_unpack(u, c, s, wc, ws, f"order{order}")
     finally:
@@ -463,6 +527,7 @@ def test_rooted_plan_all_ops():
         for k in range(6):
             parts = np.stack([normal_bf16(23, 0, 1, k * 8 + w, u.S, 1e-3) for w in range(6)])
             check_reduce(u, k, parts, "rooted")
+            check_reduce_quant(u, k, parts, "rooted")
         c, s, wc, ws = check_quant(u, db_bits, "rooted", range(6))
         check_dequant_unpack(u, c, s, wc, ws, "rooted")
     finally:

@@ -83,6 +83,15 @@ def test_config2_reduce(cfg2, rank):
     assert np.all(err <= REDUCE_TOL * OD.shard_reduce_abs_sum(parts))
     ordered = OD.shard_reduce_f32_ordered(parts, segs)
     assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), "fp32 summation order differs"
+    say(f"config 2: fused reduce + quantise rank {rank}")
+    lo, hi = u.oracle.scale_range(rank)
+    codes = torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda")
+    scales = torch.full((max(hi - lo, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    B.rs_reduce_quantize(u.plan, rank, to_dev_bf16(parts.reshape(-1)), u.S, codes, scales)
+    torch.cuda.synchronize()
+    want_c, want_s = OF.block_quant_shard(u.oracle, rank, ordered, f32=True)
+    assert np.array_equal(scales.cpu().numpy()[:hi - lo].view(np.uint32), want_s.view(np.uint32))
+    assert np.array_equal(codes.cpu().numpy(), want_c)
 
 
 def test_config2_quantize_all_and_by_rank(cfg2):

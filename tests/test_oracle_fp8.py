@@ -237,3 +237,90 @@ def test_dequantise_f32_against_library_and_exact_products():
         assert np.array_equal(o32.view(np.uint32), once.view(np.uint32))
         # rounding it to bf16 gives the bf16 form
         assert np.array_equal(F.f32_to_bf16_bits(o32), o16)
+
+
+# ---- fp32 inputs (the mean of the partials, quantised without passing through bf16) ----------
+
+def ref_quant_f32_block_by_block(x2d, bh, bw):
+    """Independent restatement for fp32 input: python loops over blocks, library cast as the
+    encoder, library division."""
+    x = torch.from_numpy(np.ascontiguousarray(x2d))
+    R, C = x.shape
+    codes = torch.zeros((R, C), dtype=torch.uint8)
+    scales = []
+    for r0 in range(0, R, bh):
+        row = []
+        for c0 in range(0, C, bw):
+            blk = x[r0:r0 + bh, c0:c0 + bw]
+            scale = blk.abs().max() / torch.tensor(448.0, dtype=torch.float32)
+            if scale == 0:
+                row.append(0.0)
+                continue
+            y = torch.clamp(blk / scale, -448.0, 448.0)
+            codes[r0:r0 + bh, c0:c0 + bw] = y.to(torch.float8_e4m3fn).view(torch.uint8)
+            row.append(float(scale))
+        scales.append(row)
+    return codes.numpy(), np.array(scales, dtype=np.float32)
+
+
+@pytest.mark.parametrize("shape,bh,bw", [((257, 130), 128, 128), ((300, 384), 128, 128), ((5, 300), 1, 128)])
+def test_quantise_f32_matrix_against_block_loop(shape, bh, bw):
+    rng = np.random.default_rng(15)
+    x = (rng.standard_normal(shape) * 1e-3).astype(np.float32)      # full fp32 mantissas
+    x[0, 0] = 0.0
+    if shape == (300, 384):
+        x[128:256, 128:256] = 0.0                                   # an all-zero block
+        x[0:128, 0:128] = -0.0
+        x[256:300, 0:128] = np.float32(1e-44)                       # scale underflows: a zero block
+        x[0:128, 256:384] *= np.float32(1e-36)                      # subnormal means, live block
+    c, s = F.quantise_matrix_f32(x, bh, bw)
+    c2, s2 = ref_quant_f32_block_by_block(x, bh, bw)
+    assert np.array_equal(s.view(np.uint32), s2.view(np.uint32))
+    assert np.array_equal(c, c2)
+    if shape == (300, 384):
+        assert s[2, 0] == 0 and np.all(c[256:300, 0:128] == 0)
+        assert s[0, 2] > 0 and np.any(c[0:128, 256:384] == 0x7E)
+
+
+def test_f32_and_bf16_quantisers_agree_on_bf16_values():
+    rng = np.random.default_rng(16)
+    bits = torch.from_numpy((rng.standard_normal((140, 260)) * 0.02).astype(np.float32)).to(
+        torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    bits[:, 128:256] = 0x0001                                        # smallest bf16 subnormal: still live
+    a = F.quantise_matrix(bits, 128, 128)
+    b = F.quantise_matrix_f32(bf16_bits_to_f32(bits), 128, 128)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+    assert a[1][0, 1] > 0 and np.all(a[0][:128, 128:256] == 0x7E)
+
+
+def test_fused_reduce_quantise_is_the_composition_and_stays_near_the_mean():
+    from oracle.dbuffer import shard_reduce, shard_reduce_f32_ordered
+    from workloads import gen_partial
+    wl, pl = toy_plan()
+    for k in (0, wl.world - 1):
+        parts = np.stack([gen_partial(wl, 4, w, pl.S) for w in range(wl.world)])
+        segs = pl.rank_segments(k)
+        codes, scales, mean = F.reduce_quant_shard(pl, k, parts)
+        assert np.array_equal(mean.view(np.uint32), shard_reduce_f32_ordered(parts, segs).view(np.uint32))
+        lo, hi = pl.scale_range(k)
+        assert scales.size == hi - lo
+        # dequantised codes lie within half an E4M3 step of the float64 mean (plus the reduce's own bound)
+        exact = shard_reduce(parts, segs).astype(np.float64)
+        tab = F.decode_table().astype(np.float64)
+        pos = 0
+        for t, src_off, dst_off, n in segs:
+            spec = pl.specs[t]
+            sub = P.TensorSpec(n // spec.cols, spec.cols, spec.mode) if spec.cols else P.TensorSpec(n, 0, spec.mode)
+            R, C, bh, bw = F._as_2d(sub)
+            nbc = -(-C // bw)
+            r, c = np.divmod(np.arange(n), C)
+            sc = scales[pos + (r // bh) * nbc + c // bw].astype(np.float64)
+            pos += sub.num_blocks
+            back = tab[codes[dst_off:dst_off + n]] * sc
+            x = exact[dst_off:dst_off + n]
+            assert np.all(np.abs(back - x) <= np.abs(x) * 2.0 ** -4 + sc * 2.0 ** -10 + 1e-9)
+        assert pos == scales.size
+        pay = np.zeros(pl.S, dtype=bool)
+        for _, _, d, n in segs:
+            pay[d:d + n] = True
+        assert np.all(codes[~pay] == 0) and np.all(mean[~pay] == 0)
