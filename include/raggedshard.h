@@ -221,6 +221,12 @@ int rs_group_zero(const rs_plan* plan, void* dbuf, void* stream);
  * base 16-byte aligned); out: device, S fp32, 16-byte aligned. */
 int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride,
               float* out, void* stream);
+/* The same mean over `rows` partials (1 <= rows <= 2^24) instead of `world`: the arithmetic one rank
+ * performs in the 2-D gradient reduction of an N-D DBuffer (Section 5: ReduceScatter along one
+ * mesh dimension, AllReduce along the other), where a region receives world * replicas
+ * contributions, or one per replica in the second step.  rs_reduce is rows == world. */
+int rs_reduce_rows(const rs_plan* plan, int rank, const void* partials, int rows, int64_t row_stride,
+                   float* out, void* stream);
 
 /* ---- block_quant: communication-free block-wise FP8 of the local shard (Sections 2.1, 4) ----
  * Per block: amax = max|x|, scale = amax/448 (fp32), code = E4M3 RNE of clamp(x/scale, +-448);

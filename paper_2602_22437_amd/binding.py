@@ -28,6 +28,7 @@ EXPORTS = [
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
     "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize",
+    "rs_reduce_rows",
 ]
 
 
@@ -100,6 +101,7 @@ _lib.rs_group_add.argtypes = [_P, _P, C.c_float, _P, _P]
 _lib.rs_group_scale.argtypes = [_P, C.c_float, _P, _P]
 _lib.rs_group_zero.argtypes = [_P, _P, _P]
 _lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
+_lib.rs_reduce_rows.argtypes = [_P, C.c_int, _P, C.c_int, C.c_int64, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_reduce_quantize.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
@@ -341,6 +343,11 @@ def rs_group_zero(plan, dbuf, stream=None) -> None:
 def rs_reduce(plan, rank: int, partials, row_stride: int, out, stream=None) -> None:
     _check(_lib.rs_reduce(plan, int(rank), _ptr(partials), int(row_stride), _ptr(out), _stream(stream)),
            "rs_reduce")
+
+
+def rs_reduce_rows(plan, rank: int, partials, rows: int, row_stride: int, out, stream=None) -> None:
+    _check(_lib.rs_reduce_rows(plan, int(rank), _ptr(partials), int(rows), int(row_stride), _ptr(out),
+                               _stream(stream)), "rs_reduce_rows")
 
 
 def rs_quantize(plan, rank: int, shard, codes, scales, stream=None) -> None:

@@ -135,7 +135,7 @@ void finish_plan(rs_plan* p, const std::vector<int64_t>& starts) {
 
 extern "C" {
 
-int rs_version(void) { return 140; }
+int rs_version(void) { return 150; }
 
 const char* rs_strerror(int code) {
   switch (code) {
@@ -490,15 +490,22 @@ int rs_group_zero(const rs_plan* plan, void* dbuf, void* stream) {
   return rs::launch_fill_zero(dbuf, plan->S * plan->world * 2, static_cast<hipStream_t>(stream));
 }
 
-int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride, float* out,
-              void* stream) {
+int rs_reduce_rows(const rs_plan* plan, int rank, const void* partials, int rows, int64_t row_stride,
+                   float* out, void* stream) {
   const int rc = check_device(plan);
   if (rc != RS_OK) return rc;
-  if (!partials || !out || rank < 0 || rank >= plan->world || row_stride < plan->S) return RS_EINVAL;
+  if (!partials || !out || rank < 0 || rank >= plan->world || rows < 1 || rows > (1 << 24) ||
+      row_stride < plan->S)
+    return RS_EINVAL;
   if (!aligned16(partials) || !aligned16(out) || row_stride % 8 != 0) return RS_EALIGN;
   return rs::launch_shard_reduce(plan->dev, int(plan->t.size()), partials, row_stride, out, plan->S,
-                                 plan->host.granules_per_rank, rank, int(plan->world),
+                                 plan->host.granules_per_rank, rank, rows,
                                  static_cast<hipStream_t>(stream));
+}
+
+int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride, float* out,
+              void* stream) {
+  return rs_reduce_rows(plan, rank, partials, plan ? int(plan->world) : 0, row_stride, out, stream);
 }
 
 int rs_quantize(const rs_plan* plan, int rank, const void* shard, uint8_t* codes, float* scales,

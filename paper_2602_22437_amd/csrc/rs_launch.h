@@ -14,7 +14,7 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
                     int64_t n_padding_gran, hipStream_t st);
 int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st);
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
-                        float* out, int64_t S, int64_t gpr, int rank, int world, hipStream_t st);
+                        float* out, int64_t S, int64_t gpr, int rank, int rows, hipStream_t st);
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
                        uint8_t* codes, float* scales, void* const* batch, int batch_count,
                        int64_t elem_base, int64_t scale_off, hipStream_t st);

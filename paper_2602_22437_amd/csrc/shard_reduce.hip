@@ -73,14 +73,14 @@ __global__ __launch_bounds__(kReduceThreads) void shard_reduce_kernel(
 // launcher (host)
 // -------------------------------------------------------------------------------------------
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
-                        float* out, int64_t S, int64_t gpr, int rank, int world, hipStream_t st) {
+                        float* out, int64_t S, int64_t gpr, int rank, int rows, hipStream_t st) {
   if (gpr <= 0 || gpr > 0x7fffffffLL) return RS_EOVERFLOW;
-  const float inv_w = 1.0f / float(world);
+  const float inv_w = 1.0f / float(rows);
   const uint16_t* P = static_cast<const uint16_t*>(partials);
   const dim3 g256{unsigned(xcd_grid(gpr))}, g512{unsigned(xcd_grid((gpr + 1) / 2))};
 #define RS_REDUCE(THREADS, DOUBLE, GRID)                                                         \
   shard_reduce_kernel<THREADS, DOUBLE><<<GRID, dim3(THREADS), 0, st>>>(                         \
-      dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, world, inv_w)
+      dev.tensors, n, dev.gran_first, P, row_stride, out, S, gpr, rank, rows, inv_w)
   if (gpr >= 4096)
     RS_REDUCE(512, true, g512);
   else

@@ -54,7 +54,10 @@ def check_reduce(u: Unit, rank, partial_bits, label, poison_padding=True):
     say(f"reduce {label}: rank={rank} W={W} S={S}")
     dev = to_dev_bf16(partial_bits.reshape(-1))
     out = torch.full((S,), float("nan"), dtype=torch.float32, device="cuda")
-    B.rs_reduce(u.plan, rank, dev, S, out)
+    if W == u.world:
+        B.rs_reduce(u.plan, rank, dev, S, out)
+    else:
+        B.rs_reduce_rows(u.plan, rank, dev, W, S, out)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     want = OD.shard_reduce(partial_bits, segs)
@@ -373,6 +376,23 @@ def test_reduce_world_sizes_and_special_cases(W):
             segs = u.oracle.rank_segments(rank)
             for _, _, d, n in segs:
                 assert np.array_equal(got[d:d + n], OD.bf16_bits_to_f32(parts[0, d:d + n]))
+    finally:
+        u.close()
+
+
+@pytest.mark.parametrize("rows", [1, 3, 12, 200])
+def test_reduce_over_a_row_count_other_than_the_world_size(rows):
+    """The 2-D gradient reduction of an N-D buffer: a region of a 4-rank plan receives one
+    partial per (rank, replica) pair, or one per replica."""
+    wl = WORKLOADS[1]
+    u = Unit.from_workload(wl)
+    try:
+        for k in (0, wl.world - 1):
+            parts = np.stack([normal_bf16(33, rows, k, w, u.S, 1e-3) for w in range(rows)])
+            check_reduce(u, k, parts, f"rows={rows}")
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_reduce_rows(u.plan, 0, torch.zeros(8, device="cuda"), 0, u.S, torch.zeros(8, device="cuda"))
+        assert e.value.code == B.RS_EINVAL
     finally:
         u.close()
 
