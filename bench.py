@@ -425,6 +425,9 @@ def main():
     cp_ms = timed(lambda i=0: B.rs_copy_probe(probe_dst[i % units], U[i % units]["dbuf"], nbytes, stream),
                   max(units, 8))
     copy_gbps = 2 * nbytes / cp_ms / 1e6
+    # the runtime's own device-to-device copy of the same buffers, as a second reference
+    rt_ms = timed(lambda i=0: probe_dst[i % units].copy_(U[i % units]["dbuf"]), max(units, 8))
+    runtime_copy_gbps = 2 * nbytes / rt_ms / 1e6
 
     dom = max(per_unit_names, key=lambda n: kern_ms[n])
     roof = {
@@ -432,7 +435,7 @@ def main():
         "unit": "GB/s", "frac": round(kernels[dom]["GBps"] / HBM_PEAK_GBPS, 4),
         "traffic": PMC_TRAFFIC_CONFIG2.get(dom) if wl.index == 2 else None,
         "avg_launch_ms": kernels[dom]["ms"], "algorithmic_bytes_per_launch": per_unit[dom],
-        "plain_copy_GBps": round(copy_gbps, 1),
+        "plain_copy_GBps": round(copy_gbps, 1), "runtime_dtod_copy_GBps": round(runtime_copy_gbps, 1),
     }
     result = {
         "metric": "HBM GB/s & % of peak: ragged_pack, shard_reduce, FP8 block_quant, unpack",
