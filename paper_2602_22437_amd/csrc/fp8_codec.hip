@@ -265,15 +265,16 @@ constexpr int kDequantThreads = 64;
 // kF32: the tensors are fp32 (value * scale, no further rounding) instead of bf16
 template <bool kF32>
 __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
-    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
-    const int32_t* __restrict__ granules, const uint8_t* __restrict__ codes,
+    const TensorDev* __restrict__ T, int n, const GranRef* __restrict__ granules,
+    const uint8_t* __restrict__ codes,
     const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr) {
-  const int64_t gid = granules[blockIdx.x];
+  const GranRef ref = granules[blockIdx.x];   // one 8-byte read: the granule and its first tensor
+  const int64_t gid = ref.gid;
   const int64_t k = gid / gpr;
   const int64_t i0 = (gid - k * gpr) * kGranule;
   const int64_t d0 = k * S + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
-  const int t0 = gran_first[gid];  // a payload granule: t0 < n
+  const int t0 = ref.first;  // a payload granule: t0 < n
   // A lane converts kGroup codes per access so that its store is one 16-byte vector and a
   // wavefront's stores are contiguous: 8 codes -> 8 bf16, or 4 codes -> 4 fp32.
   constexpr int kGroup = kF32 ? 4 : 8;
@@ -388,10 +389,10 @@ int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t 
   if (n_payload_gran < 0 || n_payload_gran > 0x7fffffffLL) return RS_EOVERFLOW;
   const dim3 g{unsigned(n_payload_gran)}, b{unsigned(kDequantThreads)};
   if (f32_out)
-    dequant_unpack_kernel<true><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,
+    dequant_unpack_kernel<true><<<g, b, 0, st>>>(dev.tensors, n, dev.payload_gran,
                                                  codes, scales, ptrs, S, gpr);
   else
-    dequant_unpack_kernel<false><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,
+    dequant_unpack_kernel<false><<<g, b, 0, st>>>(dev.tensors, n, dev.payload_gran,
                                                   codes, scales, ptrs, S, gpr);
   return launched();
 }

@@ -3,8 +3,8 @@
 // Common shape of the streaming kernels: one 16-byte vector per lane per access and a very large
 // grid (a plain copy on MI355X is fastest that way: no grid-stride loop, no multi-vector tiles),
 // single-wavefront workgroups for copies (measured 3-4 % faster than 256 lanes), non-temporal
-// loads/stores since nothing is reused, and one scalar table lookup per workgroup to find its
-// tensor.  No MFMA: nothing here is a contraction.
+// loads/stores since nothing is reused, and one 8-byte table read per workgroup to find its
+// granule and its tensor.  No MFMA: nothing here is a contraction.
 #include "device_util.h"
 
 namespace rs {
@@ -38,8 +38,8 @@ __device__ __forceinline__ u32x4 axpy8(u32x4 d, u32x4 s, float alpha) {
 
 template <int kOp>
 __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
-    const TensorDev* __restrict__ T, int n, const int32_t* __restrict__ gran_first,
-    const int32_t* __restrict__ granules, const int32_t* __restrict__ padding,
+    const TensorDev* __restrict__ T, int n, const GranRef* __restrict__ granules,
+    const int32_t* __restrict__ padding,
     unsigned n_copy_groups, void* const* __restrict__ ptrs, uint16_t* __restrict__ dbuf, int64_t S,
     int64_t gpr, int64_t region_stride, float alpha) {
   constexpr bool kFillsPadding = kOp == kGroupPack || kOp == kGroupPackScaled;
@@ -59,7 +59,8 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
     return;
   }
   const unsigned slot = blockIdx.x / kCopyParts, part = blockIdx.x % kCopyParts;
-  const int64_t bid = granules[slot];
+  const GranRef ref = granules[slot];   // one 8-byte read: the granule and its first tensor
+  const int64_t bid = ref.gid;
   const int64_t k = bid / gpr;
   const int64_t i0 = (bid - k * gpr) * kGranule;
   const int64_t d0 = k * S + i0;
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
   const int64_t d = d0 + lane_off;          // logical buffer position: what the tables speak of
   // where it lives: rank regions are region_stride elements apart (S in a plain DBuffer)
   uint16_t* const at = dbuf + k * region_stride + i0 + lane_off;
-  const int t0 = gran_first[bid];
+  const int t0 = ref.first;
 
   bool empty = t0 >= n;
   if (!empty) {
@@ -178,9 +179,9 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
   if (grid < 0 || grid > 0x7fffffffLL) return RS_EOVERFLOW;
   const dim3 g{unsigned(grid)}, b{unsigned(kCopyThreads)};
 #define RS_GROUP_OP(OP)                                                                         \
-  group_op_kernel<OP><<<g, b, 0, st>>>(dev.tensors, n, dev.gran_first, dev.payload_gran,       \
-                                       dev.padding_gran, unsigned(copy_groups), ptrs, db, S,   \
-                                       gpr, region_stride, alpha)
+  group_op_kernel<OP><<<g, b, 0, st>>>(dev.tensors, n, dev.payload_gran, dev.padding_gran,     \
+                                       unsigned(copy_groups), ptrs, db, S, gpr, region_stride, \
+                                       alpha)
   switch (op) {
     case kGroupPack: RS_GROUP_OP(kGroupPack); break;
     case kGroupUnpack: RS_GROUP_OP(kGroupUnpack); break;

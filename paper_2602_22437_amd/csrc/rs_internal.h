@@ -53,6 +53,13 @@ struct Item {
                    //              count = column strip / runs in this item (<= kStateRuns)
 };
 
+// A granule that holds payload, with the first tensor that ends after its start: what a copy
+// workgroup needs to find its work in one table read (8 bytes).
+struct GranRef {
+  int32_t gid;    // rank * granules_per_rank + index within the rank
+  int32_t first;  // gran_first[gid]
+};
+
 struct TensorHost {
   int64_t rows, cols;  // as described by the caller (cols == 0: 1-D)
   int32_t mode;
@@ -75,7 +82,7 @@ struct HostTables {
   std::vector<int64_t> item_begin;   // world + 1
   // granules that hold at least one payload element (ids = rank * granules_per_rank + index):
   // the unpack kernels launch workgroups for these only and never visit pure padding
-  std::vector<int32_t> payload_gran;
+  std::vector<GranRef> payload_gran;
   std::vector<int32_t> padding_gran;   // the rest: granules ragged_pack only has to zero
   int64_t n_payload_gran = 0, n_padding_gran = 0;
   std::vector<Item> state_items;            // rank-major; empty unless every tensor has state blocks
@@ -87,7 +94,7 @@ struct DeviceTables {
   TensorDev* tensors = nullptr;
   int32_t* gran_first = nullptr;
   Item* items = nullptr;
-  int32_t* payload_gran = nullptr;
+  GranRef* payload_gran = nullptr;
   int32_t* padding_gran = nullptr;
   Item* state_items = nullptr;
 };

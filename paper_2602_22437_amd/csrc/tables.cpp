@@ -74,7 +74,7 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
         out->padding_gran.push_back(int32_t(k * gpr + j));
         continue;
       }
-      out->payload_gran.push_back(int32_t(k * gpr + j));
+      out->payload_gran.push_back(GranRef{int32_t(k * gpr + j), f});
     }
   }
   out->n_payload_gran = int64_t(out->payload_gran.size());
