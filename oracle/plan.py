@@ -27,6 +27,8 @@ Readings taken where the paper is silent (listed again in the design notes):
     [1, ceil(total/g)], as the text prescribes ("binary-search"); it is exact where
     feasibility is monotone over multiples of g and otherwise returns some feasible S.
   * g_coll alone is tried as a unit before the first block size (it can only lower S*).
+  * The listing forms its units from the ascending block sizes, the text from prefixes of the
+    tensors sorted by element count; both families are searched (candidate_units).
 """
 from __future__ import annotations
 
@@ -196,12 +198,23 @@ def dp_segments(tensors: Sequence[Tuple[int, int]], offsets: Sequence[int], S: i
 # --------------------------------------------------------------------------------------
 
 def candidate_units(tensors: Sequence[Tuple[int, int]], g_coll: int) -> List[int]:
-    """g_coll, then the running LCM over the distinct block sizes in ascending order."""
+    """The units whose multiples are searched.  Algorithm 1's listing and the text around it
+    describe two different families; both are taken (every result passes CheckValidShard, so
+    more candidates can only lower S*):
+      * the listing: g_coll, then the running LCM over the distinct block sizes, ascending;
+      * the text: the tensors that can contain a whole shard are the largest ones, so the
+        running LCM (from g_coll) over the block sizes of the tensors sorted by element count,
+        largest first (equal counts keep the list order) - one unit per prefix."""
     units = [g_coll]
     g = g_coll
     for gp in sorted({g_t for _, g_t in tensors}):
         g = lcm(g, gp)
-        if g != units[-1]:
+        if g not in units:
+            units.append(g)
+    g = g_coll
+    for _, gp in sorted(tensors, key=lambda eg: -eg[0]):     # sorted() is stable
+        g = lcm(g, gp)
+        if g not in units:
             units.append(g)
     return units
 
@@ -230,7 +243,7 @@ def plan_shard_size(tensors: Sequence[Tuple[int, int]], m: int, g_coll: int, A: 
     best = None
     for c in candidate_units(tensors, g_coll):
         if c > cap:
-            break
+            continue
         s = min_feasible_multiple(tensors, m, c, A, start)
         if best is None or s < best:
             best = s

@@ -163,8 +163,12 @@ void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int3
   }
 }
 
-// Outer loop of Algorithm 1: unit g <- g_coll, then g <- lcm(g, g') over the ascending distinct
-// block sizes; per unit the smallest feasible multiple by lower-bound bisection; S* = minimum.
+// Outer loop of Algorithm 1: per candidate unit the smallest feasible multiple by lower-bound
+// bisection; S* = the minimum.  Two families of units, both starting from g_coll: the listing's
+// running LCM over the ascending distinct block sizes, and the text's running LCM over the block
+// sizes of the tensors sorted by element count, largest first (the tensors that can contain a
+// whole shard), one unit per prefix.  Every candidate S passes the exact check, so the second
+// family can only lower S*.
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
                      int64_t* S_out) {
   i128 total = 0;
@@ -174,18 +178,28 @@ int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_
   // can only tie or lose.
   const int64_t one_shard = round_up(int64_t(total), g_coll);
 
+  std::vector<int64_t> units{g_coll};
+  auto add_family = [&](const std::vector<int64_t>& block_sizes) {
+    i128 unit = g_coll;
+    for (int64_t g : block_sizes) {
+      unit = unit / gcd64(int64_t(unit), g) * g;
+      if (unit > one_shard) break;   // the running LCM only grows
+      if (std::find(units.begin(), units.end(), int64_t(unit)) == units.end())
+        units.push_back(int64_t(unit));
+    }
+  };
   std::vector<int64_t> sizes;
   for (const TensorHost& h : t) sizes.push_back(h.g);
   std::sort(sizes.begin(), sizes.end());
   sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
-
-  std::vector<int64_t> units{g_coll};
-  i128 unit = g_coll;
-  for (int64_t g : sizes) {
-    unit = unit / gcd64(int64_t(unit), g) * g;
-    if (unit > one_shard) break;
-    if (int64_t(unit) != units.back()) units.push_back(int64_t(unit));
-  }
+  add_family(sizes);
+  std::vector<size_t> by_count(t.size());
+  for (size_t i = 0; i < t.size(); ++i) by_count[i] = i;
+  std::stable_sort(by_count.begin(), by_count.end(),
+                   [&](size_t a, size_t b) { return t[a].e > t[b].e; });
+  sizes.clear();
+  for (size_t i : by_count) sizes.push_back(t[i].g);
+  add_family(sizes);
 
   int64_t best = -1;
   for (int64_t c : units) {

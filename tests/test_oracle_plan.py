@@ -99,9 +99,20 @@ def test_plan_is_feasible_and_never_beats_exhaustive_search():
         best = brute_min_S(tensors, m, g_coll, A, S)
         assert best is not None and best <= S
         gaps += best < S
-    # the bisection is a heuristic where feasibility is not monotone; it must still be
-    # exact most of the time on such small cases
-    assert gaps < 1500 * 0.25
+    # the bisection is a heuristic where feasibility is not monotone; with both families of
+    # candidate units (the listing's and the text's) it is exact on all of these small cases
+    assert gaps == 0
+
+
+def test_by_count_prefix_units_find_what_the_ascending_block_sizes_miss():
+    """Two tensors, 6 devices: the unit 8 = lcm(g_coll, g of the largest tensor) is a prefix of
+    the by-element-count order but not of the ascending block sizes (4, 12, 24); only it finds
+    S = 8, which an exhaustive scan confirms as the minimum."""
+    tensors, m, g_coll, A = [(40, 8), (6, 3)], 6, 4, 2
+    assert P.candidate_units(tensors, g_coll) == [4, 12, 24, 8]
+    assert P.plan_shard_size(tensors, m, g_coll, A) == 8
+    assert brute_min_S(tensors, m, g_coll, A, 48) == 8
+    assert P.min_feasible_multiple(tensors, m, 4, A) == 24      # the bisection over multiples of 4 misses 8
 
 
 def test_greedy_layout_is_optimal_for_the_order():
