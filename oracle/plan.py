@@ -28,7 +28,8 @@ Readings taken where the paper is silent (listed again in the design notes):
     feasibility is monotone over multiples of g and otherwise returns some feasible S.
   * g_coll alone is tried as a unit before the first block size (it can only lower S*).
   * The listing forms its units from the ascending block sizes, the text from prefixes of the
-    tensors sorted by element count; both families are searched (candidate_units).
+    tensors sorted by element count; both families are searched, and every single block size
+    on its own (candidate_units).
 """
 from __future__ import annotations
 
@@ -204,7 +205,9 @@ def candidate_units(tensors: Sequence[Tuple[int, int]], g_coll: int) -> List[int
       * the listing: g_coll, then the running LCM over the distinct block sizes, ascending;
       * the text: the tensors that can contain a whole shard are the largest ones, so the
         running LCM (from g_coll) over the block sizes of the tensors sorted by element count,
-        largest first (equal counts keep the list order) - one unit per prefix."""
+        largest first (equal counts keep the list order) - one unit per prefix;
+      * and, since the set of tensors that contain a whole shard may be neither kind of prefix,
+        the smallest such sets as well: lcm(g_coll, g) for every distinct block size on its own."""
     units = [g_coll]
     g = g_coll
     for gp in sorted({g_t for _, g_t in tensors}):
@@ -214,6 +217,10 @@ def candidate_units(tensors: Sequence[Tuple[int, int]], g_coll: int) -> List[int
     g = g_coll
     for _, gp in sorted(tensors, key=lambda eg: -eg[0]):     # sorted() is stable
         g = lcm(g, gp)
+        if g not in units:
+            units.append(g)
+    for gp in sorted({g_t for _, g_t in tensors}):
+        g = lcm(g_coll, gp)
         if g not in units:
             units.append(g)
     return units

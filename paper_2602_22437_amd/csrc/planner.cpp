@@ -164,11 +164,11 @@ void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int3
 }
 
 // Outer loop of Algorithm 1: per candidate unit the smallest feasible multiple by lower-bound
-// bisection; S* = the minimum.  Two families of units, both starting from g_coll: the listing's
+// bisection; S* = the minimum.  Three families of units, all starting from g_coll: the listing's
 // running LCM over the ascending distinct block sizes, and the text's running LCM over the block
 // sizes of the tensors sorted by element count, largest first (the tensors that can contain a
-// whole shard), one unit per prefix.  Every candidate S passes the exact check, so the second
-// family can only lower S*.
+// whole shard), one unit per prefix; and every distinct block size on its own.  Every candidate
+// S passes the exact check, so more candidates can only lower S*.
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
                      int64_t* S_out) {
   i128 total = 0;
@@ -197,9 +197,12 @@ int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_
   for (size_t i = 0; i < t.size(); ++i) by_count[i] = i;
   std::stable_sort(by_count.begin(), by_count.end(),
                    [&](size_t a, size_t b) { return t[a].e > t[b].e; });
-  sizes.clear();
-  for (size_t i : by_count) sizes.push_back(t[i].g);
-  add_family(sizes);
+  std::vector<int64_t> by_size;
+  for (size_t i : by_count) by_size.push_back(t[i].g);
+  add_family(by_size);
+  // the set of tensors that contain a whole shard may be neither kind of prefix: the smallest
+  // such sets as well, every distinct block size on its own
+  for (int64_t g : sizes) add_family(std::vector<int64_t>{g});
 
   int64_t best = -1;
   for (int64_t c : units) {

@@ -109,10 +109,21 @@ def test_by_count_prefix_units_find_what_the_ascending_block_sizes_miss():
     the by-element-count order but not of the ascending block sizes (4, 12, 24); only it finds
     S = 8, which an exhaustive scan confirms as the minimum."""
     tensors, m, g_coll, A = [(40, 8), (6, 3)], 6, 4, 2
-    assert P.candidate_units(tensors, g_coll) == [4, 12, 24, 8]
+    assert P.candidate_units(tensors, g_coll) == [4, 12, 24, 8]      # 8 first appears as a by-count prefix
     assert P.plan_shard_size(tensors, m, g_coll, A) == 8
     assert brute_min_S(tensors, m, g_coll, A, 48) == 8
     assert P.min_feasible_multiple(tensors, m, 4, A) == 24      # the bisection over multiples of 4 misses 8
+
+
+def test_single_block_size_units_find_what_both_prefix_families_miss():
+    """Only the second-largest tensor contains a whole shard at the optimum, so its block size
+    alone (200) is the unit that finds S = 4400; an exhaustive scan confirms the minimum."""
+    tensors = [(1255, 14), (352, 1024), (1536, 128), (6000, 200), (384, 8), (6792, 3072)]
+    m, g_coll, A = 4, 8, 8
+    assert 200 in P.candidate_units(tensors, g_coll)
+    assert P.plan_shard_size(tensors, m, g_coll, A) == 4400
+    for S in range(g_coll, 4400, g_coll):
+        assert not P.check_valid_shard(tensors, m, S, A, P.smallest_start_scan if S < 600 else P.smallest_start)
 
 
 def test_greedy_layout_is_optimal_for_the_order():
