@@ -119,8 +119,8 @@ int rs_plan_create_rooted(const rs_tensor_desc* descs, int n, int world, int ali
                           rs_plan** out);
 void rs_plan_destroy(rs_plan* plan);
 
-/* SelectRoot of Algorithm 2 (distributed Muon, Section 6.3), which the paper leaves at "load
- * balancing": longest-processing-time-first.  2-D tensors in descending cost (equal costs in
+/* SelectRoot of Algorithm 2 (distributed Muon, Section 6.3), of which the paper says only that
+ * it balances load: longest-processing-time-first.  2-D tensors in descending cost (equal costs in
  * index order) each go to the device with the least accumulated cost, the lowest such device.
  * Cost of an R x C matrix = one quintic Newton-Schulz iteration, a*a*(2b + a) with
  * a = min(R, C), b = max(R, C).  roots (host, n values) receives the device, -1 for 1-D

@@ -3,17 +3,17 @@ imported by the product.
 
 Three small host-side pieces, each written out from its definition:
 
-  * shard_dim_granularity: composing RaggedShard with an even Shard(dim > 0) (Section 4,
-    "Composing with existing sharding formats", case (ii)): the ragged granularity is made the
+  * shard_dim_granularity: composing RaggedShard with an even Shard(dim > 0) (Section 4, the
+    paragraph on composing with existing sharding formats, its second case): the granularity is the
     least common multiple of a stride of the tensor and the user's granularity so that a ragged
     boundary never falls inside dimension `dim`.
-  * select_roots: SelectRoot of Algorithm 2 (distributed Muon, Section 6.3), which the paper
-    describes only as "load balancing".
+  * select_roots: SelectRoot of Algorithm 2 (distributed Muon, Section 6.3), of which the paper
+    says only that it balances load.
   * rooted_plan: the DBuffer of a group of tensors placed RaggedShard(r_t): all blocks of tensor
     t on device r_t (Section 4: arbitrary sharding distribution; Algorithm 2's redistribute target).
 
 Readings taken where the paper is silent:
-  * "Never cuts into dimension dim" is read as: every ragged boundary, counted in elements of the
+  * Keeping dimension dim whole is read as: every ragged boundary, counted in elements of the
     row-major local tensor, has all coordinates along dimensions >= dim equal to zero.  Those
     offsets are the multiples of prod(shape[dim:]) (the stride of dimension dim - 1), so
     g = lcm(prod(shape[dim:]), g_user).
