@@ -445,6 +445,21 @@ def test_device_argument_errors():
         with pytest.raises(B.RaggedShardError) as e:
             B.rs_pack(w.plan, tab, x)                           # table made for another plan
         assert e.value.code == B.RS_EINVAL
+        # the fused reduce + quantise checks what both of its halves check
+        sc, mean = torch.zeros(8, device="cuda"), torch.zeros(u.S + 4, device="cuda")
+        ucodes = torch.zeros(u.S, dtype=torch.uint8, device="cuda")
+        for args, code in [((u.plan, 2, x, u.S, ucodes, sc), B.RS_EINVAL),             # rank out of range
+                           ((u.plan, 0, x, u.S - 8, ucodes, sc), B.RS_EINVAL),         # rows overlap
+                           ((u.plan, 0, x, u.S + 3, ucodes, sc), B.RS_EALIGN),         # row stride
+                           ((u.plan, 0, x[1:], u.S, ucodes, sc), B.RS_EALIGN),         # partials
+                           ((u.plan, 0, x, u.S, ucodes, sc, mean[1:]), B.RS_EALIGN),   # mean buffer
+                           ((w.plan, 0, x, w.S, codes, sc), B.RS_EUNSUPPORTED)]:       # no FP8 blocks
+            with pytest.raises(B.RaggedShardError) as e:
+                B.rs_reduce_quantize(*args)
+            assert e.value.code == code, args[1:4]
+        with pytest.raises(B.RaggedShardError) as e:
+            B.rs_reduce_rows(u.plan, 0, x, 1 << 25, u.S, torch.zeros(u.S, device="cuda"))
+        assert e.value.code == B.RS_EINVAL
     finally:
         u.close()
         w.close()
