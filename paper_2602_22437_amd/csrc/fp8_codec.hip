@@ -268,13 +268,17 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
     const TensorDev* __restrict__ T, int n, const GranRef* __restrict__ granules,
     const uint8_t* __restrict__ codes,
     const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr) {
-  const GranRef ref = granules[blockIdx.x];   // one 8-byte read: the granule and its first tensor
-  const int64_t gid = ref.gid;
-  const int64_t k = gid / gpr;
-  const int64_t i0 = (gid - k * gpr) * kGranule;
+  // one 8-byte read: the granule and its first tensor (a payload granule: t0 < n)
+  const long long packed = reinterpret_cast<const long long*>(granules)[blockIdx.x];
+  const int t0 = int32_t(packed >> 32);
+  // the tensor's record and base pointer are requested at once, ahead of the index arithmetic
+  const TensorDev t = T[t0];
+  void* const tensor = ptrs[t0];
+  const unsigned gid = unsigned(packed);             // granule ids and gpr fit 31 bits
+  const unsigned k = gid / unsigned(gpr);
+  const int64_t i0 = int64_t(gid - k * unsigned(gpr)) * kGranule;
   const int64_t d0 = k * S + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
-  const int t0 = ref.first;  // a payload granule: t0 < n
   // A lane converts kGroup codes per access so that its store is one 16-byte vector and a
   // wavefront's stores are contiguous: 8 codes -> 8 bf16, or 4 codes -> 4 fp32.
   constexpr int kGroup = kF32 ? 4 : 8;
@@ -283,12 +287,13 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
   const int lane = threadIdx.x * kGroup;
 
   {
-    const TensorDev t = T[t0];
-    uint16_t* out = reinterpret_cast<uint16_t*>(ptrs[t0]);
-    float* out32 = reinterpret_cast<float*>(ptrs[t0]);
-    const bool inside = t.ell <= d0 && d0 + len <= t.ell + t.e;
-    if (inside && (t.flags & kFlagVec) && (reinterpret_cast<uintptr_t>(out) & 15) == 0 &&
-        t.cols < (int64_t(1) << 30)) {
+    uint16_t* out = reinterpret_cast<uint16_t*>(tensor);
+    float* out32 = reinterpret_cast<float*>(tensor);
+    // one round of table reads, one branch
+    const bool inside = (t.ell <= d0) & (d0 + len <= t.ell + t.e);
+    const bool structured = ((t.flags & kFlagVec) != 0) & ((reinterpret_cast<uintptr_t>(out) & 15) == 0) &
+                            (t.cols < (int64_t(1) << 30));
+    if (inside & structured) {
       // The whole granule lies in one tensor whose rows keep every 8-element group inside one
       // row and one block.  (row, col) of the granule's first element once per workgroup
       // (exact: a double holds any element index below 2^53), then 32-bit steps per lane.

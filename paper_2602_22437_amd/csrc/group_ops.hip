@@ -47,9 +47,9 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
   constexpr bool kUsesTensors = kOp != kGroupScale;
   if (kFillsPadding && blockIdx.x >= n_copy_groups) {
     // a granule of nothing but padding: this wavefront zeroes all of it
-    const int64_t gid = padding[blockIdx.x - n_copy_groups];
-    const int64_t k = gid / gpr;
-    const int64_t i0 = (gid - k * gpr) * kGranule;
+    const unsigned gid = unsigned(padding[blockIdx.x - n_copy_groups]);
+    const unsigned k = gid / unsigned(gpr);
+    const int64_t i0 = int64_t(gid - k * unsigned(gpr)) * kGranule;
     const int len = int(min(int64_t(kGranule), S - i0));
 #pragma unroll
     for (int h = 0; h < kCopyParts; ++h) {
@@ -59,10 +59,17 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
     return;
   }
   const unsigned slot = blockIdx.x / kCopyParts, part = blockIdx.x % kCopyParts;
-  const GranRef ref = granules[slot];   // one 8-byte read: the granule and its first tensor
-  const int64_t bid = ref.gid;
-  const int64_t k = bid / gpr;
-  const int64_t i0 = (bid - k * gpr) * kGranule;
+  // one 8-byte read: the granule and its first tensor (a payload granule: t0 < n and tensor t0
+  // starts before the granule ends)
+  const long long packed = reinterpret_cast<const long long*>(granules)[slot];
+  const int t0 = int32_t(packed >> 32);
+  // Everything the common case needs is requested at once, ahead of the index arithmetic (one
+  // round of table reads, one branch): the tensor's interval and its base pointer.
+  const int64_t ell = T[t0].ell, end = ell + T[t0].e;
+  uint16_t* const tensor = kUsesTensors ? reinterpret_cast<uint16_t*>(ptrs[t0]) : nullptr;
+  const unsigned bid = unsigned(packed);             // granule ids and gpr fit 31 bits
+  const unsigned k = bid / unsigned(gpr);
+  const int64_t i0 = int64_t(bid - k * unsigned(gpr)) * kGranule;
   const int64_t d0 = k * S + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
   const int lane_off = (int(part) * kCopyThreads + int(threadIdx.x)) * 8;
@@ -70,34 +77,21 @@ __global__ __launch_bounds__(kCopyThreads) void group_op_kernel(
   const int64_t d = d0 + lane_off;          // logical buffer position: what the tables speak of
   // where it lives: rank regions are region_stride elements apart (S in a plain DBuffer)
   uint16_t* const at = dbuf + k * region_stride + i0 + lane_off;
-  const int t0 = ref.first;
-
-  bool empty = t0 >= n;
-  if (!empty) {
-    const int64_t ell = T[t0].ell, end = ell + T[t0].e;
-    if (ell <= d0 && d0 + len <= end) {
-      // the whole granule lies inside tensor t0 (the common case by far)
-      if (!kUsesTensors) {
-        st16(at, scale8(ld16(at), alpha));
-        return;
-      }
-      uint16_t* base = reinterpret_cast<uint16_t*>(ptrs[t0]) + (d0 - ell);
-      if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
-        if (kOp == kGroupUnpack)
-          st16(base + lane_off, ld16(at));
-        else if (kOp == kGroupPack)
-          st16(at, ld16(base + lane_off));
-        else if (kOp == kGroupPackScaled)
-          st16(at, scale8(ld16(base + lane_off), alpha));
-        else
-          st16(at, axpy8(ld16(at), ld16(base + lane_off), alpha));
-        return;
-      }
-    }
-    empty = ell >= d0 + len;
-  }
-  if (empty) {  // nothing but padding here
-    if (kFillsPadding) st16(at, u32x4{0, 0, 0, 0});
+  uint16_t* const base = kUsesTensors ? tensor + (d0 - ell) : nullptr;
+  const bool inside = (ell <= d0) & (d0 + len <= end);
+  const bool usable = !kUsesTensors | ((reinterpret_cast<uintptr_t>(base) & 15) == 0);
+  if (inside & usable) {
+    // the whole granule lies inside tensor t0 (the common case by far)
+    if (kOp == kGroupScale)
+      st16(at, scale8(ld16(at), alpha));
+    else if (kOp == kGroupUnpack)
+      st16(base + lane_off, ld16(at));
+    else if (kOp == kGroupPack)
+      st16(at, ld16(base + lane_off));
+    else if (kOp == kGroupPackScaled)
+      st16(at, scale8(ld16(base + lane_off), alpha));
+    else
+      st16(at, axpy8(ld16(at), ld16(base + lane_off), alpha));
     return;
   }
 

@@ -55,7 +55,7 @@ struct Item {
 
 // A granule that holds payload, with the first tensor that ends after its start: what a copy
 // workgroup needs to find its work in one table read (8 bytes).
-struct GranRef {
+struct alignas(8) GranRef {
   int32_t gid;    // rank * granules_per_rank + index within the rank
   int32_t first;  // gran_first[gid]
 };
