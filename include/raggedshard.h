@@ -93,10 +93,12 @@ const char* rs_strerror(int code);
  * Solves  min S  s.t. each tensor is one contiguous interval [l_t, l_t + e_t) of the
  * world*S-element buffer, intervals are disjoint, and every interior rank boundary k*S
  * that falls inside a tensor falls on a multiple of g_t from l_t  (Section 5, the
- * minimisation problem), by Algorithm 1 for the tensor order given: candidate units are
- * g_coll and the running LCM of the ascending distinct block sizes; for each unit the
- * smallest feasible multiple is found by bisection with CheckValidShard, which places each
- * tensor at its earliest feasible start.
+ * minimisation problem), by Algorithm 1 for the tensor order given: for each candidate unit
+ * the smallest feasible multiple is found by bisection with CheckValidShard, which places
+ * each tensor at its earliest feasible start; S is the smallest result.  Candidate units, all
+ * running LCMs that start from g_coll: over the ascending distinct block sizes (the listing);
+ * over the block sizes of the tensors sorted by element count, largest first (the text: the
+ * tensors that can contain a whole shard); and every distinct block size on its own.
  *   g_coll = align_bytes / min_itemsize elements (S is a multiple of it, so every rank
  *   region starts align_bytes-aligned for every dtype that shares the plan);
  *   tensor_align_elems = alignment of every l_t, must divide g_coll; 0 selects g_coll.
