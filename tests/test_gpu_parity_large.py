@@ -368,7 +368,8 @@ def test_moe_units_sampled(idx, cap):
         say(f"config {idx}: {len(u.specs)} tensors, W={wl.world}, S={u.S}, total={u.total}")
         src = device_params(wl, 10 + idx)
         pick = sample_tensors(u, wl, cap)
-        say(f"config {idx}: sampled tensors {pick}")
+        share = sum(u.specs[t].e for t in pick) / u.oracle.payload
+        say(f"config {idx}: sampled tensors {pick} ({100 * share:.1f} % of the unit's elements)")
         dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
         B.rs_pack(u.plan, u.table(src), dbuf)
         torch.cuda.synchronize()
@@ -417,5 +418,33 @@ def test_moe_units_sampled(idx, cap):
         torch.cuda.synchronize()
         assert not bool(torch.isnan(out).any())
         check_reduce_windows(u, wl, k, partials, out, reduce_windows(u, k, 12, 4096))
+
+        say(f"config {idx}: fused reduce + quantise of rank {k}")
+        c_f = torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda")
+        s_f = torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda")
+        mean = torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda")
+        B.rs_reduce_quantize(u.plan, k, partials, u.S, c_f, s_f, mean)
+        torch.cuda.synchronize()
+        assert torch.equal(mean.view(torch.int32), out.view(torch.int32)), "fused mean != rs_reduce"
+        assert not bool(torch.isnan(s_f[:hi - lo]).any())
+        # whole rows of tiles against the oracle: the first and the last of every tiled segment
+        rows_2d = partials.view(wl.world, u.S)
+        sb = u.oracle.scale_bases()
+        for t, src_off, dst_off, n in u.oracle.rank_segments(k):
+            spec = u.specs[t]
+            if spec.mode != OP.BLOCK_128x128:
+                continue
+            C, g = spec.cols, 128 * spec.cols
+            n_rows_of_tiles = -(-n // g)
+            for br in sorted({0, n_rows_of_tiles - 1}):
+                a, b = dst_off + br * g, min(dst_off + (br + 1) * g, dst_off + n)
+                say(f"config {idx}: oracle mean and codes of tensor {t}, row of tiles {src_off // g + br}")
+                win = rows_2d[:, a:b].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+                want_mean = OD.shard_reduce_f32_ordered(win, [(0, 0, 0, b - a)])
+                wc, ws = OF.quantise_matrix_f32(want_mean.reshape(-1, C), 128, 128)
+                assert np.array_equal(c_f[a:b].cpu().numpy(), wc.reshape(-1)), f"fused codes, tensor {t}"
+                s0 = sb[t] + (src_off // g + br) * spec.nbc - lo
+                assert np.array_equal(s_f[s0:s0 + spec.nbc].cpu().numpy().view(np.uint32),
+                                      ws.reshape(-1).view(np.uint32)), f"fused scales, tensor {t}"
     finally:
         u.close()
