@@ -323,3 +323,31 @@ def test_state_codec_feeds_the_adam_step():
         diff(am.cpu().numpy().view(np.uint32), oam.view(np.uint32), "m absmax")
     finally:
         u.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_adam8_random_units(seed):
+    """Random units of tensors that carry 8-bit state in every granularity, two steps on a few ranks."""
+    import random
+    rnd = random.Random(6000 + seed)
+    n = rnd.randint(1, 6)
+    tensors = []
+    for _ in range(n):
+        kind = rnd.random()
+        if kind < 0.25:
+            tensors.append((rnd.randint(1, 3000), 0, rnd.choice([MODE_1x128, MODE_32x32])))
+        elif kind < 0.65:
+            tensors.append((rnd.randint(1, 300), rnd.choice([8, 24, 30, 32, 40, 100, 128, 130, 256, 300, 1100]),
+                            rnd.choice([MODE_32x32, MODE_32x32, MODE_128x128])))
+        else:
+            tensors.append((rnd.randint(1, 90), rnd.choice([8, 40, 128, 200, 333]), MODE_1x128))
+    world = rnd.choice([1, 2, 3, 4, 7, 16])
+    A = rnd.choice([0, 0, 0, 1])
+    u = Unit(tensors, world, 16, 1, A)
+    try:
+        say(f"random unit {seed}: {tensors} W={world} A={A} S={u.S}")
+        assert B.rs_plan_state_bases(u.plan) == OA.state_bases(u.oracle)
+        for k in sorted(set(rnd.sample(range(world), min(world, 2)) + [0, world - 1])):
+            run_steps(u, k, 500 * seed + k, hypers(2), f"random{seed}")
+    finally:
+        u.close()

@@ -247,3 +247,35 @@ def test_strided_regions_of_a_2d_mesh(groups, gap):
                           P(0)) == B.RS_EALIGN
     finally:
         u.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_units_group_ops(seed):
+    """Random units (any block mode, odd pitches, element-aligned starts, reordered buffers)."""
+    import random
+    rnd = random.Random(7000 + seed)
+    n = rnd.randint(1, 7)
+    tensors = []
+    for _ in range(n):
+        kind = rnd.random()
+        if kind < 0.3:
+            tensors.append((rnd.randint(1, 3000), 0, MODE_1x128))
+        elif kind < 0.6:
+            tensors.append((rnd.randint(1, 400), rnd.choice([8, 24, 30, 128, 130, 136, 256, 1100]), MODE_128x128))
+        elif kind < 0.8:
+            tensors.append((rnd.randint(1, 60), rnd.choice([8, 40, 128, 333]), MODE_1x128))
+        else:
+            tensors.append((rnd.randint(1, 80), rnd.randint(1, 90), MODE_WHOLE))
+    world = rnd.choice([1, 2, 3, 5, 8, 16])
+    align, item = rnd.choice([(16, 1), (16, 2), (32, 2)])
+    A = rnd.choice([0, 0, 1, 4])
+    if A and (align // item) % A:
+        A = 0
+    u = Unit(tensors, world, align, item, A, order=rnd.choice([0, 1, 2, 3]))
+    try:
+        say(f"random unit {seed}: {tensors} W={world} align={align}/{item} A={A}")
+        params = [normal_bf16(32, seed, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        grads = [normal_bf16(32, seed, 1, i, s.e, 1e-3) for i, s in enumerate(u.specs)]
+        check_group_ops(u, params, grads, f"random{seed}")
+    finally:
+        u.close()

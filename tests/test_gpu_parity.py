@@ -751,3 +751,44 @@ def test_one_plan_serves_two_threads_on_two_streams():
                 assert torch.equal(got.view(torch.uint8), exp.view(torch.uint8)), f"thread {i} result differs"
     finally:
         u.close()
+
+
+def random_quantised_unit(rnd):
+    """A random unit of tensors that carry FP8 blocks: odd pitches, short tensors, partial tiles."""
+    n = rnd.randint(1, 7)
+    tensors = []
+    for _ in range(n):
+        kind = rnd.random()
+        if kind < 0.3:
+            tensors.append((rnd.randint(1, 3000), 0, MODE_1x128))
+        elif kind < 0.7:
+            tensors.append((rnd.randint(1, 400), rnd.choice([8, 24, 30, 128, 130, 136, 256, 100, 1100]), MODE_128x128))
+        else:
+            tensors.append((rnd.randint(1, 60), rnd.choice([8, 40, 128, 200, 333]), MODE_1x128))
+    world = rnd.choice([1, 2, 3, 4, 7, 8, 16, 33])
+    align, item = rnd.choice([(16, 1), (16, 2), (32, 1)])
+    A = rnd.choice([0, 0, 0, 1, 2, 8])
+    if A and (align // item) % A:
+        A = 0
+    return tensors, world, align, item, A
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_units_all_ops(seed):
+    import random
+    rnd = random.Random(9000 + seed)
+    tensors, world, align, item, A = random_quantised_unit(rnd)
+    u = Unit(tensors, world, align, item, A, order=rnd.choice([0, 0, 1, 2, 3]))
+    try:
+        say(f"random unit {seed}: {tensors} W={world} align={align}/{item} A={A} S={u.S}")
+        params = [normal_bf16(50, seed, 0, i, s.e, 0.02) for i, s in enumerate(u.specs)]
+        _, db_bits = check_pack_unpack(u, params, f"random{seed}")
+        ranks = sorted(set(rnd.sample(range(world), min(world, 3)) + [0, world - 1]))
+        for k in ranks:
+            parts = np.stack([normal_bf16(50, seed, 1, k * 64 + w, u.S, 1e-3) for w in range(world)])
+            check_reduce(u, k, parts, f"random{seed}")
+            check_reduce_quant(u, k, parts, f"random{seed}")
+        c, s, wc, ws = check_quant(u, db_bits, f"random{seed}", ranks)
+        check_dequant_unpack(u, c, s, wc, ws, f"random{seed}")
+    finally:
+        u.close()
