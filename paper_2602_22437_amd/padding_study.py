@@ -6,6 +6,7 @@ multiples costs least, and reports the padding overhead of the plan against the 
 sweep on synthetic units shaped like the two models the section uses.
 
     python -m paper_2602_22437_amd.padding_study [--model deepseek|gpt_oss|gpt_oss_fused] [--order 0..3]
+    python -m paper_2602_22437_amd.padding_study --pick 480 544        # the FSDP sizes of a range with least padding
 """
 from __future__ import annotations
 
@@ -59,12 +60,35 @@ def sweep(model: str, worlds: Sequence[int], granularities: Sequence[int] = (1, 
     return out
 
 
+def pick_world(model: str, lo: int, hi: int, rows_per_block: int,
+               order: int = B.RS_ORDER_DEFAULT) -> List[Tuple[float, int]]:
+    """The section's guideline as a tool: every FSDP size of [lo, hi] with its padding overhead,
+    least padding first (equal overheads: smaller size first)."""
+    unit = moe_unit(model, rows_per_block)
+    found = []
+    for w in range(lo, hi + 1):
+        plan = B.rs_plan_create_ordered(unit, w, 16, 2, 0, order)
+        found.append((B.rs_plan_padding_elems(plan) / B.rs_plan_payload_elems(plan), w))
+        B.rs_plan_destroy(plan)
+    return sorted(found)
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--model", default="deepseek", choices=["deepseek", "gpt_oss", "gpt_oss_fused"])
     ap.add_argument("--order", type=int, default=B.RS_ORDER_DEFAULT)
     ap.add_argument("--worlds", default="8,16,32,64,96,128,192,256,384,512,768,1024")
+    ap.add_argument("--pick", type=int, nargs=2, metavar=("LO", "HI"),
+                    help="rank the FSDP sizes of [LO, HI] by padding overhead instead of sweeping --worlds")
     args = ap.parse_args()
+    if args.pick:
+        lo, hi = args.pick
+        print(f"FSDP sizes {lo}..{hi} with the least padding, {args.model}-shaped MoE unit")
+        for g in (1, 16, 128):
+            ranked = pick_world(args.model, lo, hi, g, args.order)
+            print(f"{g:>4d}x rows: " + ", ".join(f"{w} ({100 * p:.2f}%)" for p, w in ranked[:5])
+                  + f"  ... worst {ranked[-1][1]} ({100 * ranked[-1][0]:.2f}%)")
+        return
     worlds = [int(x) for x in args.worlds.split(",")]
     res = sweep(args.model, worlds, order=args.order)
     print(f"padding overhead (padding / parameter elements), {args.model}-shaped MoE unit, bf16, 16-byte units")

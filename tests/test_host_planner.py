@@ -206,6 +206,17 @@ def test_padding_study_reproduces_the_papers_qualitative_claims():
         assert all(res[g][w][1] < 0.3 for g in res for w in worlds)
 
 
+def test_group_size_picker_finds_the_size_that_divides_the_experts():
+    """Section 6.4's guideline (simulate layouts offline, choose the FSDP size with the least
+    rounding loss): around 512 the DeepSeek-shaped unit of 257 experts fits 514 = 2 x 257 devices
+    without any padding at 128-row granularity, while 512 itself pays several per cent."""
+    from paper_2602_22437_amd import padding_study as PS
+    ranked = PS.pick_world("deepseek", 508, 516, 128)
+    assert ranked == sorted(ranked) and [w for _, w in ranked][0] == 514
+    assert ranked[0][0] < 1e-4
+    assert dict((w, p) for p, w in ranked)[512] > 0.03
+
+
 def test_state_block_layout_matches_oracle():
     """32-row granularity (Section 6.3) and the 8-bit state-block numbering: library == oracle on
     random units whose tensors all have state blocks; other units report RS_EUNSUPPORTED."""
