@@ -39,7 +39,8 @@ enum {
   RS_EALIGN = -4,        /* a device pointer or stride misses its required alignment */
   RS_EUNSUPPORTED = -5,  /* operation undefined for this plan (e.g. FP8 on whole-matrix blocks) */
   RS_EHIP = -6,          /* a HIP runtime call failed (no device, launch error) */
-  RS_ENOTUPLOADED = -7   /* device call before rs_plan_upload */
+  RS_ENOTUPLOADED = -7,  /* device call before rs_plan_upload */
+  RS_ETOOBIG = -8        /* more tensors than the fixed device array of rs_pack_noalloc holds */
 };
 
 /* Sharding granularity of one tensor (Section 4: the atomic non-shardable block).
@@ -178,6 +179,19 @@ void rs_tensor_table_destroy(rs_tensor_table* table);
  * dbuf[l_t + i] = src_t[i] for every tensor, every other element of dbuf[0, world*S) = +0.
  * src: table of bf16 device tensors; dbuf: device, world*S bf16, 16-byte aligned (RS_EALIGN). */
 int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* stream);
+
+/* rs_pack for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc, and callers whose source tensors move from call
+ * to call, for whom a table from rs_tensor_table_create would have to be made (and freed) every
+ * time.  Same result as rs_pack, bit for bit.  src_ptrs: HOST array of n device pointers (bf16
+ * tensors, element-aligned, none null), read before the call returns.  The pointers travel as
+ * kernel arguments into a fixed array of RS_NOALLOC_MAX_TENSORS pointers (32 KiB) that every GPU
+ * the library runs on holds until the process ends; the call enqueues ceil(n / 256) small staging
+ * kernels and the copy kernel on `stream` and calls no allocating routine.
+ * n > RS_NOALLOC_MAX_TENSORS: RS_ETOOBIG.  Every call on a GPU shares that GPU's array: calls that
+ * may overlap in time on one GPU (different streams or threads) race; calls on one stream are safe. */
+#define RS_NOALLOC_MAX_TENSORS 4096
+int rs_pack_noalloc(const rs_plan* plan, const void* const* src_ptrs, void* dbuf, void* stream);
 
 /* Inverse group copy: dst_t[i] = dbuf[l_t + i] (bf16 DBuffer -> per-tensor bf16). */
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream);

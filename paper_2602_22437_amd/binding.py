@@ -12,8 +12,9 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libraggedsh
 
 RS_BLOCK_1x128, RS_BLOCK_128x128, RS_BLOCK_WHOLE, RS_BLOCK_EXPLICIT, RS_BLOCK_32x32 = 0, 1, 2, 3, 4
 RS_ORDER_DEFAULT, RS_ORDER_BLOCK_SIZE, RS_ORDER_SHAPE, RS_ORDER_BEST = 0, 1, 2, 3
-RS_OK, RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM, RS_EALIGN, RS_EUNSUPPORTED, RS_EHIP, RS_ENOTUPLOADED = (
-    0, -1, -2, -3, -4, -5, -6, -7)
+RS_OK, RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM, RS_EALIGN, RS_EUNSUPPORTED, RS_EHIP, RS_ENOTUPLOADED, RS_ETOOBIG = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8)
+RS_NOALLOC_MAX_TENSORS = 4096
 
 EXPORTS = [
     "rs_version", "rs_strerror", "rs_plan_create", "rs_plan_destroy", "rs_check_valid_shard",
@@ -28,7 +29,7 @@ EXPORTS = [
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
     "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize",
-    "rs_reduce_rows",
+    "rs_reduce_rows", "rs_pack_noalloc",
 ]
 
 
@@ -94,6 +95,7 @@ _lib.rs_tensor_table_destroy.argtypes = [_P]
 _lib.rs_tensor_table_destroy.restype = None
 _lib.rs_pack.argtypes = [_P, _P, _P, _P]
 _lib.rs_unpack_bf16.argtypes = [_P, _P, _P, _P]
+_lib.rs_pack_noalloc.argtypes = [_P, C.POINTER(_P), _P, _P]
 _lib.rs_pack_strided.argtypes = [_P, _P, _P, C.c_int64, _P]
 _lib.rs_unpack_bf16_strided.argtypes = [_P, _P, C.c_int64, _P, _P]
 _lib.rs_pack_scaled.argtypes = [_P, _P, C.c_float, _P, _P]
@@ -309,6 +311,19 @@ def rs_tensor_table_destroy(table) -> None:
 
 def rs_pack(plan, src_table, dbuf, stream=None) -> None:
     _check(_lib.rs_pack(plan, src_table, _ptr(dbuf), _stream(stream)), "rs_pack")
+
+
+def rs_pack_noalloc(plan, src_tensors: Sequence, dbuf, stream=None) -> None:
+    """src_tensors: torch device tensors (contiguous) or raw device addresses, one per plan tensor."""
+    n = len(src_tensors)
+    if n != rs_plan_num_tensors(plan):
+        raise ValueError("one pointer per plan tensor is required")
+    arr = (_P * max(1, n))()
+    for i, t in enumerate(src_tensors):
+        if hasattr(t, "is_contiguous") and not t.is_contiguous():
+            raise ValueError("source tensors must be contiguous")
+        arr[i] = _ptr(t)
+    _check(_lib.rs_pack_noalloc(plan, arr, _ptr(dbuf), _stream(stream)), "rs_pack_noalloc")
 
 
 def rs_unpack_bf16(plan, dbuf, dst_table, stream=None) -> None:

@@ -135,7 +135,7 @@ void finish_plan(rs_plan* p, const std::vector<int64_t>& starts) {
 
 extern "C" {
 
-int rs_version(void) { return 150; }
+int rs_version(void) { return 160; }
 
 const char* rs_strerror(int code) {
   switch (code) {
@@ -147,6 +147,7 @@ const char* rs_strerror(int code) {
     case RS_EUNSUPPORTED: return "operation not supported for this plan";
     case RS_EHIP: return "HIP runtime error";
     case RS_ENOTUPLOADED: return "plan tables not uploaded to a device";
+    case RS_ETOOBIG: return "more tensors than the fixed device array of rs_pack_noalloc holds";
     default: return "unknown error";
   }
 }
@@ -354,7 +355,11 @@ int rs_plan_upload(rs_plan* plan, int device) {
   int cur = -1;
   if (hipGetDevice(&cur) != hipSuccess) return RS_EHIP;
   if (cur != device && hipSetDevice(device) != hipSuccess) return RS_EHIP;
-  int rc = RS_OK;
+  int rc = rs::scratch_init(device);   // where this GPU keeps the fixed array of rs_pack_noalloc
+  if (rc != RS_OK) {
+    if (cur != device) (void)hipSetDevice(cur);
+    return rc;
+  }
   try {
     rs::build_host_tables(plan->t, plan->world, plan->S, plan->all_quant, plan->all_state,
                           &plan->host);
@@ -450,6 +455,22 @@ static int group_op(int op, const rs_plan* plan, const rs_tensor_table* tab, con
 
 int rs_pack(const rs_plan* plan, const rs_tensor_table* src, void* dbuf, void* stream) {
   return group_op(rs::kGroupPack, plan, src, dbuf, 1.0f, stream);
+}
+
+int rs_pack_noalloc(const rs_plan* plan, const void* const* src_ptrs, void* dbuf, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!src_ptrs || !dbuf) return RS_EINVAL;
+  if (!aligned16(dbuf)) return RS_EALIGN;
+  const int n = int(plan->t.size());
+  if (n > RS_NOALLOC_MAX_TENSORS) return RS_ETOOBIG;
+  for (int i = 0; i < n; ++i) {
+    if (!src_ptrs[i]) return RS_EINVAL;
+    if (reinterpret_cast<uintptr_t>(src_ptrs[i]) & 1) return RS_EALIGN;  // bf16 element alignment
+  }
+  return rs::launch_pack_staged(plan->dev, n, src_ptrs, plan->orig.data(), dbuf, plan->S,
+                                plan->host.granules_per_rank, plan->host.n_payload_gran,
+                                plan->host.n_padding_gran, static_cast<hipStream_t>(stream));
 }
 
 int rs_unpack_bf16(const rs_plan* plan, const void* dbuf, const rs_tensor_table* dst, void* stream) {

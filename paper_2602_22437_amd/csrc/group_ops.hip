@@ -5,6 +5,8 @@
 // single-wavefront workgroups for copies (measured 3-4 % faster than 256 lanes), non-temporal
 // loads/stores since nothing is reused, and one 8-byte table read per workgroup to find its
 // granule and its tensor.  No MFMA: nothing here is a contraction.
+#include <mutex>
+
 #include "device_util.h"
 
 namespace rs {
@@ -158,6 +160,50 @@ __global__ __launch_bounds__(kCopyThreads) void copy_probe_kernel(const u32x4* _
 }
 
 // -------------------------------------------------------------------------------------------
+// Pointer staging for callers that cannot allocate: the tensor -> address table of one call lives
+// in a fixed array in device memory instead of a table made by hipMalloc.  The host hands the
+// pointers over as kernel arguments (kStageChunk per launch), so nothing is copied from host
+// memory either.  One array per GPU, shared by every call on that GPU.
+// -------------------------------------------------------------------------------------------
+static_assert(kScratchTensors == RS_NOALLOC_MAX_TENSORS, "the header states the array's capacity");
+static __device__ __align__(256) unsigned char scratch[kScratchTensors * sizeof(void*)];
+
+constexpr int kStageChunk = 256;           // 2 KiB of kernel arguments
+struct PtrChunk {
+  void* p[kStageChunk];
+};
+
+__global__ __launch_bounds__(kStageChunk) void stage_ptrs_kernel(PtrChunk chunk, void** table,
+                                                                int first, int count) {
+  const int i = threadIdx.x;
+  if (i < count) table[first + i] = chunk.p[i];
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_addr[kMaxDevices] = {};      // device address of `scratch` on every GPU seen so far
+}  // namespace
+
+// Looks up where `scratch` lives on `device`, which must be the current device.  The array's name
+// is only a host-side handle: kernels and copies get the address found here.
+int scratch_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return RS_EINVAL;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_addr[device]) return RS_OK;
+  void* addr = nullptr;
+  if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) return RS_EHIP;
+  scratch_addr[device] = addr;
+  return RS_OK;
+}
+
+static void* scratch_of(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  return scratch_addr[device];
+}
+
+// -------------------------------------------------------------------------------------------
 // launchers (host)
 // -------------------------------------------------------------------------------------------
 int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, void* dbuf, float alpha,
@@ -186,6 +232,30 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
   }
 #undef RS_GROUP_OP
   return launched();
+}
+
+// ragged_pack with the pointer table staged in the GPU's fixed array: host_ptrs[order[j]] is the
+// j-th tensor in the buffer.  Launches ceil(n / kStageChunk) staging kernels and the copy kernel
+// on `st`; allocates nothing.
+int launch_pack_staged(const DeviceTables& dev, int n, const void* const* host_ptrs,
+                       const int32_t* order, void* dbuf, int64_t S, int64_t gpr,
+                       int64_t n_payload_gran, int64_t n_padding_gran, hipStream_t st) {
+  if (n > kScratchTensors) return RS_ETOOBIG;
+  int rc = scratch_init(dev.device);
+  if (rc != RS_OK) return rc;
+  void** table = static_cast<void**>(scratch_of(dev.device));
+  if (!table) return RS_EHIP;
+  for (int first = 0; first < n; first += kStageChunk) {
+    const int count = n - first < kStageChunk ? n - first : kStageChunk;
+    PtrChunk chunk;
+    for (int i = 0; i < count; ++i) chunk.p[i] = const_cast<void*>(host_ptrs[order[first + i]]);
+    for (int i = count; i < kStageChunk; ++i) chunk.p[i] = nullptr;
+    stage_ptrs_kernel<<<dim3(1), dim3(kStageChunk), 0, st>>>(chunk, table, first, count);
+    rc = launched();
+    if (rc != RS_OK) return rc;
+  }
+  return launch_group_op(kGroupPack, dev, n, table, dbuf, 1.0f, S, gpr,
+                         S, n_payload_gran, n_padding_gran, st);
 }
 
 int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st) {

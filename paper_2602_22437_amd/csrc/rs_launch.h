@@ -13,6 +13,14 @@ int launch_group_op(int op, const DeviceTables& dev, int n, void* const* ptrs, v
                     int64_t S, int64_t gpr, int64_t region_stride, int64_t n_payload_gran,
                     int64_t n_padding_gran, hipStream_t st);
 int launch_fill_zero(void* dst, int64_t bytes, hipStream_t st);
+// ragged_pack for callers that cannot allocate: the pointer table is staged in a fixed array that
+// every GPU holds (kScratchTensors pointers), found once per device by scratch_init (the device
+// must be current).  host_ptrs[order[j]] is the j-th tensor in the buffer.
+constexpr int kScratchTensors = 4096;
+int scratch_init(int device);
+int launch_pack_staged(const DeviceTables& dev, int n, const void* const* host_ptrs,
+                       const int32_t* order, void* dbuf, int64_t S, int64_t gpr,
+                       int64_t n_payload_gran, int64_t n_padding_gran, hipStream_t st);
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
                         float* out, int64_t S, int64_t gpr, int rank, int rows, hipStream_t st);
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
