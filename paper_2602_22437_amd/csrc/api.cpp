@@ -378,7 +378,7 @@ int rs_plan_upload(rs_plan* plan, int device) {
     }
     // the big host mirrors are not needed again
     std::vector<int32_t>().swap(plan->host.gran_first);
-    std::vector<rs::Item>().swap(plan->host.items);
+    std::vector<rs::QItem>().swap(plan->host.items);
     std::vector<rs::GranRef>().swap(plan->host.payload_gran);
     std::vector<int32_t>().swap(plan->host.padding_gran);
     std::vector<rs::Item>().swap(plan->host.state_items);

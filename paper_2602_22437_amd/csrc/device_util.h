@@ -24,6 +24,26 @@ __device__ __forceinline__ void st8(void* p, u32x2 v) {
   __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
 }
 
+// Maximum of an unsigned value (or the bit pattern of a non-negative float) over each row of 16
+// lanes, delivered to every lane of the row: four rotate-within-row DPP steps, no LDS traffic.
+template <int kCtrl>
+__device__ __forceinline__ unsigned dpp_max_step(unsigned v) {
+  return max(v, unsigned(__builtin_amdgcn_update_dpp(0, int(v), kCtrl, 0xf, 0xf, false)));
+}
+__device__ __forceinline__ unsigned row16_max(unsigned v) {
+  v = dpp_max_step<0x121>(v);   // row_ror:1
+  v = dpp_max_step<0x122>(v);   // row_ror:2
+  v = dpp_max_step<0x124>(v);   // row_ror:4
+  return dpp_max_step<0x128>(v);   // row_ror:8
+}
+// the same over the whole wavefront, as a wave-uniform value
+__device__ __forceinline__ unsigned wave_max(unsigned v) {
+  v = row16_max(v);
+  const unsigned a = __builtin_amdgcn_readlane(int(v), 0), b = __builtin_amdgcn_readlane(int(v), 16);
+  const unsigned c = __builtin_amdgcn_readlane(int(v), 32), d = __builtin_amdgcn_readlane(int(v), 48);
+  return max(max(a, b), max(c, d));
+}
+
 // Workgroups are handed to the 8 XCDs round-robin by block index.  This turns the block index
 // into a work index such that each XCD takes runs of `chunk` consecutive work items (work that is
 // adjacent in memory then shares an XCD's L2 and DRAM pages).  The grid must be a multiple of
@@ -89,6 +109,20 @@ __device__ __forceinline__ Divisor shared_divisor(float b) {
   d.r = d.fast ? 1.0f / b : 0.0f;
   return d;
 }
+
+// The correctly rounded fp32 quotient x / b for many dividends x that share the divisor b, by
+// way of double precision: RN32(RN64(x * rd)) with rd = RN64(1 / b) (any rd within 2^-51
+// relative of 1 / b will do).  Why this is RN32(x / b) exactly: with x and b fp32 (24-bit
+// significands), let m be a midpoint between neighbouring fp32 values near y = x / b, spacing
+// 2^(E-23).  x - m * b is an integer multiple of 2^(E + e_b - 47), so unless it is zero y lies at
+// least 2^(E-48) from m; the double product is within 2^(E-50) of y and so falls on the same side
+// of every midpoint, and the conversion to fp32 rounds it as it would round y.  x = m * b exactly
+// needs a 25-bit m times b to fit x's 24 bits, which forces b to a power of two, where the
+// quotient is exact anyway.  No range restrictions (doubles neither over- nor underflow on fp32
+// inputs), -0 stays -0, three full-rate operations per element against five FMAs plus a
+// sign fix-up for the fp32 recurrence above.
+__device__ __forceinline__ double shared_reciprocal(float b) { return 1.0 / double(b); }
+__device__ __forceinline__ float exact_quotient(float x, double rd) { return float(double(x) * rd); }
 
 // status of the launch just enqueued
 static inline int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }

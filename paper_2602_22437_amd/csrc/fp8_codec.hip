@@ -5,87 +5,95 @@
 
 namespace rs {
 
-__device__ __forceinline__ unsigned abs_max_bits(unsigned m, unsigned packed) {
-  // bf16 magnitudes order like their 15-bit patterns
-  m = max(m, packed & 0x7fffu);
-  return max(m, (packed >> 16) & 0x7fffu);
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// bf16 magnitudes order like their 15-bit patterns; both halves of a word at once
+// (v_and_b32 + v_pk_max_u16)
+__device__ __forceinline__ u16x2 abs_pair(unsigned packed) {
+  return __builtin_bit_cast(u16x2, packed & 0x7fff7fffu);
 }
 
-// The divisor of a block is its scale; see Divisor in device_util.h.  The exact shortcut is taken
-// while kDivFastLo <= amax < kDivFastHi, which rules out under- and overflow of every
-// intermediate for all elements whose quotient is not far below the smallest E4M3 subnormal
-// (those give a zero code either way); blocks outside that range take the plain division.
-constexpr unsigned kDivFastLo = 67u << 7;    // amax >= 2^-60 (bf16 bit pattern)
-constexpr unsigned kDivFastHi = 188u << 7;   // amax <  2^61
-
-__device__ __forceinline__ Divisor make_divisor(unsigned amax_bits) {
-  Divisor d;
-  d.b = __uint_as_float(amax_bits << 16) / kE4M3Max;
-  d.fast = amax_bits >= kDivFastLo && amax_bits < kDivFastHi;
-  d.r = d.fast ? 1.0f / d.b : 0.0f;
-  return d;
+// largest 15-bit magnitude pattern among the 8 bf16 values of a vector
+__device__ __forceinline__ unsigned abs_max8(const u32x4 v) {
+  const u16x2 ab = __builtin_elementwise_max(abs_pair(v.x), abs_pair(v.y));
+  const u16x2 cd = __builtin_elementwise_max(abs_pair(v.z), abs_pair(v.w));
+  const unsigned mx = __builtin_bit_cast(unsigned, __builtin_elementwise_max(ab, cd));
+  return max(mx & 0xffffu, mx >> 16);
 }
 
-__device__ __forceinline__ unsigned quant_pair(unsigned packed, const Divisor& d) {
-  // two bf16 -> two E4M3 codes in the low 16 bits
-  const float a = divide(__uint_as_float(packed << 16), d);
-  const float b = divide(__uint_as_float(packed & 0xffff0000u), d);
-  const float ca = __builtin_amdgcn_fmed3f(a, -kE4M3Max, kE4M3Max);
-  const float cb = __builtin_amdgcn_fmed3f(b, -kE4M3Max, kE4M3Max);
-  return unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false)) & 0xffffu;
+// scale = amax / 448, correctly rounded (one fp32 division per block)
+__device__ __forceinline__ float scale_of(unsigned amax_bits) {
+  return __uint_as_float(amax_bits << 16) / kE4M3Max;
 }
 
-// One full work item whose rows are 16-byte structured: 128 slots of exactly 128 elements,
-// slot s at x + s * pitch.  kTile: one scale for the whole item (a 128x128 tile);
-// otherwise one scale per slot (128 consecutive 1x128 blocks), written to scales[slot].
-template <bool kTile>
-__device__ __forceinline__ void quant_full_item(const uint16_t* __restrict__ x,
+// codes of 8 bf16 values of a block: E4M3(clamp(RN(x / scale))), the quotient by way of the
+// block's double-precision reciprocal (exact_quotient in device_util.h), hardware RNE convert
+__device__ __forceinline__ u32x2 quant8(const u32x4 v, double rd) {
+  const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                      bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+  float q[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    q[j] = __builtin_amdgcn_fmed3f(exact_quotient(x[j], rd), -kE4M3Max, kE4M3Max);
+  u32x2 c;
+  c.x = unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0, false), true));
+  c.y = unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(q[6], q[7], __builtin_amdgcn_cvt_pk_fp8_f32(q[4], q[5], 0, false), true));
+  return c;
+}
+
+// One work item whose rows are 16-byte structured: 128 slots of 128 elements, slot s at
+// x + s * pitch.  kTile: one scale for the whole item (a 128x128 tile, of which `rows` x `cols`
+// exist when kMask; cols is a multiple of 8); otherwise one scale per slot (128 consecutive
+// 1x128 blocks), written to scales[slot].
+template <bool kTile, bool kMask>
+__device__ __forceinline__ void quant_lean_item(const uint16_t* __restrict__ x,
                                                 uint8_t* __restrict__ codes, int64_t pitch,
-                                                float* __restrict__ scales, unsigned* wave_max) {
+                                                float* __restrict__ scales, unsigned* wave_max_lds,
+                                                int rows, int cols) {
   const int tid = threadIdx.x;
   const int64_t lane_off = int64_t(tid >> 4) * pitch + (tid & 15) * 8;
   const int64_t step = int64_t(kQuantRowStep) * pitch;
   u32x4 v[kQuantLoads];
-#pragma unroll
-  for (int i = 0; i < kQuantLoads; ++i) v[i] = ld16(x + lane_off + i * step);
-  unsigned m[kQuantLoads];
+  bool on[kQuantLoads];
 #pragma unroll
   for (int i = 0; i < kQuantLoads; ++i) {
-    unsigned a = abs_max_bits(0, v[i].x);
-    a = abs_max_bits(a, v[i].y);
-    a = abs_max_bits(a, v[i].z);
-    m[i] = abs_max_bits(a, v[i].w);
+    on[i] = !kMask || (((tid & 15) * 8 < cols) & ((tid >> 4) + kQuantRowStep * i < rows));
+    v[i] = u32x4{0, 0, 0, 0};
+    if (on[i]) v[i] = ld16(x + lane_off + i * step);
   }
+  unsigned m[kQuantLoads];
+#pragma unroll
+  for (int i = 0; i < kQuantLoads; ++i) m[i] = abs_max8(v[i]);
+  double rd[kQuantLoads];
   if (kTile) {
-    unsigned a = max(max(m[0], m[1]), max(m[2], m[3]));
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
-    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    unsigned a = wave_max(max(max(m[0], m[1]), max(m[2], m[3])));
+    if ((tid & 63) == 0) wave_max_lds[tid >> 6] = a;
     __syncthreads();
-    a = wave_max[0];
+    a = wave_max_lds[0];
 #pragma unroll
-    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
-    if (tid == 0) scales[0] = __uint_as_float(a << 16) / kE4M3Max;
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max_lds[w]);
+    const float sc = scale_of(a);
+    if (tid == 0) scales[0] = sc;
+    const double r = shared_reciprocal(sc);
 #pragma unroll
-    for (int i = 0; i < kQuantLoads; ++i) m[i] = a;
+    for (int i = 0; i < kQuantLoads; ++i) {
+      m[i] = a;
+      rd[i] = r;
+    }
   } else {
 #pragma unroll
     for (int i = 0; i < kQuantLoads; ++i) {
-      unsigned a = m[i];
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
-      m[i] = a;
-      if ((tid & 15) == 0) scales[(tid >> 4) + kQuantRowStep * i] = __uint_as_float(a << 16) / kE4M3Max;
+      m[i] = row16_max(m[i]);
+      const float sc = scale_of(m[i]);
+      if ((tid & 15) == 0) scales[(tid >> 4) + kQuantRowStep * i] = sc;
+      rd[i] = shared_reciprocal(sc);
     }
   }
 #pragma unroll
   for (int i = 0; i < kQuantLoads; ++i) {
+    if (!on[i]) continue;
     u32x2 c{0, 0};
-    if (m[i] != 0) {
-      const Divisor d = make_divisor(m[i]);
-      c.x = quant_pair(v[i].x, d) | (quant_pair(v[i].y, d) << 16);
-      c.y = quant_pair(v[i].z, d) | (quant_pair(v[i].w, d) << 16);
-    }
+    if (m[i] != 0) c = quant8(v[i], rd[i]);
     st8(codes + lane_off + i * step, c);
   }
 }
@@ -96,11 +104,11 @@ __device__ __forceinline__ void quant_full_item(const uint16_t* __restrict__ x,
 // x / codes are addressed relative to elem_base (0 or rank * S), scales to scale_off.
 // -------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
-    const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
+    const TensorDev* __restrict__ T, const QItem* __restrict__ items, int64_t item_off,
     const uint16_t* __restrict__ x_one, uint8_t* __restrict__ codes_one,
     float* __restrict__ scales_one, void* const* __restrict__ batch, int batch_count,
     int64_t elem_base, int64_t scale_off, int64_t item_count) {
-  __shared__ unsigned wave_max[kQuantThreads / 64];
+  __shared__ unsigned wave_max_lds[kQuantThreads / 64];
   // batched launch: batch = [shards | codes | scales] pointers of batch_count units
   const uint16_t* __restrict__ x = x_one;
   uint8_t* __restrict__ codes = codes_one;
@@ -118,37 +126,31 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
   } else if (idx >= item_count) {
     return;
   }
-  const Item it = items[item_off + idx];
+  const QItem it = items[item_off + idx];
   if (it.tensor < 0) {
     zero_fill_bytes(codes + (it.first - elem_base), it.count, kQuantThreads);
     return;
   }
+  // Items whose rows are 16-byte structured (nearly all of them) need nothing but their own
+  // record: no per-slot bookkeeping, straight-line loads, one reduction, straight-line stores.
+  if (it.lean != 0) {
+    const int64_t off = it.elem - elem_base;
+    float* const sc = scales + (it.scale - scale_off);
+    if (it.lean == 2)
+      quant_lean_item<false, false>(x + off, codes + off, 128, sc, wave_max_lds, 128, 128);
+    else if (it.rows == 128 && it.cols == 128)
+      quant_lean_item<true, false>(x + off, codes + off, it.pitch, sc, wave_max_lds, 128, 128);
+    else
+      quant_lean_item<true, true>(x + off, codes + off, it.pitch, sc, wave_max_lds, it.rows, it.cols);
+    return;
+  }
+  // tensors without that structure (odd row pitches, unaligned starts, ragged runs)
   const TensorDev t = T[it.tensor];
   const bool tile = (t.flags & kFlagTile) != 0;
   const bool vec = (t.flags & kFlagVec) != 0;
   const int tid = threadIdx.x;
   const int r_in = tid >> 4, col0 = (tid & 15) * 8;
   const int64_t base = t.ell - elem_base;
-
-  // Full, 16-byte-structured items (nearly all of them) take the lean path: no per-slot
-  // bookkeeping, straight-line loads, one reduction, straight-line stores.
-  if (vec) {
-    if (tile) {
-      if ((it.first + 1) * 128 <= t.rows && int64_t(it.count + 1) * 128 <= t.cols) {
-        const int64_t off = base + it.first * 128 * t.cols + int64_t(it.count) * 128;
-        quant_full_item<true>(x + off, codes + off, t.cols,
-                              scales + (t.scale_base + it.first * t.nbc + it.count - scale_off),
-                              wave_max);
-        return;
-      }
-    } else if ((t.flags & kFlagContig) && it.count == kItemSlots &&
-               (it.first + kItemSlots) * 128 <= t.e) {
-      const int64_t off = base + it.first * 128;
-      quant_full_item<false>(x + off, codes + off, 128,
-                             scales + (t.scale_base + it.first - scale_off), wave_max);
-      return;
-    }
-  }
 
   Slot sl[kQuantLoads];
   u32x4 v[kQuantLoads];
@@ -180,40 +182,31 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
   // per-slot amax over this lane's 8 elements, then over the 16 lanes of the slot
   unsigned m[kQuantLoads];
 #pragma unroll
-  for (int i = 0; i < kQuantLoads; ++i) {
-    unsigned a = 0;
-    a = abs_max_bits(a, v[i].x);
-    a = abs_max_bits(a, v[i].y);
-    a = abs_max_bits(a, v[i].z);
-    a = abs_max_bits(a, v[i].w);
-    m[i] = a;
-  }
+  for (int i = 0; i < kQuantLoads; ++i) m[i] = abs_max8(v[i]);
+  double rd[kQuantLoads];
   if (tile) {
-    unsigned a = m[0];
-#pragma unroll
-    for (int i = 1; i < kQuantLoads; ++i) a = max(a, m[i]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
-    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    unsigned a = wave_max(max(max(m[0], m[1]), max(m[2], m[3])));
+    if ((tid & 63) == 0) wave_max_lds[tid >> 6] = a;
     __syncthreads();
-    a = wave_max[0];
+    a = wave_max_lds[0];
 #pragma unroll
-    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max_lds[w]);
+    const float sc = scale_of(a);
+    const double r = shared_reciprocal(sc);
 #pragma unroll
-    for (int i = 0; i < kQuantLoads; ++i) m[i] = a;
-    if (tid == 0) {
-      const int64_t sidx = t.scale_base + it.first * t.nbc + it.count - scale_off;
-      scales[sidx] = __uint_as_float(a << 16) / kE4M3Max;
+    for (int i = 0; i < kQuantLoads; ++i) {
+      m[i] = a;
+      rd[i] = r;
     }
+    if (tid == 0) scales[t.scale_base + it.first * t.nbc + it.count - scale_off] = sc;
   } else {
 #pragma unroll
     for (int i = 0; i < kQuantLoads; ++i) {
-      unsigned a = m[i];
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
-      m[i] = a;
+      m[i] = row16_max(m[i]);
+      const float sc = scale_of(m[i]);
+      rd[i] = shared_reciprocal(sc);
       if ((tid & 15) == 0 && r_in + kQuantRowStep * i < it.count)
-        scales[t.scale_base + sl[i].blk - scale_off] = __uint_as_float(a << 16) / kE4M3Max;
+        scales[t.scale_base + sl[i].blk - scale_off] = sc;
     }
   }
 
@@ -221,11 +214,7 @@ __global__ __launch_bounds__(kQuantThreads) void block_quant_kernel(
   for (int i = 0; i < kQuantLoads; ++i) {
     if (sl[i].ncol == 0) continue;
     u32x2 c{0, 0};
-    if (m[i] != 0) {
-      const Divisor d = make_divisor(m[i]);
-      c.x = quant_pair(v[i].x, d) | (quant_pair(v[i].y, d) << 16);
-      c.y = quant_pair(v[i].z, d) | (quant_pair(v[i].w, d) << 16);
-    }
+    if (m[i] != 0) c = quant8(v[i], rd[i]);
     uint8_t* dst = codes + base + sl[i].off;
     if (vec && sl[i].ncol == 8) {
       st8(dst, c);

@@ -35,14 +35,14 @@ __device__ __forceinline__ unsigned quant4(float a, float b, float c, float e, c
 }
 
 __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
-    const TensorDev* __restrict__ T, const Item* __restrict__ items, int64_t item_off,
+    const TensorDev* __restrict__ T, const QItem* __restrict__ items, int64_t item_off,
     int64_t item_count, const uint16_t* __restrict__ P, int64_t row_stride,
     uint8_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mean_out,
     int64_t elem_base, int64_t scale_off, int W, float inv_w) {
   __shared__ unsigned wave_max[kQuantThreads / 64];
   const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
   if (idx >= item_count) return;
-  const Item it = items[item_off + idx];
+  const QItem it = items[item_off + idx];
   const int tid = threadIdx.x;
   if (it.tensor < 0) {   // padding of the region: zero codes, zero mean
     const int64_t off = it.first - elem_base;

@@ -53,6 +53,24 @@ struct Item {
                    //              count = column strip / runs in this item (<= kStateRuns)
 };
 
+// A quantisation work item (48 bytes): the Item fields plus what lets a workgroup start loading
+// without reading the tensor's record first (one table read instead of two dependent ones).
+struct alignas(16) QItem {
+  int64_t first;   // as Item
+  int32_t tensor;  // -1 marks a zero-fill item
+  int32_t count;   // as Item
+  int64_t elem;    // buffer element of the item's first element (tile: its top-left corner)
+  int64_t scale;   // index of the item's first scale in the unit's scale array
+  int32_t pitch;   // tile: elements from one row to the next; runs: 128
+  int16_t rows;    // tile: rows that exist (1..128); runs: blocks in the item
+  int16_t cols;    // tile: columns that exist (1..128); runs: 128
+  int32_t lean;    // non-zero: every row piece is 16-byte structured and a whole number of 8-element
+                   // groups, so the kernel needs nothing but this record.  1: a tile of any extent;
+                   // 2: 128 full back-to-back runs of 128
+  int32_t reserved;
+};
+static_assert(sizeof(QItem) == 48, "three 16-byte loads");
+
 // A granule that holds payload, with the first tensor that ends after its start: what a copy
 // workgroup needs to find its work in one table read (8 bytes).
 struct alignas(8) GranRef {
@@ -78,7 +96,7 @@ struct HostTables {
   std::vector<TensorDev> tensors;
   std::vector<int32_t> gran_first;   // world * granules_per_rank
   int64_t granules_per_rank = 0;
-  std::vector<Item> items;           // rank-major
+  std::vector<QItem> items;          // rank-major
   std::vector<int64_t> item_begin;   // world + 1
   // granules that hold at least one payload element (ids = rank * granules_per_rank + index):
   // the unpack kernels launch workgroups for these only and never visit pure padding
@@ -93,7 +111,7 @@ struct DeviceTables {
   int device = -1;
   TensorDev* tensors = nullptr;
   int32_t* gran_first = nullptr;
-  Item* items = nullptr;
+  QItem* items = nullptr;
   GranRef* payload_gran = nullptr;
   int32_t* padding_gran = nullptr;
   Item* state_items = nullptr;

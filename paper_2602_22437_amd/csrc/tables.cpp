@@ -9,9 +9,9 @@ namespace rs {
 
 namespace {
 
-void add_fill(std::vector<Item>* items, int64_t from, int64_t to) {
+void add_fill(std::vector<QItem>* items, int64_t from, int64_t to) {
   for (int64_t d = from; d < to; d += kFillElems) {
-    Item it{};
+    QItem it{};
     it.first = d;
     it.tensor = -1;
     it.count = int32_t(std::min<int64_t>(kFillElems, to - d));
@@ -139,12 +139,19 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
       const int64_t src_a = a - h.ell, src_b = b - h.ell;  // whole granules by construction
       if (h.mode == RS_BLOCK_128x128) {
         const int64_t br_a = src_a / h.g, br_b = (src_b + h.g - 1) / h.g;
+        const bool vec = h.ell % 8 == 0 && h.cols % 8 == 0 && h.cols < (int64_t(1) << 31);
         for (int64_t br = br_a; br < br_b; ++br)
           for (int64_t bc = 0; bc < h.nbc; ++bc) {
-            Item it{};
+            QItem it{};
             it.first = br;
             it.count = int32_t(bc);
             it.tensor = i;
+            it.elem = h.ell + br * 128 * h.cols + bc * 128;
+            it.scale = h.scale_base + br * h.nbc + bc;
+            it.pitch = int32_t(std::min<int64_t>(h.cols, 0x7fffffff));
+            it.rows = int16_t(std::min<int64_t>(128, h.rows - br * 128));
+            it.cols = int16_t(std::min<int64_t>(128, h.cols - bc * 128));
+            it.lean = vec ? 1 : 0;
             out->items.push_back(it);
           }
       } else {
@@ -156,11 +163,18 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
           blk_a = src_a / 128;
           blk_b = (src_b + 127) / 128;
         }
+        const bool contig = h.cols == 0 || h.cols % 128 == 0;
         for (int64_t q = blk_a; q < blk_b; q += kItemSlots) {
-          Item it{};
+          QItem it{};
           it.first = q;
           it.tensor = i;
           it.count = int32_t(std::min<int64_t>(kItemSlots, blk_b - q));
+          it.elem = h.ell + q * 128;              // meaningful for back-to-back blocks only
+          it.scale = h.scale_base + q;
+          it.pitch = 128;
+          it.rows = int16_t(it.count);
+          it.cols = 128;
+          it.lean = (contig && h.ell % 8 == 0 && it.count == kItemSlots && (q + kItemSlots) * 128 <= h.e) ? 2 : 0;
           out->items.push_back(it);
         }
       }

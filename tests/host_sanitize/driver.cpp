@@ -144,7 +144,7 @@ int main(int argc, char** argv) {
       std::vector<int64_t> covered(size_t(world), 0);
       for (int64_t k = 0; k < world; ++k)
         for (int64_t q = h.item_begin[size_t(k)]; q < h.item_begin[size_t(k) + 1]; ++q) {
-          const rs::Item& it = h.items[size_t(q)];
+          const rs::QItem& it = h.items[size_t(q)];
           if (it.tensor < 0) {
             REQUIRE(it.first >= k * S && it.first + it.count <= (k + 1) * S && it.count > 0);
             covered[size_t(k)] += it.count;
@@ -168,6 +168,27 @@ int main(int argc, char** argv) {
           }
           REQUIRE(lo >= 0 && hi <= x.e && lo < hi);
           REQUIRE(x.ell + lo >= k * S && x.ell + hi <= (k + 1) * S);
+          // what the table-free path of the kernel goes by: every 16-byte access it derives from
+          // the record alone lies inside the tensor (hence the rank) and is 8-element aligned
+          if (it.lean == 1) {
+            REQUIRE(x.mode == RS_BLOCK_128x128 && it.pitch == x.cols && x.ell % 8 == 0 && x.cols % 8 == 0);
+            REQUIRE(it.rows >= 1 && it.rows <= 128 && it.cols >= 8 && it.cols <= 128 && it.cols % 8 == 0);
+            REQUIRE(it.elem == x.ell + it.first * 128 * x.cols + int64_t(it.count) * 128);
+            REQUIRE(it.first * 128 + it.rows <= x.rows && int64_t(it.count) * 128 + it.cols <= x.cols);
+            REQUIRE(it.rows == 128 || it.first * 128 + it.rows == x.rows);
+            REQUIRE(it.cols == 128 || int64_t(it.count) * 128 + it.cols == x.cols);
+            REQUIRE(it.scale == x.scale_base + it.first * x.nbc + it.count);
+            const int64_t last = it.elem + int64_t(it.rows - 1) * it.pitch + it.cols;   // one past the end
+            REQUIRE(it.elem % 8 == 0 && last <= x.ell + x.e);
+          } else if (it.lean == 2) {
+            REQUIRE(x.mode != RS_BLOCK_128x128 && it.pitch == 128 && it.rows == 128 && it.cols == 128);
+            REQUIRE(x.cols == 0 || x.cols % 128 == 0);
+            REQUIRE(it.elem == x.ell + it.first * 128 && it.elem % 8 == 0);
+            REQUIRE(it.elem + 128 * 128 <= x.ell + x.e && it.count == rs::kItemSlots);
+            REQUIRE(it.scale == x.scale_base + it.first);
+          } else {
+            REQUIRE(it.lean == 0);
+          }
         }
       int64_t padding = world * S;
       for (const rs::TensorHost& x : t) padding -= x.e;
