@@ -15,6 +15,8 @@ before the timed region:
     then ONE block_quant launch over the rank's shard of every unit a rank holds: the 32 decoder
     units of configuration 2, and for the MoE configurations the rank's shard of as many units as
     the model has MoE layers (36 / 58; one unit's other buffers would not fit 32 times over).
+    Configuration 2's regions are short (3.7 M elements, 68 us per reduce), so its 32 reduces
+    are likewise one launch (rs_reduce_batch), after the per-unit pack and unpack launches.
 HIP events on the launch stream bracket the launches inside the timed region; the same launches
 are also timed back to back without events in between.  Further kernels of the library (fused
 reduce + quantise, fp32 unpack, group operators, 8-bit Adam step, strided and rooted copies,
@@ -262,36 +264,54 @@ def bench_config(wl, args, torch, B):
     names = list(per_unit)
     batch = (B.rs_shard_batch_create(plan, rank, [q[0] for q in Q], [q[1] for q in Q], [q[2] for q in Q])
              if quant else None)
-    per_unit_names = [n for n in names if n != "block_quant"]
+    # many units per step: their reduces are one launch too (the per-unit launch is timed outside)
+    rbatch = (B.rs_partials_batch_create(plan, rank, [d["partials"] for d in U], S, [d["out"] for d in U])
+              if units > 1 else None)
+    batched_names = [n for n in names if n == "block_quant" or (n == "shard_reduce" and rbatch)]
+    per_unit_names = [n for n in names if n not in batched_names]
     event_every = args.event_every if units > 1 else 1
 
     def step(events=None, qevents=None):
         for ui, d in enumerate(U):
             ev = ([torch.cuda.Event(enable_timing=True) for _ in range(len(per_unit_names) + 1)]
                   if events is not None and ui % event_every == 0 else None)
+            k = 0
             if ev:
-                ev[0].record(stream)
+                ev[k].record(stream)
             B.rs_pack(plan, d["src_tab"], d["dbuf"], stream)
+            k += 1
             if ev:
-                ev[1].record(stream)
-            B.rs_reduce(plan, rank, d["partials"], S, d["out"], stream)
-            if ev:
-                ev[2].record(stream)
+                ev[k].record(stream)
+            if not rbatch:
+                B.rs_reduce(plan, rank, d["partials"], S, d["out"], stream)
+                k += 1
+                if ev:
+                    ev[k].record(stream)
             if quant:
                 B.rs_unpack(plan, d["codes"], d["scales"], d["dst_tab"], stream)
             else:
                 B.rs_unpack_bf16(plan, d["dbuf"], d["dst_tab"], stream)
+            k += 1
             if ev:
-                ev[3].record(stream)
+                ev[k].record(stream)
                 events.append(ev)
+        qe = ([torch.cuda.Event(enable_timing=True) for _ in range(len(batched_names) + 1)]
+              if qevents is not None and batched_names else None)
+        k = 0
+        if qe:
+            qe[0].record(stream)
+        if rbatch:
+            B.rs_reduce_batch(plan, rbatch, stream)
+            k += 1
+            if qe:
+                qe[k].record(stream)
         if quant:
-            qe = [torch.cuda.Event(enable_timing=True) for _ in range(2)] if qevents is not None else None
-            if qe:
-                qe[0].record(stream)
             B.rs_quantize_batch(plan, batch, stream)
+            k += 1
             if qe:
-                qe[1].record(stream)
-                qevents.append(qe)
+                qe[k].record(stream)
+        if qe:
+            qevents.append(qe)
 
     for _ in range(args.warmup):
         step()
@@ -312,11 +332,16 @@ def bench_config(wl, args, torch, B):
         for i, n in enumerate(per_unit_names):
             samples[n].append(ev[i].elapsed_time(ev[i + 1]))
     launch_bytes = dict(per_unit)
+    for qe in qevents:      # the launches that cover many units at once
+        for i, n in enumerate(batched_names):
+            samples[n].append(qe[i].elapsed_time(qe[i + 1]))
     if quant:   # one launch covers the rank's shard of all qshards units
-        samples["block_quant"] = [a.elapsed_time(b) for a, b in qevents]
         launch_bytes["block_quant"] = qshards * per_unit["block_quant"]
+    if rbatch:
+        launch_bytes["shard_reduce"] = units * per_unit["shard_reduce"]
     kern_ms = {n: sum(v) / len(v) for n, v in samples.items()}
-    step_bytes = units * sum(v for k, v in per_unit.items() if k != "block_quant") + launch_bytes.get("block_quant", 0)
+    step_bytes = units * sum(v for k, v in per_unit.items() if k not in batched_names) + sum(
+        launch_bytes[k] for k in batched_names)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     kernels = {}
@@ -328,6 +353,8 @@ def bench_config(wl, args, torch, B):
                       "median_ms": round(ordered[len(ordered) // 2], 4), "min_ms": round(ordered[0], 4)}
     if quant:
         kernels["block_quant"]["note"] = f"one launch over rank {rank}'s shard of {qshards} unit(s)"
+    if rbatch:
+        kernels["shard_reduce"]["note"] = f"one launch over rank {rank}'s region of {units} units (rs_reduce_batch)"
 
     def timed(fn, reps):
         fn()
@@ -352,7 +379,8 @@ def bench_config(wl, args, torch, B):
     # few microseconds of stream time that the per-launch figures above attribute to the kernel
     b2b = {
         "ragged_pack": lambda i=0: B.rs_pack(plan, U[i % units]["src_tab"], U[i % units]["dbuf"], stream),
-        "shard_reduce": lambda i=0: B.rs_reduce(plan, rank, U[i % units]["partials"], S, U[i % units]["out"], stream),
+        "shard_reduce": ((lambda i=0: B.rs_reduce_batch(plan, rbatch, stream)) if rbatch else
+                         (lambda i=0: B.rs_reduce(plan, rank, U[i % units]["partials"], S, U[i % units]["out"], stream))),
     }
     if quant:
         b2b["dequant_unpack"] = lambda i=0: B.rs_unpack(plan, U[i % units]["codes"], U[i % units]["scales"],
@@ -365,6 +393,13 @@ def bench_config(wl, args, torch, B):
         kernels[n_]["back_to_back_ms"] = round(ms, 4)
         kernels[n_]["back_to_back_frac_of_peak"] = round(launch_bytes[n_] / ms / 1e6 / HBM_PEAK_GBPS, 4)
 
+    if rbatch:
+        ms = timed(lambda i=0: B.rs_reduce(plan, rank, U[i % units]["partials"], S, U[i % units]["out"], stream), reps)
+        kernels["shard_reduce_per_unit"] = {
+            "ms": round(ms, 4), "bytes": per_unit["shard_reduce"],
+            "GBps": round(per_unit["shard_reduce"] / ms / 1e6, 1),
+            "frac_of_peak": round(per_unit["shard_reduce"] / ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "note": "rs_reduce on one unit's region per launch, back to back; not in the step"}
     nbytes = total * 2
     probe_dst = torch.empty(total, dtype=torch.bfloat16, device="cuda")
     cp_ms = timed(lambda i=0: B.rs_copy_probe(probe_dst, U[i % units]["dbuf"], nbytes, stream), reps)
@@ -465,7 +500,7 @@ def bench_config(wl, args, torch, B):
                     ab_ms, na * a_bytes, f"the same step over rank {rank}'s shard of {na} units in one launch")
             del A
 
-    dom = max(per_unit_names, key=lambda n: kern_ms[n])
+    dom = max(per_unit_names, key=lambda n: kern_ms[n])     # the launch that takes longest of its kind
     traffic = pmc_traffic(wl.index)
     roof = {
         "bound": "hbm", "kernel": dom, "launches_timed": len(events), "achieved": kernels[dom]["GBps"],
@@ -493,6 +528,8 @@ def bench_config(wl, args, torch, B):
 
     if batch:
         B.rs_shard_batch_destroy(batch)
+    if rbatch:
+        B.rs_partials_batch_destroy(rbatch)
     for d in U:
         B.rs_tensor_table_destroy(d["src_tab"])
         B.rs_tensor_table_destroy(d["dst_tab"])

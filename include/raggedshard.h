@@ -85,6 +85,7 @@ typedef struct rs_segment {
 typedef struct rs_plan rs_plan;                  /* layout plan + device tables, library-owned */
 typedef struct rs_tensor_table rs_tensor_table;  /* device copy of n tensor base pointers */
 typedef struct rs_shard_batch rs_shard_batch;    /* device copy of the buffers of `count` units' shards */
+typedef struct rs_partials_batch rs_partials_batch;  /* the same for the partials and means of `count` units */
 typedef struct rs_adam8_batch rs_adam8_batch;    /* the same for the optimiser buffers of `count` units */
 
 int rs_version(void);
@@ -243,6 +244,17 @@ int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_s
  * contributions, or one per replica in the second step.  rs_reduce is rows == world. */
 int rs_reduce_rows(const rs_plan* plan, int rank, const void* partials, int rows, int64_t row_stride,
                    float* out, void* stream);
+
+/* The same mean for rank `rank`'s region of `count` units that share this plan (the layers of a
+ * model) in one launch, as the DBuffer fuses identical kernels across a group (Section 5): the
+ * region of one unit may be too short to fill the GPU.  partials / outs: host arrays of `count`
+ * device pointers with rs_reduce's meaning and alignment, all with the one row_stride; uploaded
+ * once, reusable by any number of calls.  count <= 65535.  Bit for bit the result of rs_reduce on
+ * every unit (same summation order). */
+int rs_partials_batch_create(const rs_plan* plan, int rank, int count, const void* const* partials,
+                             int64_t row_stride, float* const* outs, rs_partials_batch** out);
+void rs_partials_batch_destroy(rs_partials_batch* batch);
+int rs_reduce_batch(const rs_plan* plan, const rs_partials_batch* batch, void* stream);
 
 /* ---- block_quant: communication-free block-wise FP8 of the local shard (Sections 2.1, 4) ----
  * Per block: amax = max|x|, scale = amax/448 (fp32), code = E4M3 RNE of clamp(x/scale, +-448);

@@ -29,7 +29,8 @@ EXPORTS = [
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
     "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize",
-    "rs_reduce_rows", "rs_pack_noalloc",
+    "rs_reduce_rows", "rs_pack_noalloc", "rs_partials_batch_create", "rs_partials_batch_destroy",
+    "rs_reduce_batch",
 ]
 
 
@@ -104,6 +105,11 @@ _lib.rs_group_scale.argtypes = [_P, C.c_float, _P, _P]
 _lib.rs_group_zero.argtypes = [_P, _P, _P]
 _lib.rs_reduce.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P]
 _lib.rs_reduce_rows.argtypes = [_P, C.c_int, _P, C.c_int, C.c_int64, _P, _P]
+_lib.rs_partials_batch_create.argtypes = [_P, C.c_int, C.c_int, C.POINTER(_P), C.c_int64, C.POINTER(_P),
+                                          C.POINTER(_P)]
+_lib.rs_partials_batch_destroy.argtypes = [_P]
+_lib.rs_partials_batch_destroy.restype = None
+_lib.rs_reduce_batch.argtypes = [_P, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_reduce_quantize.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
@@ -363,6 +369,28 @@ def rs_reduce(plan, rank: int, partials, row_stride: int, out, stream=None) -> N
 def rs_reduce_rows(plan, rank: int, partials, rows: int, row_stride: int, out, stream=None) -> None:
     _check(_lib.rs_reduce_rows(plan, int(rank), _ptr(partials), int(rows), int(row_stride), _ptr(out),
                                _stream(stream)), "rs_reduce_rows")
+
+
+def rs_partials_batch_create(plan, rank: int, partials: Sequence, row_stride: int, outs: Sequence) -> int:
+    """partials / outs: one device tensor (or address) per unit, as rs_reduce takes them."""
+    n = len(partials)
+    if len(outs) != n:
+        raise ValueError("one partial buffer and one output per unit")
+    a, b = (_P * max(1, n))(), (_P * max(1, n))()
+    for i in range(n):
+        a[i], b[i] = _ptr(partials[i]), _ptr(outs[i])
+    out = _P()
+    _check(_lib.rs_partials_batch_create(plan, int(rank), n, a, int(row_stride), b, C.byref(out)),
+           "rs_partials_batch_create")
+    return out.value
+
+
+def rs_partials_batch_destroy(batch) -> None:
+    _lib.rs_partials_batch_destroy(batch)
+
+
+def rs_reduce_batch(plan, batch, stream=None) -> None:
+    _check(_lib.rs_reduce_batch(plan, batch, _stream(stream)), "rs_reduce_batch")
 
 
 def rs_quantize(plan, rank: int, shard, codes, scales, stream=None) -> None:

@@ -69,10 +69,30 @@ __device__ __forceinline__ StateSlot state_slot(const TensorDev& t, const Item& 
 
 __device__ __forceinline__ float quant_step(float absmax, float levels) { return absmax / levels; }
 
-// code = rint(x / step) clamped to [lo, hi]; an all-zero block (absmax 0) gives 0
-__device__ __forceinline__ int state_code(float x, float absmax, const Divisor& step, float lo, float hi) {
-  if (absmax == 0.0f) return 0;
-  return int(__builtin_amdgcn_fmed3f(__builtin_rintf(divide(x, step)), lo, hi));
+// Reciprocal of a block's quantisation step for exact_quotient; an all-zero block (absmax 0,
+// step 0) gets 0, which turns every code of the block into 0.
+__device__ __forceinline__ double step_reciprocal(float absmax, float levels) {
+  return absmax == 0.0f ? 0.0 : shared_reciprocal(quant_step(absmax, levels));
+}
+
+// code = rint(x / step) clamped to [lo, hi]
+__device__ __forceinline__ int state_code(float x, double step_rcp, float lo, float hi) {
+  return int(__builtin_amdgcn_fmed3f(__builtin_rintf(exact_quotient(x, step_rcp)), lo, hi));
+}
+
+// maximum of non-negative floats over the 8 lanes of a 32-column state tile (lanes 8k .. 8k+7),
+// in every lane: neighbour swap, pair swap, mirror within the 8 - three DPP steps
+__device__ __forceinline__ float tile8_max(float v) {
+  unsigned u = __float_as_uint(v);
+  u = dpp_max_step<0xB1>(u);    // quad_perm [1,0,3,2]
+  u = dpp_max_step<0x4E>(u);    // quad_perm [2,3,0,1]
+  u = dpp_max_step<0x141>(u);   // row_half_mirror
+  return __uint_as_float(u);
+}
+// the same over 32 lanes (a run of 128 elements): a row of 16 by rotations, then the other row
+__device__ __forceinline__ float run32_max(float v) {
+  const unsigned u = row16_max(__float_as_uint(v));
+  return __uint_as_float(max(u, unsigned(__shfl_xor(int(u), 16))));
 }
 
 template <bool kTile, bool kFull>
@@ -149,7 +169,6 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
   }
 
   // pass 1: the update; new moments stay in registers
-  const Divisor bc2 = shared_divisor(c.bc2_sqrt);
   float m[kStateSlots][4], v[kStateSlots][4];
   float mmax[kStateSlots], vmax[kStateSlots];
 #pragma unroll
@@ -169,7 +188,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
       const float t3 = c.beta2 * v_old, t4 = c.one_minus_beta2 * gg;
       v[i][j] = t3 + t4;
       const float w1 = __uint_as_float(wq[j]) * c.decay;
-      const float root = divide(__builtin_sqrtf(v[i][j]), bc2);
+      const float root = exact_quotient(__builtin_sqrtf(v[i][j]), c.bc2_sqrt_rcp);
       const float denom = root + c.eps;
       const float upd = c.step_size * (m[i][j] / denom);
       wn[j] = w1 - upd;
@@ -199,11 +218,8 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
       a = fmaxf(a, mmax[i]);
       b = fmaxf(b, vmax[i]);
     }
-#pragma unroll
-    for (int off = 1; off <= 4; off <<= 1) {
-      a = fmaxf(a, __shfl_xor(a, off));
-      b = fmaxf(b, __shfl_xor(b, off));
-    }
+    a = tile8_max(a);
+    b = tile8_max(b);
     if ((cq & 7) == 0) {
       tile_max[0][rw][cq >> 3] = a;
       tile_max[1][rw][cq >> 3] = b;
@@ -228,12 +244,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
   } else {
 #pragma unroll
     for (int i = 0; i < kStateSlots; ++i) {
-      float a = mmax[i], b = vmax[i];
-#pragma unroll
-      for (int off = 1; off <= 16; off <<= 1) {
-        a = fmaxf(a, __shfl_xor(a, off));
-        b = fmaxf(b, __shfl_xor(b, off));
-      }
+      const float a = run32_max(mmax[i]), b = run32_max(vmax[i]);
       mmax[i] = a;
       vmax[i] = b;
       if ((cq & 31) == 0 && sl[i].nv > 0) {
@@ -247,13 +258,12 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
 #pragma unroll
   for (int i = 0; i < kStateSlots; ++i) {
     if (!kFull && sl[i].nv == 0) continue;
-    const Divisor s1 = shared_divisor(quant_step(mmax[i], 127.0f));
-    const Divisor s2 = shared_divisor(quant_step(vmax[i], 255.0f));
+    const double s1 = step_reciprocal(mmax[i], 127.0f), s2 = step_reciprocal(vmax[i], 255.0f);
     unsigned cm = 0, cv = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      cm |= (unsigned(state_code(m[i][j], mmax[i], s1, -127.0f, 127.0f)) & 0xffu) << (8 * j);
-      cv |= (unsigned(state_code(v[i][j], vmax[i], s2, 0.0f, 255.0f)) & 0xffu) << (8 * j);
+      cm |= (unsigned(state_code(m[i][j], s1, -127.0f, 127.0f)) & 0xffu) << (8 * j);
+      cv |= (unsigned(state_code(v[i][j], s2, 0.0f, 255.0f)) & 0xffu) << (8 * j);
     }
     if (kFull || (vec && sl[i].nv == 4)) {
       __builtin_nontemporal_store(cm, reinterpret_cast<unsigned*>(mc + sl[i].off));
@@ -379,8 +389,7 @@ __device__ __forceinline__ void state_codec_item(const TensorDev& t, const Item&
     float a = vmax[0];
 #pragma unroll
     for (int i = 1; i < kStateSlots; ++i) a = fmaxf(a, vmax[i]);
-#pragma unroll
-    for (int off = 1; off <= 4; off <<= 1) a = fmaxf(a, __shfl_xor(a, off));
+    a = tile8_max(a);
     if ((cq & 7) == 0) tile_max[rw][cq >> 3] = a;
     __syncthreads();
     a = tile_max[0][cq >> 3];
@@ -392,9 +401,7 @@ __device__ __forceinline__ void state_codec_item(const TensorDev& t, const Item&
   } else {
 #pragma unroll
     for (int i = 0; i < kStateSlots; ++i) {
-      float a = vmax[i];
-#pragma unroll
-      for (int off = 1; off <= 16; off <<= 1) a = fmaxf(a, __shfl_xor(a, off));
+      const float a = run32_max(vmax[i]);
       vmax[i] = a;
       if ((cq & 31) == 0 && sl[i].nv > 0) absmax[sl[i].blk] = a;
     }
@@ -402,11 +409,11 @@ __device__ __forceinline__ void state_codec_item(const TensorDev& t, const Item&
 #pragma unroll
   for (int i = 0; i < kStateSlots; ++i) {
     if (sl[i].nv == 0) continue;
-    const Divisor step = shared_divisor(quant_step(vmax[i], levels));
+    const double step_rcp = step_reciprocal(vmax[i], levels);
     const float lo = is_unsigned ? 0.0f : -127.0f;
     unsigned c = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c |= (unsigned(state_code(v[i][j], vmax[i], step, lo, levels)) & 0xffu) << (8 * j);
+    for (int j = 0; j < 4; ++j) c |= (unsigned(state_code(v[i][j], step_rcp, lo, levels)) & 0xffu) << (8 * j);
     if (vec && sl[i].nv == 4) {
       __builtin_nontemporal_store(c, reinterpret_cast<unsigned*>(codes + sl[i].off));
     } else {

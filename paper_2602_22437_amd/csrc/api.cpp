@@ -520,8 +520,61 @@ int rs_reduce_rows(const rs_plan* plan, int rank, const void* partials, int rows
     return RS_EINVAL;
   if (!aligned16(partials) || !aligned16(out) || row_stride % 8 != 0) return RS_EALIGN;
   return rs::launch_shard_reduce(plan->dev, int(plan->t.size()), partials, row_stride, out, plan->S,
-                                 plan->host.granules_per_rank, rank, rows,
+                                 plan->host.granules_per_rank, rank, rows, nullptr, 0,
                                  static_cast<hipStream_t>(stream));
+}
+
+int rs_partials_batch_create(const rs_plan* plan, int rank, int count, const void* const* partials,
+                             int64_t row_stride, float* const* outs, rs_partials_batch** out) {
+  if (!out) return RS_EINVAL;
+  *out = nullptr;
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!partials || !outs || count <= 0 || count > 65535 || rank < 0 || rank >= plan->world ||
+      row_stride < plan->S)
+    return RS_EINVAL;
+  if (row_stride % 8 != 0) return RS_EALIGN;
+  Staging host(size_t(count) * 2);
+  if (!host.data) return RS_ENOMEM;
+  for (int u = 0; u < count; ++u) {
+    if (!partials[u] || !outs[u]) return RS_EINVAL;
+    if (!aligned16(partials[u]) || !aligned16(outs[u])) return RS_EALIGN;
+    host[size_t(u)] = const_cast<void*>(partials[u]);
+    host[size_t(count) + u] = outs[u];
+  }
+  rs_partials_batch* b = new (std::nothrow) rs_partials_batch();
+  if (!b) return RS_ENOMEM;
+  b->owner = plan;
+  b->rank = rank;
+  b->count = count;
+  b->row_stride = row_stride;
+  const size_t bytes = host.size() * sizeof(void*);
+  if (hipMalloc(reinterpret_cast<void**>(&b->ptrs), bytes) != hipSuccess) {
+    delete b;
+    return RS_ENOMEM;
+  }
+  if (hipMemcpy(b->ptrs, host.data.get(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(b->ptrs);
+    delete b;
+    return RS_EHIP;
+  }
+  *out = b;
+  return RS_OK;
+}
+
+void rs_partials_batch_destroy(rs_partials_batch* batch) {
+  if (!batch) return;
+  if (batch->ptrs) (void)hipFree(batch->ptrs);
+  delete batch;
+}
+
+int rs_reduce_batch(const rs_plan* plan, const rs_partials_batch* batch, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!batch || batch->owner != plan || !batch->ptrs) return RS_EINVAL;
+  return rs::launch_shard_reduce(plan->dev, int(plan->t.size()), nullptr, batch->row_stride, nullptr,
+                                 plan->S, plan->host.granules_per_rank, batch->rank, int(plan->world),
+                                 batch->ptrs, batch->count, static_cast<hipStream_t>(stream));
 }
 
 int rs_reduce(const rs_plan* plan, int rank, const void* partials, int64_t row_stride, float* out,
@@ -585,6 +638,7 @@ static int adam8_consts(const rs_adam8_hyper* hyper, rs::Adam8Consts* c) {
   c->bc2_sqrt = float(std::sqrt(bc2));
   c->decay = float(1.0 - h.lr * h.weight_decay);
   if (!std::isfinite(c->step_size) || !(c->bc2_sqrt > 0.0f)) return RS_EINVAL;
+  c->bc2_sqrt_rcp = 1.0 / double(c->bc2_sqrt);
   return RS_OK;
 }
 

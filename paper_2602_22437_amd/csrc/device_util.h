@@ -1,5 +1,5 @@
 // Device-side helpers shared by the kernel files: 16-byte vector accesses, the XCD-aware block
-// index remap, bf16 packing, and exact division by a shared divisor.
+// index remap, DPP maxima, bf16 packing, and exact division by a shared divisor.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -71,56 +71,16 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
 __device__ __forceinline__ float bf16_lo(unsigned packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned packed) { return __uint_as_float(packed & 0xffff0000u); }
 
-// The divisor of a block (its scale) is shared by all its elements, so the correctly rounded
-// quotient x / scale is obtained without a per-element IEEE division sequence:
-//   r  = RN(1 / b)                      one true division per block
-//   q0 = RN(a * r)                      within 1.5 ulp of a / b
-//   q1 = RN(q0 + RN(a - b * q0) * r)    a faithful rounding of a / b
-//   q2 = RN(q1 + (a - b * q1) * r)      = RN(a / b): from a faithful q1 the residual is exact
-//                                         in an FMA and this last step rounds correctly (Markstein)
-// This holds while no intermediate under- or overflows; whoever builds a Divisor sets `fast`
-// only where that is guaranteed for every quotient that matters, and the plain division is
-// taken otherwise.
-// The sign is re-applied at the end because the corrections turn -0 into +0.
-struct Divisor {
-  float b, r;
-  bool fast;
-};
-
-__device__ __forceinline__ float divide(float a, const Divisor& d) {
-  if (!d.fast) return a / d.b;
-  float q = a * d.r;
-  float e = __builtin_fmaf(-q, d.b, a);
-  q = __builtin_fmaf(e, d.r, q);
-  e = __builtin_fmaf(-q, d.b, a);
-  q = __builtin_fmaf(e, d.r, q);
-  return __builtin_copysignf(q, a);
-}
-
-// A divisor shared by many dividends, with the exact-division shortcut described at `divide`
-// above.  It is taken while the divisor lies in [2^-60, 2^60]: every dividend used with it here
-// is either at most a few hundred times the divisor in magnitude or a square root (never
-// subnormal unless zero), so no intermediate of a quotient that matters under- or overflows.
-__device__ __forceinline__ Divisor shared_divisor(float b) {
-  Divisor d;
-  d.b = b;
-  const unsigned e = (__float_as_uint(b) >> 23) & 0xffu;
-  d.fast = e >= 67u && e < 187u;
-  d.r = d.fast ? 1.0f / b : 0.0f;
-  return d;
-}
-
-// The correctly rounded fp32 quotient x / b for many dividends x that share the divisor b, by
-// way of double precision: RN32(RN64(x * rd)) with rd = RN64(1 / b) (any rd within 2^-51
-// relative of 1 / b will do).  Why this is RN32(x / b) exactly: with x and b fp32 (24-bit
-// significands), let m be a midpoint between neighbouring fp32 values near y = x / b, spacing
-// 2^(E-23).  x - m * b is an integer multiple of 2^(E + e_b - 47), so unless it is zero y lies at
-// least 2^(E-48) from m; the double product is within 2^(E-50) of y and so falls on the same side
-// of every midpoint, and the conversion to fp32 rounds it as it would round y.  x = m * b exactly
-// needs a 25-bit m times b to fit x's 24 bits, which forces b to a power of two, where the
-// quotient is exact anyway.  No range restrictions (doubles neither over- nor underflow on fp32
-// inputs), -0 stays -0, three full-rate operations per element against five FMAs plus a
-// sign fix-up for the fp32 recurrence above.
+// The correctly rounded fp32 quotient x / b for many dividends x that share the divisor b (a
+// block's scale or quantisation step, a constant of the optimiser), by way of double precision:
+// RN32(RN64(x * rd)) with rd = RN64(1 / b).  Why this is RN32(x / b) exactly: let m be a midpoint
+// between neighbouring fp32 values near y = x / b, where fp32 values are 2^(E-23) apart.  With x
+// and b fp32 (24-bit significands), x - m * b is an integer multiple of 2^(E + e_b - 47), and it
+// is never zero because m * b has at least 25 significant bits; so y lies at least 2^(E-48) from
+// every midpoint.  The double product is within 2^(E-50) of y, falls on the same side of every
+// midpoint, and its conversion to fp32 rounds it as y would be rounded.  No range restrictions
+// (doubles neither over- nor underflow on fp32 inputs), -0 stays -0, and three full-rate
+// operations per element instead of the twelve or so of the IEEE division sequence.
 __device__ __forceinline__ double shared_reciprocal(float b) { return 1.0 / double(b); }
 __device__ __forceinline__ float exact_quotient(float x, double rd) { return float(double(x) * rd); }
 

@@ -25,11 +25,11 @@ __device__ __forceinline__ void slot_mean(const uint16_t* p, int64_t row_stride,
   for (int q = 0; q < 8; ++q) r[q] = q < ncol ? sum[q] * inv_w : 0.0f;
 }
 
-__device__ __forceinline__ unsigned quant4(float a, float b, float c, float e, const Divisor& d) {
-  const float qa = __builtin_amdgcn_fmed3f(divide(a, d), -kE4M3Max, kE4M3Max);
-  const float qb = __builtin_amdgcn_fmed3f(divide(b, d), -kE4M3Max, kE4M3Max);
-  const float qc = __builtin_amdgcn_fmed3f(divide(c, d), -kE4M3Max, kE4M3Max);
-  const float qe = __builtin_amdgcn_fmed3f(divide(e, d), -kE4M3Max, kE4M3Max);
+__device__ __forceinline__ unsigned quant4(float a, float b, float c, float e, double rd) {
+  const float qa = __builtin_amdgcn_fmed3f(exact_quotient(a, rd), -kE4M3Max, kE4M3Max);
+  const float qb = __builtin_amdgcn_fmed3f(exact_quotient(b, rd), -kE4M3Max, kE4M3Max);
+  const float qc = __builtin_amdgcn_fmed3f(exact_quotient(c, rd), -kE4M3Max, kE4M3Max);
+  const float qe = __builtin_amdgcn_fmed3f(exact_quotient(e, rd), -kE4M3Max, kE4M3Max);
   const int lo = __builtin_amdgcn_cvt_pk_fp8_f32(qa, qb, 0, false);
   return unsigned(__builtin_amdgcn_cvt_pk_fp8_f32(qc, qe, lo, true));
 }
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
     int64_t item_count, const uint16_t* __restrict__ P, int64_t row_stride,
     uint8_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mean_out,
     int64_t elem_base, int64_t scale_off, int W, float inv_w) {
-  __shared__ unsigned wave_max[kQuantThreads / 64];
+  __shared__ unsigned wave_max_lds[kQuantThreads / 64];
   const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
   if (idx >= item_count) return;
   const QItem it = items[item_off + idx];
@@ -85,14 +85,12 @@ __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
   }
   float scale[kQuantLoads];
   if (tile) {
-    unsigned a = max(max(m[0], m[1]), max(m[2], m[3]));
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
-    if ((tid & 63) == 0) wave_max[tid >> 6] = a;
+    unsigned a = wave_max(max(max(m[0], m[1]), max(m[2], m[3])));
+    if ((tid & 63) == 0) wave_max_lds[tid >> 6] = a;
     __syncthreads();
-    a = wave_max[0];
+    a = wave_max_lds[0];
 #pragma unroll
-    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max[w]);
+    for (int w = 1; w < kQuantThreads / 64; ++w) a = max(a, wave_max_lds[w]);
     const float s = __uint_as_float(a) / kE4M3Max;
 #pragma unroll
     for (int i = 0; i < kQuantLoads; ++i) scale[i] = s;
@@ -100,9 +98,7 @@ __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
   } else {
 #pragma unroll
     for (int i = 0; i < kQuantLoads; ++i) {
-      unsigned a = m[i];
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) a = max(a, unsigned(__shfl_xor(int(a), off)));
+      const unsigned a = row16_max(m[i]);
       scale[i] = __uint_as_float(a) / kE4M3Max;
       if ((tid & 15) == 0 && r_in + kQuantRowStep * i < it.count)
         scales[t.scale_base + sl[i].blk - scale_off] = scale[i];
@@ -114,7 +110,7 @@ __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
     if (sl[i].ncol == 0) continue;
     u32x2 c{0, 0};
     if (scale[i] != 0.0f) {
-      const Divisor d = shared_divisor(scale[i]);
+      const double d = shared_reciprocal(scale[i]);
       c.x = quant4(r[i][0], r[i][1], r[i][2], r[i][3], d);
       c.y = quant4(r[i][4], r[i][5], r[i][6], r[i][7], d);
     }

@@ -10,6 +10,9 @@ namespace rs {
 // Tile-table granule: the DBuffer region of every rank is cut into granules of this many
 // elements; the table gives, per granule, the first tensor that ends after the granule's start.
 constexpr int kGranule = 2048;
+// gran_first entries carry this flag when the granule lies wholly inside the tensor they name:
+// a workgroup then knows all of its elements are payload without reading the tensor's record.
+constexpr int32_t kGranWhole = int32_t(1) << 30;
 // A quantisation work item covers at most this many "row slots" of 128 elements:
 // one 128x128 tile, or 128 consecutive 1x128 blocks.
 constexpr int kItemSlots = 128;
@@ -94,7 +97,7 @@ struct TensorHost {
 
 struct HostTables {
   std::vector<TensorDev> tensors;
-  std::vector<int32_t> gran_first;   // world * granules_per_rank
+  std::vector<int32_t> gran_first;   // world * granules_per_rank; tensor index, + kGranWhole
   int64_t granules_per_rank = 0;
   std::vector<QItem> items;          // rank-major
   std::vector<int64_t> item_begin;   // world + 1
@@ -163,6 +166,14 @@ struct rs_shard_batch {
   int rank = 0;
   int count = 0;
   void** ptrs = nullptr;  // device array: count shards, count code buffers, count scale slices
+};
+
+struct rs_partials_batch {
+  const rs_plan* owner = nullptr;
+  int rank = 0;
+  int count = 0;
+  int64_t row_stride = 0;
+  void** ptrs = nullptr;  // device array: count partial buffers, count outputs
 };
 
 struct rs_adam8_batch {

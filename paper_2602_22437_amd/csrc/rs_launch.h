@@ -21,8 +21,10 @@ int scratch_init(int device);
 int launch_pack_staged(const DeviceTables& dev, int n, const void* const* host_ptrs,
                        const int32_t* order, void* dbuf, int64_t S, int64_t gpr,
                        int64_t n_payload_gran, int64_t n_padding_gran, hipStream_t st);
+// batch: null, or a device array [partials | out] of batch_count units reduced in one launch
 int launch_shard_reduce(const DeviceTables& dev, int n, const void* partials, int64_t row_stride,
-                        float* out, int64_t S, int64_t gpr, int rank, int rows, hipStream_t st);
+                        float* out, int64_t S, int64_t gpr, int rank, int rows, void* const* batch,
+                        int batch_count, hipStream_t st);
 int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count, const void* x,
                        uint8_t* codes, float* scales, void* const* batch, int batch_count,
                        int64_t elem_base, int64_t scale_off, hipStream_t st);
@@ -37,6 +39,7 @@ int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t 
 // fp32 constants of one 8-bit Adam step
 struct Adam8Consts {
   float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_size, bc2_sqrt, decay;
+  double bc2_sqrt_rcp;   // 1 / double(bc2_sqrt), correctly rounded: the divisor every element shares
 };
 int launch_adam8_step(const DeviceTables& dev, int64_t item_off, int64_t item_count, const float* grad,
                       float* master, void* param_bf16, int8_t* m_codes, uint8_t* v_codes,

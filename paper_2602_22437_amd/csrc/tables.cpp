@@ -75,6 +75,7 @@ void build_host_tables(const std::vector<TensorHost>& t, int64_t world, int64_t 
         continue;
       }
       out->payload_gran.push_back(GranRef{int32_t(k * gpr + j), f});
+      if (t[f].ell <= start && stop <= t[f].ell + t[f].e) out->gran_first[size_t(k * gpr + j)] = f | kGranWhole;
     }
   }
   out->n_payload_gran = int64_t(out->payload_gran.size());

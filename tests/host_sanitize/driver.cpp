@@ -132,9 +132,13 @@ int main(int argc, char** argv) {
     REQUIRE(h.n_payload_gran + h.n_padding_gran == world * gpr);
     for (int64_t k = 0; k < world; ++k)
       for (int64_t j = 0; j < gpr; ++j) {
-        const int32_t f = h.gran_first[size_t(k * gpr + j)];
+        const int32_t entry = h.gran_first[size_t(k * gpr + j)];
+        const int32_t f = entry & ~rs::kGranWhole;
         REQUIRE(f >= 0 && f <= n);
         const int64_t start = k * S + j * rs::kGranule;
+        const int64_t stop = std::min(start + rs::kGranule, (k + 1) * S);
+        const bool whole = f < n && t[size_t(f)].ell <= start && stop <= t[size_t(f)].ell + t[size_t(f)].e;
+        REQUIRE(whole == ((entry & rs::kGranWhole) != 0));
         if (f < n) REQUIRE(t[size_t(f)].ell + t[size_t(f)].e > start);
         if (f > 0) REQUIRE(t[size_t(f - 1)].ell + t[size_t(f - 1)].e <= start);
       }

@@ -526,6 +526,60 @@ def test_quantize_batch_equals_per_unit_quantize():
         u.close()
 
 
+@pytest.mark.parametrize("long_region", [False, True])
+def test_reduce_batch_equals_per_unit_reduce(long_region):
+    """rs_reduce_batch over several units that share a plan: every unit's mean is within the
+    tolerance of the float64 definition, equals the stated fp32 order bit for bit and equals
+    rs_reduce on the same partials; short regions (256-lane workgroups) and long ones (512)."""
+    if long_region:
+        W, n_units = 3, 3
+        tensors = [(9_000_001, 0, MODE_1x128), (700, 136, MODE_128x128), (16_500_000, 0, MODE_1x128)]
+    else:
+        W, n_units = 6, 5
+        tensors = [(300, 384, MODE_128x128), (1000, 0, MODE_1x128), (257, 130, MODE_128x128), (64, 256, MODE_1x128)]
+    u = Unit(tensors, W)
+    try:
+        assert (-(-u.S // 2048) >= 4096) == long_region
+        stride = u.S + 24          # rows further apart than S, as a strided view would be
+        for rank in (0, W - 1):
+            segs = u.oracle.rank_segments(rank)
+            hosts, devs, outs, singles = [], [], [], []
+            for unit in range(n_units):
+                parts = np.stack([normal_bf16(21, unit, 1, 100 * rank + w, u.S, 1e-3 * (unit + 1)) for w in range(W)])
+                padded = np.zeros((W, stride), dtype=np.uint16)
+                padded[:, :u.S] = parts
+                padded[:, u.S:] = 0x7fc0          # NaN between the rows: must never be read into a sum
+                hosts.append(parts)
+                devs.append(to_dev_bf16(padded.reshape(-1)))
+                outs.append(torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda"))
+                singles.append(torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda"))
+            say(f"reduce_batch rank {rank}: {n_units} units, long={long_region}")
+            batch = B.rs_partials_batch_create(u.plan, rank, devs, stride, outs)
+            B.rs_reduce_batch(u.plan, batch)
+            for unit in range(n_units):
+                B.rs_reduce(u.plan, rank, devs[unit], stride, singles[unit])
+            torch.cuda.synchronize()
+            B.rs_partials_batch_destroy(batch)
+            for unit in range(n_units):
+                got = outs[unit].cpu().numpy()
+                assert np.array_equal(got.view(np.uint32), singles[unit].cpu().numpy().view(np.uint32)), f"unit {unit}"
+                want = OD.shard_reduce(hosts[unit], segs)
+                assert np.all(np.abs(got.astype(np.float64) - want) <= REDUCE_TOL * OD.shard_reduce_abs_sum(hosts[unit]))
+                ordered = OD.shard_reduce_f32_ordered(hosts[unit], segs)
+                assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), f"unit {unit} order"
+        x = torch.zeros(W * stride, dtype=torch.bfloat16, device="cuda")
+        o = torch.zeros(u.S, dtype=torch.float32, device="cuda")
+        for args, code in [((u.plan, W, [x], stride, [o]), B.RS_EINVAL),            # rank out of range
+                           ((u.plan, 0, [x], u.S - 8, [o]), B.RS_EINVAL),           # rows overlap
+                           ((u.plan, 0, [x], stride + 4, [o]), B.RS_EALIGN),        # stride not 16-byte
+                           ((u.plan, 0, [x[1:]], stride, [o]), B.RS_EALIGN)]:       # partials misaligned
+            with pytest.raises(B.RaggedShardError) as e:
+                B.rs_partials_batch_create(*args)
+            assert e.value.code == code
+    finally:
+        u.close()
+
+
 @pytest.mark.parametrize("order", [1, 2, 3])
 def test_reordered_plans_all_ops(order):
     """Plans whose buffer order differs from the caller's tensor order (sorted by block size, by
