@@ -98,6 +98,50 @@ void oc_shard_reduce(const uint16_t* partials, int W, int64_t S, const int64_t* 
   }
 }
 
+/* sum over the W partials of |P[w][i]| in double: the scale of shard_reduce's accepted error */
+void oc_shard_abs_sum(const uint16_t* partials, int W, int64_t S, double* out) {
+  int64_t i;
+#pragma omp parallel for schedule(static)
+  for (i = 0; i < S; ++i) {
+    double acc = 0.0;
+    int w;
+    for (w = 0; w < W; ++w) acc += fabs((double)bf16_to_f32(partials[(int64_t)w * S + i]));
+    out[i] = acc;
+  }
+}
+
+/* The mean in float, in the one stated order that makes the reduction reproducible bit for bit (a
+ * reading: the paper fixes no order): partial w is added, w ascending, to running sum number
+ * w mod 8, all eight starting from +0; the sums combine as ((a0+a1)+(a2+a3))+((a4+a5)+(a6+a7));
+ * the result is multiplied by the float value of 1/W.  Every operation is one rounded float
+ * operation (volatile keeps the compiler from re-associating or widening). */
+void oc_shard_reduce_f32_ordered(const uint16_t* partials, int W, int64_t S, const int64_t* seg_off,
+                                 const int64_t* seg_len, int nseg, float* out) {
+  int64_t i;
+  int s;
+  const float inv = 1.0f / (float)W;
+#pragma omp parallel for schedule(static)
+  for (i = 0; i < S; ++i) out[i] = 0.0f;
+  for (s = 0; s < nseg; ++s) {
+    const int64_t d = seg_off[s], len = seg_len[s];
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < len; ++i) {
+      volatile float a[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      volatile float s01, s23, s45, s67, lo, hi, total;
+      int w;
+      for (w = 0; w < W; ++w) a[w & 7] = a[w & 7] + bf16_to_f32(partials[(int64_t)w * S + d + i]);
+      s01 = a[0] + a[1];
+      s23 = a[2] + a[3];
+      s45 = a[4] + a[5];
+      s67 = a[6] + a[7];
+      lo = s01 + s23;
+      hi = s45 + s67;
+      total = lo + hi;
+      out[d + i] = total * inv;
+    }
+  }
+}
+
 void oc_quantise_matrix(const uint16_t* x, int64_t R, int64_t C, int bh, int bw, uint8_t* codes,
                         float* scales) {
   const int64_t nbr = (R + bh - 1) / bh, nbc = (C + bw - 1) / bw;

@@ -84,6 +84,24 @@ def shard_reduce(partials: np.ndarray, segments: Sequence[Tuple[int, int, int, i
     return out
 
 
+def shard_reduce_f32_ordered(partials: np.ndarray, segments: Sequence[Tuple[int, int, int, int]]) -> np.ndarray:
+    P = np.ascontiguousarray(partials, dtype=np.uint16)
+    W, S = P.shape
+    off = np.asarray([s[2] for s in segments], dtype=np.int64)
+    ln = np.asarray([s[3] for s in segments], dtype=np.int64)
+    out = np.empty(S, dtype=np.float32)
+    lib().oc_shard_reduce_f32_ordered(_p(P), W, C.c_int64(S), _p(off), _p(ln), len(segments), _p(out))
+    return out
+
+
+def shard_reduce_abs_sum(partials: np.ndarray) -> np.ndarray:
+    P = np.ascontiguousarray(partials, dtype=np.uint16)
+    W, S = P.shape
+    out = np.empty(S, dtype=np.float64)
+    lib().oc_shard_abs_sum(_p(P), W, C.c_int64(S), _p(out))
+    return out
+
+
 def quantise_matrix(bits: np.ndarray, bh: int, bw: int) -> Tuple[np.ndarray, np.ndarray]:
     x = np.ascontiguousarray(bits, dtype=np.uint16)
     R, Cc = x.shape

@@ -1,21 +1,25 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (same plans, same entry points, whole-unit launches).
 
-Config 2 (the benched workload) is checked element by element on a whole unit.  Configs 3-5
-are too large for a full CPU pass within a test's time limit, so whole-buffer properties are
-checked on the device (payload preserved, padding zero) and sampled tensors / windows are
-compared element by element with the oracle.  Inputs for configs 3-5 are drawn on the device
-with torch's seeded generator and copied to the host for the oracle."""
+Config 2 is checked element by element on a whole unit against the numpy oracle.  Configs 3-5 are
+checked element by element too, on EVERY tensor of the unit and on the whole region of the rank:
+the unit stays on the device (inputs drawn there with torch's seeded generator), tensors are
+streamed to the host one at a time and compared with the plain-C oracle (oracle/c, which
+tests/test_oracle_c.py holds bit for bit against the numpy oracle); a few tensors and one stretch
+of each reduce also go through the numpy oracle itself.  Every test builds what it needs, so any
+of them can run alone."""
 import numpy as np
 import pytest
 import torch
 
+from oracle import c_oracle as OC
 from oracle import dbuffer as OD
 from oracle import fp8 as OF
 from oracle import plan as OP
 from paper_2602_22437_amd import binding as B
 from workloads import WORKLOADS, gen_params, gen_partial
 
+from fused_check import order_free_fused_check
 from gpu_util import Unit, bits_of, say, to_dev_bf16
 
 pytestmark = pytest.mark.gpu
@@ -27,35 +31,60 @@ REDUCE_TOL = 1e-5
 # ---------------------------------------------------------------------------------------------
 
 class Cfg2:
-    unit = None
-    params = None
-    db_bits = None
-    dbuf = None
-    codes = None
-    scales = None
+    """Unit 0 of configuration 2 on both sides; every stage is built on first use and kept."""
+
+    def __init__(self):
+        self.wl = WORKLOADS[2]
+        say("config 2: generating unit 0 on the host")
+        self.unit = Unit.from_workload(self.wl)
+        self.params = gen_params(self.wl, seed=1)
+        self._packed = self._quantised = None
+
+    def packed(self):
+        """(device DBuffer, oracle DBuffer bits)"""
+        if self._packed is None:
+            u = self.unit
+            say("config 2: pack")
+            dev = [to_dev_bf16(p) for p in self.params]
+            dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+            B.rs_pack(u.plan, u.table(dev), dbuf)
+            torch.cuda.synchronize()
+            self._packed = (dbuf, OD.ragged_pack(self.params, u.oracle.offsets, u.total))
+        return self._packed
+
+    def quantised(self):
+        """(device codes, device scales, oracle codes, oracle scales) of the whole unit"""
+        if self._quantised is None:
+            u = self.unit
+            dbuf, db_bits = self.packed()
+            nb = B.rs_plan_num_scales(u.plan)
+            codes = torch.full((u.total,), 0xAB, dtype=torch.uint8, device="cuda")
+            scales = torch.full((nb,), float("nan"), dtype=torch.float32, device="cuda")
+            say("config 2: quantize all ranks")
+            B.rs_quantize(u.plan, -1, dbuf, codes, scales)
+            torch.cuda.synchronize()
+            say("config 2: oracle quantisation of the whole unit")
+            wc, ws = OF.block_quant_all(u.oracle, db_bits)
+            self._quantised = (codes, scales, wc, ws)
+        return self._quantised
+
+    def close(self):
+        self.unit.close()
+        self._packed = self._quantised = self.params = None
 
 
 @pytest.fixture(scope="module")
 def cfg2():
-    wl = WORKLOADS[2]
-    say("config 2: generating unit 0 on the host")
-    Cfg2.unit = Unit.from_workload(wl)
-    Cfg2.params = gen_params(wl, seed=1)
-    yield Cfg2
-    Cfg2.unit.close()
-    Cfg2.params = Cfg2.db_bits = Cfg2.dbuf = Cfg2.codes = Cfg2.scales = None
+    state = Cfg2()
+    yield state
+    state.close()
+    torch.cuda.empty_cache()
 
 
 def test_config2_pack_and_unpack_bf16(cfg2):
     u = cfg2.unit
-    say("config 2: pack")
-    dev = [to_dev_bf16(p) for p in cfg2.params]
-    dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
-    B.rs_pack(u.plan, u.table(dev), dbuf)
-    torch.cuda.synchronize()
-    want = OD.ragged_pack(cfg2.params, u.oracle.offsets, u.total)
+    dbuf, want = cfg2.packed()
     assert np.array_equal(bits_of(dbuf), want)
-    cfg2.db_bits, cfg2.dbuf = want, dbuf
     say("config 2: unpack_bf16")
     outs = [torch.empty(p.size, dtype=torch.bfloat16, device="cuda") for p in cfg2.params]
     B.rs_unpack_bf16(u.plan, dbuf, u.table(outs))
@@ -64,7 +93,7 @@ def test_config2_pack_and_unpack_bf16(cfg2):
         assert np.array_equal(bits_of(o), p)
 
 
-@pytest.mark.parametrize("rank", [0, 63])
+@pytest.mark.parametrize("rank", [0, 40, 63])       # rank 63 holds padding only
 def test_config2_reduce(cfg2, rank):
     wl, u = WORKLOADS[2], cfg2.unit
     say(f"config 2: reduce rank {rank}, generating {wl.world} partials")
@@ -92,29 +121,25 @@ def test_config2_reduce(cfg2, rank):
     want_c, want_s = OF.block_quant_shard(u.oracle, rank, ordered, f32=True)
     assert np.array_equal(scales.cpu().numpy()[:hi - lo].view(np.uint32), want_s.view(np.uint32))
     assert np.array_equal(codes.cpu().numpy(), want_c)
+    # and against the definition alone, whatever the summation order
+    n = order_free_fused_check(u.oracle, u.specs, rank, lambda a, b: np.ascontiguousarray(parts[:, a:b]),
+                               codes.cpu().numpy(), scales.cpu().numpy()[:hi - lo], f"config 2 rank {rank}", reducer=OC)
+    say(f"config 2: fused reduce + quantise, order-free check on {n} elements")
+    assert n == int(pay.sum())
 
 
 def test_config2_quantize_all_and_by_rank(cfg2):
     u = cfg2.unit
-    assert cfg2.dbuf is not None, "pack test must run first"
-    nb = B.rs_plan_num_scales(u.plan)
-    codes = torch.full((u.total,), 0xAB, dtype=torch.uint8, device="cuda")
-    scales = torch.full((nb,), float("nan"), dtype=torch.float32, device="cuda")
-    say("config 2: quantize all ranks")
-    B.rs_quantize(u.plan, -1, cfg2.dbuf, codes, scales)
-    torch.cuda.synchronize()
-    say("config 2: oracle quantisation of the whole unit")
-    wc, ws = OF.block_quant_all(u.oracle, cfg2.db_bits)
+    dbuf, _ = cfg2.packed()
+    codes, scales, wc, ws = cfg2.quantised()
     assert np.array_equal(scales.cpu().numpy().view(np.uint32), ws.view(np.uint32))
     assert np.array_equal(codes.cpu().numpy(), wc)
-    cfg2.codes, cfg2.scales = codes, scales
-    cfg2.want_codes, cfg2.want_scales = wc, ws
     for k in (0, 4, 63):                     # the launch bench.py times is the rank-0 one
         say(f"config 2: quantize rank {k}")
         lo, hi = B.rs_plan_scale_range(u.plan, k)
         c = torch.full((u.S,), 0xCD, dtype=torch.uint8, device="cuda")
         s = torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda")
-        B.rs_quantize(u.plan, k, cfg2.dbuf[k * u.S:(k + 1) * u.S], c, s)
+        B.rs_quantize(u.plan, k, dbuf[k * u.S:(k + 1) * u.S], c, s)
         torch.cuda.synchronize()
         assert np.array_equal(c.cpu().numpy(), wc[k * u.S:(k + 1) * u.S])
         assert np.array_equal(s.cpu().numpy()[:hi - lo].view(np.uint32), ws[lo:hi].view(np.uint32))
@@ -122,134 +147,29 @@ def test_config2_quantize_all_and_by_rank(cfg2):
 
 def test_config2_dequant_unpack(cfg2):
     u = cfg2.unit
-    assert cfg2.codes is not None, "quantize test must run first"
+    codes, scales, want_codes, want_scales = cfg2.quantised()
     outs = [torch.empty(p.size, dtype=torch.bfloat16, device="cuda") for p in cfg2.params]
     say("config 2: dequant_unpack")
-    B.rs_unpack(u.plan, cfg2.codes, cfg2.scales, u.table(outs))
+    B.rs_unpack(u.plan, codes, scales, u.table(outs))
     torch.cuda.synchronize()
     for i, (spec, l, sb) in enumerate(zip(u.specs, u.oracle.offsets, u.oracle.scale_bases())):
         say(f"config 2: oracle dequantise tensor {i}")
-        want = OF.dequantise_tensor(cfg2.want_codes[l:l + spec.e],
-                                    cfg2.want_scales[sb:sb + spec.num_blocks], spec)
+        want = OF.dequantise_tensor(want_codes[l:l + spec.e], want_scales[sb:sb + spec.num_blocks], spec)
         assert np.array_equal(bits_of(outs[i]), want), f"tensor {i}"
     say("config 2: unpack_f32")
     outs32 = [torch.empty(p.size, dtype=torch.float32, device="cuda") for p in cfg2.params]
-    B.rs_unpack_f32(u.plan, cfg2.codes, cfg2.scales, u.table(outs32))
+    B.rs_unpack_f32(u.plan, codes, scales, u.table(outs32))
     torch.cuda.synchronize()
     for i, (spec, l, sb) in enumerate(zip(u.specs, u.oracle.offsets, u.oracle.scale_bases())):
-        want = OF.dequantise_tensor_f32(cfg2.want_codes[l:l + spec.e],
-                                        cfg2.want_scales[sb:sb + spec.num_blocks], spec)
+        want = OF.dequantise_tensor_f32(want_codes[l:l + spec.e], want_scales[sb:sb + spec.num_blocks], spec)
         assert np.array_equal(outs32[i].cpu().numpy().view(np.uint32), want.view(np.uint32)), f"fp32 tensor {i}"
 
 
-# ---------------------------------------------------------------------------------------------
-# helpers for the sampled configurations
-# ---------------------------------------------------------------------------------------------
-
-def device_params(wl, seed):
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(seed)
-    return [torch.empty(t.numel, dtype=torch.bfloat16, device="cuda").normal_(0, wl.sigma, generator=gen)
-            for t in wl.tensors]
-
-
-def sample_tensors(u, wl, cap):
-    """The tensors compared one by one: those overlapping the rank of interest, the first and
-    the last, those touching a shard boundary among the first 8 ranks, then every 16th."""
-    n = len(u.specs)
-    pick = []
-
-    def add(t):
-        if t not in pick and len(pick) < cap:
-            pick.append(t)
-    for t, _, _, _ in u.oracle.rank_segments(wl.rank):
-        add(t)
-    add(0)
-    add(n - 1)
-    for k in range(1, 9):
-        b = k * u.S
-        for t, (s, l) in enumerate(zip(u.specs, u.oracle.offsets)):
-            if l <= b <= l + s.e:
-                add(t)
-    for t in range(0, n, 16):
-        add(t)
-    return pick
-
-
-def check_pack_window(u, dbuf, src, t):
-    """DBuffer around tensor t (with the padding on both sides) against the oracle pack."""
-    spec, l = u.specs[t], u.oracle.offsets[t]
-    prev_end = 0 if t == 0 else u.oracle.offsets[t - 1] + u.specs[t - 1].e
-    next_start = u.total if t == len(u.specs) - 1 else u.oracle.offsets[t + 1]
-    a = max(prev_end, l - 4096)
-    b = min(next_start, l + spec.e + 4096)
-    want = OD.ragged_pack([bits_of(src[t])], [l - a], b - a)
-    assert np.array_equal(bits_of(dbuf[a:b]), want), f"pack window of tensor {t}"
-
-
-def padding_is_zero_and_payload_kept(u, dbuf, src):
-    """Whole-buffer property on the device: as many non-zeros in the DBuffer as in the sources
-    (so nothing but zeros in the padding, given the sampled tensors match)."""
-    nz_buf = 0
-    v = dbuf.view(torch.int16)
-    step = 1 << 28
-    for a in range(0, v.numel(), step):
-        nz_buf += int(torch.count_nonzero(v[a:a + step]))
-    nz_src = sum(int(torch.count_nonzero(s.view(torch.int16))) for s in src)
-    assert nz_buf == nz_src
-
-
-def gaps_are_zero(u, buf):
-    """Every padding interval of the buffer (between tensors and after the last) is all zero."""
-    flat = buf.view(torch.int16) if buf.dtype == torch.bfloat16 else buf
-    cur = 0
-    for spec, l in zip(u.specs, u.oracle.offsets):
-        if l > cur:
-            assert int(torch.count_nonzero(flat[cur:l])) == 0, f"padding before offset {l}"
-        cur = l + spec.e
-    if cur < u.total:
-        assert int(torch.count_nonzero(flat[cur:])) == 0, "padding at the end of the buffer"
-
-
-def check_reduce_windows(u, wl, rank, partials, out, windows):
-    segs = u.oracle.rank_segments(rank)
-    W, S = wl.world, u.S
-    pv = partials.view(W, S)
-    for a, b in windows:
-        sub = bits_of(pv[:, a:b].contiguous().view(-1)).reshape(W, b - a)
-        local = []
-        for t, so, do, n in segs:
-            x, y = max(do, a), min(do + n, b)
-            if x < y:
-                local.append((t, 0, x - a, y - x))
-        want = OD.shard_reduce(sub, local)
-        got = out[a:b].cpu().numpy()
-        pay = np.zeros(b - a, dtype=bool)
-        for _, _, d, n in local:
-            pay[d:d + n] = True
-        assert np.all(got[~pay] == 0)
-        err = np.abs(got.astype(np.float64) - want)
-        assert np.all(err <= REDUCE_TOL * OD.shard_reduce_abs_sum(sub)), f"window {a}:{b}"
-        ordered = OD.shard_reduce_f32_ordered(sub, local)
-        assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), f"window {a}:{b} order"
-
-
-def reduce_windows(u, rank, count, width):
-    """Windows over the rank's region: its start, its end, every segment edge, evenly spread."""
-    S = u.S
-    pts = {0, max(0, S - width)}
-    for _, _, d, n in u.oracle.rank_segments(rank):
-        for p in (d, d + n):
-            pts.add(min(max(0, p - width // 2) // 8 * 8, max(0, S - width)))
-    for i in range(count):
-        pts.add((S - width) * i // max(1, count - 1) // 8 * 8)
-    return [(p, min(S, p + width)) for p in sorted(pts)]
-
-
-def test_config2_batched_quantize_and_adam_as_the_bench_launches_them(cfg2):
+def test_config2_batched_launches_as_the_bench_launches_them(cfg2):
     """The launch shapes bench.py times on config 2 besides the per-unit ones: rank 0's shard of
-    32 units in ONE block_quant launch, and the same for the 8-bit Adam step; every unit's
-    outputs against the oracle (quantise) or against the per-unit launch (Adam)."""
+    32 units in ONE block_quant launch, the same for the 8-bit Adam step, and rank 0's region of
+    32 units in ONE reduce launch; every unit's outputs against the oracle (quantise, reduce) or
+    against the per-unit launch (Adam)."""
     from workloads import normal_bf16
     u, wl = cfg2.unit, WORKLOADS[2]
     rank, n_units, S = wl.rank, wl.units, cfg2.unit.S
@@ -273,9 +193,34 @@ def test_config2_batched_quantize_and_adam_as_the_bench_launches_them(cfg2):
         oc, os_ = OF.block_quant_shard(u.oracle, rank, host[unit])
         assert np.array_equal(codes[unit].cpu().numpy(), oc), f"unit {unit} codes"
         assert np.array_equal(scales[unit].cpu().numpy().view(np.uint32), os_.view(np.uint32)), f"unit {unit} scales"
+    del shards, codes, scales
+
+    # one reduce launch over the region of 32 units; 4 units through the oracle, all against rs_reduce
+    W = wl.world
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    parts = [torch.empty(W * S, dtype=torch.bfloat16, device="cuda").normal_(0, 1e-3, generator=gen) for _ in range(n_units)]
+    outs = [torch.full((S,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_units)]
+    rb = B.rs_partials_batch_create(u.plan, rank, parts, S, outs)
+    say("config 2: reduce_batch")
+    B.rs_reduce_batch(u.plan, rb)
+    torch.cuda.synchronize()
+    B.rs_partials_batch_destroy(rb)
+    single = torch.empty(S, dtype=torch.float32, device="cuda")
+    segs = u.oracle.rank_segments(rank)
+    for unit in range(n_units):
+        B.rs_reduce(u.plan, rank, parts[unit], S, single)
+        torch.cuda.synchronize()
+        assert torch.equal(single.view(torch.int32), outs[unit].view(torch.int32)), f"unit {unit}: batch != rs_reduce"
+        if unit % 8 == 0:
+            sub = bits_of(parts[unit]).reshape(W, S)
+            got = outs[unit].cpu().numpy()
+            err = np.abs(got.astype(np.float64) - OC.shard_reduce(sub, segs))
+            assert np.all(err <= REDUCE_TOL * OC.shard_reduce_abs_sum(sub)), f"unit {unit}"
+            assert np.array_equal(got.view(np.uint32), OC.shard_reduce_f32_ordered(sub, segs).view(np.uint32))
+    del parts, outs
 
     slo, shi = B.rs_plan_state_range(u.plan, rank)
-    gen = torch.Generator(device="cuda")
     gen.manual_seed(99)
 
     def state():
@@ -310,6 +255,81 @@ def test_config2_batched_quantize_and_adam_as_the_bench_launches_them(cfg2):
 
 
 # ---------------------------------------------------------------------------------------------
+# helpers for the configurations that stay on the device
+# ---------------------------------------------------------------------------------------------
+
+def device_params(wl, seed):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    return [torch.empty(t.numel, dtype=torch.bfloat16, device="cuda").normal_(0, wl.sigma, generator=gen)
+            for t in wl.tensors]
+
+
+def gaps_are_zero(u, buf):
+    """Every padding interval of the buffer (between tensors and after the last) is all zero."""
+    flat = buf.view(torch.int16) if buf.dtype == torch.bfloat16 else buf
+    cur = 0
+    for l, t in sorted(zip(u.oracle.offsets, range(len(u.specs)))):
+        if l > cur:
+            assert int(torch.count_nonzero(flat[cur:l])) == 0, f"padding before offset {l}"
+        cur = l + u.specs[t].e
+    if cur < u.total:
+        assert int(torch.count_nonzero(flat[cur:])) == 0, "padding at the end of the buffer"
+
+
+def block_shape(spec):
+    """(rows, cols, block height, block width) of a tensor as the C oracle's matrix quantiser sees it"""
+    if spec.cols == 0:
+        return 1, spec.rows, 1, 128
+    return (spec.rows, spec.cols, 128, 128) if spec.mode == OP.BLOCK_128x128 else (spec.rows, spec.cols, 1, 128)
+
+
+def check_reduce_whole_region(u, wl, rank, partials, out, chunk, numpy_too=True):
+    """The whole region of the rank, streamed to the host in column chunks: zero on padding, within
+    the tolerance of the float64 mean, bit-equal to the stated fp32 order (C oracle; the first
+    chunk that holds payload also through the numpy oracle).  Returns the elements compared."""
+    segs = u.oracle.rank_segments(rank)
+    W, S = wl.world, u.S
+    pv = partials.view(W, S)
+    done = 0
+    for a in range(0, S, chunk):
+        b = min(S, a + chunk)
+        local = []
+        for t, so, do, n in segs:
+            x, y = max(do, a), min(do + n, b)
+            if x < y:
+                local.append((t, 0, x - a, y - x))
+        got = out[a:b].cpu().numpy()
+        if not local:
+            assert not got.any(), f"padding {a}:{b}"
+            done += b - a
+            continue
+        sub = bits_of(pv[:, a:b].contiguous().view(-1)).reshape(W, b - a)
+        pay = np.zeros(b - a, dtype=bool)
+        for _, _, d, n in local:
+            pay[d:d + n] = True
+        assert np.all(got[~pay] == 0), f"padding inside {a}:{b}"
+        want = OC.shard_reduce(sub, local)
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        # the C mean is the float64 mean rounded to fp32: half an ulp of slack on top of the bound
+        bound = REDUCE_TOL * OC.shard_reduce_abs_sum(sub) + np.abs(want).astype(np.float64) * 2.0 ** -24
+        assert np.all(err <= bound), f"chunk {a}:{b}"
+        ordered = OC.shard_reduce_f32_ordered(sub, local)
+        assert np.array_equal(got.view(np.uint32), ordered.view(np.uint32)), f"chunk {a}:{b} order"
+        if numpy_too:
+            w = min(b - a, 1 << 16)
+            clip = [(t, 0, d, min(n, w - d)) for t, _, d, n in local if d < w]
+            if clip:
+                sw = np.ascontiguousarray(sub[:, :w])
+                assert np.all(np.abs(got[:w].astype(np.float64) - OD.shard_reduce(sw, clip)) <=
+                              REDUCE_TOL * OD.shard_reduce_abs_sum(sw)), "numpy oracle"
+                assert np.array_equal(got[:w].view(np.uint32), OD.shard_reduce_f32_ordered(sw, clip).view(np.uint32))
+                numpy_too = False
+        done += b - a
+    return done
+
+
+# ---------------------------------------------------------------------------------------------
 # config 3: whole-matrix sharding (Muon / Shampoo style), W = 32, bf16 only
 # ---------------------------------------------------------------------------------------------
 
@@ -322,22 +342,23 @@ def test_config3_whole_matrix_pack_reduce_unpack():
         dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
         B.rs_pack(u.plan, u.table(src), dbuf)
         torch.cuda.synchronize()
-        for t in range(len(u.specs)):
-            check_pack_window(u, dbuf, src, t)
-        padding_is_zero_and_payload_kept(u, dbuf, src)
+        for t, (spec, l) in enumerate(zip(u.specs, u.oracle.offsets)):   # every tensor, on the host
+            want = OD.ragged_pack([bits_of(src[t])], [0], spec.e)
+            assert np.array_equal(bits_of(dbuf[l:l + spec.e]), want), f"tensor {t}"
+        gaps_are_zero(u, dbuf)
         say("config 3: unpack_bf16")
         outs = [torch.full_like(s, 1.0) for s in src]
         B.rs_unpack_bf16(u.plan, dbuf, u.table(outs))
         torch.cuda.synchronize()
-        for o, s in zip(outs, src):
-            assert torch.equal(o.view(torch.int16), s.view(torch.int16))
+        for t, (o, s) in enumerate(zip(outs, src)):
+            assert np.array_equal(bits_of(o), bits_of(s)), f"tensor {t}"
         del outs, dbuf
         # every matrix sits whole on one rank
         for t, (spec, l) in enumerate(zip(u.specs, u.oracle.offsets)):
             if spec.cols:
                 assert l // u.S == (l + spec.e - 1) // u.S
         for rank in (0, 3, 31):                      # rank 31 holds nothing: all zeros, no reads
-            say(f"config 3: reduce rank {rank}")
+            say(f"config 3: reduce rank {rank}, whole region")
             gen = torch.Generator(device="cuda")
             gen.manual_seed(100 + rank)
             partials = torch.empty(wl.world * u.S, dtype=torch.bfloat16, device="cuda").normal_(0, 1e-3, generator=gen)
@@ -347,104 +368,192 @@ def test_config3_whole_matrix_pack_reduce_unpack():
             if not u.oracle.rank_segments(rank):
                 assert int(torch.count_nonzero(out)) == 0
             else:
-                check_reduce_windows(u, wl, rank, partials, out, reduce_windows(u, rank, 24, 16384))
+                n = check_reduce_whole_region(u, wl, rank, partials, out, 1 << 22)
+                assert n == u.S
             del partials, out
         with pytest.raises(B.RaggedShardError) as e:
             B.rs_quantize(u.plan, 0, src[0], src[0], src[0])
         assert e.value.code == B.RS_EUNSUPPORTED
     finally:
         u.close()
+        torch.cuda.empty_cache()
 
 
 # ---------------------------------------------------------------------------------------------
-# configs 4 and 5: MoE units, all four ops, sampled element-by-element parity
+# configs 4 and 5: MoE units, all four ops, every tensor element by element
 # ---------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("idx,cap", [(4, 10), (5, 8)])
-def test_moe_units_sampled(idx, cap):
-    wl = WORKLOADS[idx]
-    u = Unit.from_workload(wl)
-    try:
+class MoE:
+    """One MoE unit on the device after pack, quantise (all ranks) and dequant_unpack."""
+    live = None
+
+    def __init__(self, idx):
+        if MoE.live is not None:          # one large unit at a time on the card
+            MoE.live.close()
+        MoE.live = self
+        self.idx = idx
+        self.wl = wl = WORKLOADS[idx]
+        self.u = u = Unit.from_workload(wl)
         say(f"config {idx}: {len(u.specs)} tensors, W={wl.world}, S={u.S}, total={u.total}")
-        src = device_params(wl, 10 + idx)
-        pick = sample_tensors(u, wl, cap)
-        share = sum(u.specs[t].e for t in pick) / u.oracle.payload
-        say(f"config {idx}: sampled tensors {pick} ({100 * share:.1f} % of the unit's elements)")
-        dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
-        B.rs_pack(u.plan, u.table(src), dbuf)
-        torch.cuda.synchronize()
-        for t in pick:
-            check_pack_window(u, dbuf, src, t)
-        padding_is_zero_and_payload_kept(u, dbuf, src)
-        gaps_are_zero(u, dbuf)
-
+        self.src = device_params(wl, 10 + idx)
+        self.dbuf = torch.full((u.total,), -1, dtype=torch.int16, device="cuda").view(torch.bfloat16)
+        B.rs_pack(u.plan, u.table(self.src), self.dbuf)
         nb = B.rs_plan_num_scales(u.plan)
-        codes = torch.full((u.total,), 0xAB, dtype=torch.uint8, device="cuda")
-        scales = torch.full((nb,), float("nan"), dtype=torch.float32, device="cuda")
+        self.codes = torch.full((u.total,), 0xAB, dtype=torch.uint8, device="cuda")
+        self.scales = torch.full((nb,), float("nan"), dtype=torch.float32, device="cuda")
         say(f"config {idx}: quantize all ranks, nb={nb}")
-        B.rs_quantize(u.plan, -1, dbuf, codes, scales)
-        torch.cuda.synchronize()
-        assert not bool(torch.isnan(scales).any())
-        k = wl.rank
-        lo, hi = B.rs_plan_scale_range(u.plan, k)
-        say(f"config {idx}: quantize rank {k} alone")
-        c_r = torch.full((u.S,), 0xCD, dtype=torch.uint8, device="cuda")
-        s_r = torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda")
-        B.rs_quantize(u.plan, k, dbuf[k * u.S:(k + 1) * u.S], c_r, s_r)
-        torch.cuda.synchronize()
-        assert torch.equal(c_r, codes[k * u.S:(k + 1) * u.S])
-        assert torch.equal(s_r[:hi - lo].view(torch.int32), scales[lo:hi].view(torch.int32))
-
-        dst = [torch.empty_like(s) for s in src]
+        B.rs_quantize(u.plan, -1, self.dbuf, self.codes, self.scales)
+        self.dst = [torch.empty_like(s) for s in self.src]
         say(f"config {idx}: dequant_unpack")
-        B.rs_unpack(u.plan, codes, scales, u.table(dst))
+        B.rs_unpack(u.plan, self.codes, self.scales, u.table(self.dst))
         torch.cuda.synchronize()
-        sb = u.oracle.scale_bases()
-        for t in pick:
-            spec, l = u.specs[t], u.oracle.offsets[t]
-            say(f"config {idx}: oracle quantise/dequantise tensor {t} ({spec.rows}x{spec.cols})")
-            wc, ws = OF.quantise_tensor(bits_of(src[t]), spec)
-            assert np.array_equal(codes[l:l + spec.e].cpu().numpy(), wc), f"codes of tensor {t}"
-            assert np.array_equal(scales[sb[t]:sb[t + 1]].cpu().numpy().view(np.uint32), ws.view(np.uint32))
-            assert np.array_equal(bits_of(dst[t]), OF.dequantise_tensor(wc, ws, spec)), f"unpack of tensor {t}"
-        gaps_are_zero(u, codes)
-        del dst
-        say(f"config {idx}: reduce rank {k} with {wl.world} partials")
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(77)
-        partials = torch.empty(wl.world * u.S, dtype=torch.bfloat16, device="cuda").normal_(0, 1e-3, generator=gen)
-        out = torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda")
-        B.rs_reduce(u.plan, k, partials, u.S, out)
-        torch.cuda.synchronize()
-        assert not bool(torch.isnan(out).any())
-        check_reduce_windows(u, wl, k, partials, out, reduce_windows(u, k, 12, 4096))
+        self.sb = u.oracle.scale_bases()
 
-        say(f"config {idx}: fused reduce + quantise of rank {k}")
-        c_f = torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda")
-        s_f = torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda")
-        mean = torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda")
-        B.rs_reduce_quantize(u.plan, k, partials, u.S, c_f, s_f, mean)
-        torch.cuda.synchronize()
-        assert torch.equal(mean.view(torch.int32), out.view(torch.int32)), "fused mean != rs_reduce"
-        assert not bool(torch.isnan(s_f[:hi - lo]).any())
-        # whole rows of tiles against the oracle: the first and the last of every tiled segment
-        rows_2d = partials.view(wl.world, u.S)
-        sb = u.oracle.scale_bases()
-        for t, src_off, dst_off, n in u.oracle.rank_segments(k):
-            spec = u.specs[t]
-            if spec.mode != OP.BLOCK_128x128:
-                continue
-            C, g = spec.cols, 128 * spec.cols
-            n_rows_of_tiles = -(-n // g)
-            for br in sorted({0, n_rows_of_tiles - 1}):
-                a, b = dst_off + br * g, min(dst_off + (br + 1) * g, dst_off + n)
-                say(f"config {idx}: oracle mean and codes of tensor {t}, row of tiles {src_off // g + br}")
-                win = rows_2d[:, a:b].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-                want_mean = OD.shard_reduce_f32_ordered(win, [(0, 0, 0, b - a)])
-                wc, ws = OF.quantise_matrix_f32(want_mean.reshape(-1, C), 128, 128)
-                assert np.array_equal(c_f[a:b].cpu().numpy(), wc.reshape(-1)), f"fused codes, tensor {t}"
-                s0 = sb[t] + (src_off // g + br) * spec.nbc - lo
-                assert np.array_equal(s_f[s0:s0 + spec.nbc].cpu().numpy().view(np.uint32),
-                                      ws.reshape(-1).view(np.uint32)), f"fused scales, tensor {t}"
-    finally:
-        u.close()
+    def close(self):
+        if self.u is not None:
+            self.u.close()
+        self.u = self.src = self.dbuf = self.codes = self.scales = self.dst = None
+        if MoE.live is self:
+            MoE.live = None
+        torch.cuda.empty_cache()
+
+
+_moe_cache = {}
+
+
+def moe(idx):
+    st = _moe_cache.get(idx)
+    if st is None or st.u is None:
+        st = _moe_cache[idx] = MoE(idx)
+    return st
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _release_moe_units():
+    yield
+    for st in _moe_cache.values():
+        st.close()
+    _moe_cache.clear()
+
+
+def check_tensor(st, t, numpy_too=False):
+    """Pack, codes, scales and dequantised values of tensor t against the oracle, every element."""
+    u = st.u
+    spec, l = u.specs[t], u.oracle.offsets[t]
+    src = bits_of(st.src[t])
+    assert np.array_equal(bits_of(st.dbuf[l:l + spec.e]), OC.ragged_pack([src], [0], spec.e)), f"pack of tensor {t}"
+    R, C, bh, bw = block_shape(spec)
+    wc, ws = OC.quantise_matrix(src.reshape(R, C), bh, bw)
+    assert np.array_equal(st.codes[l:l + spec.e].cpu().numpy(), wc.reshape(-1)), f"codes of tensor {t}"
+    got_s = st.scales[st.sb[t]:st.sb[t + 1]].cpu().numpy()
+    assert np.array_equal(got_s.view(np.uint32), ws.reshape(-1).view(np.uint32)), f"scales of tensor {t}"
+    want = OC.dequantise_matrix(wc, ws, bh, bw)
+    assert np.array_equal(bits_of(st.dst[t]), want.reshape(-1)), f"unpack of tensor {t}"
+    if numpy_too:       # the numpy oracle itself on this tensor
+        nc, ns = OF.quantise_tensor(src, spec)
+        assert np.array_equal(nc, wc.reshape(-1)) and np.array_equal(ns.view(np.uint32), ws.reshape(-1).view(np.uint32))
+        assert np.array_equal(OF.dequantise_tensor(nc, ns, spec), want.reshape(-1))
+    return spec.e
+
+
+MOE_CHUNKS = {4: 4, 5: 8}
+
+
+@pytest.mark.parametrize("idx,chunk", [(i, c) for i in (4, 5) for c in range(MOE_CHUNKS[i])])
+def test_moe_unit_every_tensor(idx, chunk):
+    """Tensors chunk, chunk + k, chunk + 2k, ... of the unit (k chunks cover all of them)."""
+    st = moe(idx)
+    u, wl = st.u, st.wl
+    n = len(u.specs)
+    mine = list(range(chunk, n, MOE_CHUNKS[idx]))
+    # through the numpy oracle as well: the first tensor of the chunk, and in configuration 5 the
+    # shared expert's row-block matrices (the only 1x128 blocks on matrices in the configurations)
+    also = {mine[0]} | ({768, 769, 770} & set(mine) if idx == 5 else set())
+    done = 0
+    for i, t in enumerate(mine):
+        done += check_tensor(st, t, numpy_too=t in also)
+        if i % 32 == 0:
+            say(f"config {idx} chunk {chunk}: tensor {t} done ({i + 1} of {len(mine)})")
+    say(f"config {idx} chunk {chunk}: {len(mine)} tensors, {done} elements = "
+        f"{100.0 * done / u.oracle.payload:.1f} % of the unit compared element by element "
+        f"(all chunks together: 100 %)")
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_moe_unit_padding_and_rank_launch(idx):
+    st = moe(idx)
+    u, wl = st.u, st.wl
+    gaps_are_zero(u, st.dbuf)
+    gaps_are_zero(u, st.codes)
+    assert not bool(torch.isnan(st.scales).any())
+    k = wl.rank
+    lo, hi = B.rs_plan_scale_range(u.plan, k)
+    say(f"config {idx}: quantize rank {k} alone")
+    c_r = torch.full((u.S,), 0xCD, dtype=torch.uint8, device="cuda")
+    s_r = torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda")
+    B.rs_quantize(u.plan, k, st.dbuf[k * u.S:(k + 1) * u.S], c_r, s_r)
+    torch.cuda.synchronize()
+    assert torch.equal(c_r, st.codes[k * u.S:(k + 1) * u.S])
+    assert torch.equal(s_r[:hi - lo].view(torch.int32), st.scales[lo:hi].view(torch.int32))
+    # the tensors that touch a rank boundary among the first 8 ranks, the rank of interest, and the
+    # ends of the unit lie in the chunks above; name them so a reader can see they are covered
+    touching = sorted({t for kk in range(1, 9) for t, (s, l) in enumerate(zip(u.specs, u.oracle.offsets))
+                       if l <= kk * u.S <= l + s.e} | {t for t, _, _, _ in u.oracle.rank_segments(k)} | {0, len(u.specs) - 1})
+    say(f"config {idx}: boundary / rank-of-interest tensors {touching} are among the tensors compared")
+
+
+@pytest.mark.parametrize("idx", [4, 5])
+def test_moe_unit_reduce_whole_region(idx):
+    st = moe(idx)
+    u, wl = st.u, st.wl
+    k = wl.rank
+    lo, hi = B.rs_plan_scale_range(u.plan, k)
+    say(f"config {idx}: reduce rank {k} with {wl.world} partials, whole region")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    partials = torch.empty(wl.world * u.S, dtype=torch.bfloat16, device="cuda").normal_(0, 1e-3, generator=gen)
+    out = torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda")
+    B.rs_reduce(u.plan, k, partials, u.S, out)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any())
+    chunk = max(2048, (1 << 28) // wl.world // 2048 * 2048)        # 512 MB of partials per chunk
+    n = check_reduce_whole_region(u, wl, k, partials, out, chunk)
+    say(f"config {idx}: reduce compared on {n} of {u.S} elements of the region")
+    assert n == u.S
+
+    say(f"config {idx}: fused reduce + quantise of rank {k}")
+    c_f = torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda")
+    s_f = torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda")
+    mean = torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda")
+    B.rs_reduce_quantize(u.plan, k, partials, u.S, c_f, s_f, mean)
+    torch.cuda.synchronize()
+    assert torch.equal(mean.view(torch.int32), out.view(torch.int32)), "fused mean != rs_reduce"
+    assert not bool(torch.isnan(s_f[:hi - lo]).any())
+    # every tiled segment of the region against the oracle's quantisation of the ordered mean
+    # (numpy, fp32 input), a row of tiles at a time on the first and last rows of tiles, and the
+    # whole region against the definition alone (order-free)
+    rows_2d = partials.view(wl.world, u.S)
+    sb = u.oracle.scale_bases()
+    for t, src_off, dst_off, n_seg in u.oracle.rank_segments(k):
+        spec = u.specs[t]
+        if spec.mode != OP.BLOCK_128x128:
+            continue
+        C, g = spec.cols, 128 * spec.cols
+        n_rows_of_tiles = -(-n_seg // g)
+        for br in sorted({0, n_rows_of_tiles - 1}):
+            a, b = dst_off + br * g, min(dst_off + (br + 1) * g, dst_off + n_seg)
+            win = rows_2d[:, a:b].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            want_mean = OD.shard_reduce_f32_ordered(win, [(0, 0, 0, b - a)])
+            wc, ws = OF.quantise_matrix_f32(want_mean.reshape(-1, C), 128, 128)
+            assert np.array_equal(c_f[a:b].cpu().numpy(), wc.reshape(-1)), f"fused codes, tensor {t}"
+            s0 = sb[t] + (src_off // g + br) * spec.nbc - lo
+            assert np.array_equal(s_f[s0:s0 + spec.nbc].cpu().numpy().view(np.uint32),
+                                  ws.reshape(-1).view(np.uint32)), f"fused scales, tensor {t}"
+    codes_h, scales_h = c_f.cpu().numpy(), s_f.cpu().numpy()[:hi - lo]
+
+    def get_parts(a, b):
+        return bits_of(rows_2d[:, a:b].contiguous().view(-1)).reshape(wl.world, b - a)
+    checked = order_free_fused_check(u.oracle, u.specs, k, get_parts, codes_h, scales_h, f"config {idx} rank {k}",
+                                     reducer=OC)
+    assert checked == sum(seg[3] for seg in u.oracle.rank_segments(k))
+    say(f"config {idx}: fused reduce + quantise, order-free check on {checked} elements (the rank's whole payload)")

@@ -68,6 +68,22 @@ def test_pack_and_reduce_agree():
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+@pytest.mark.parametrize("W", [1, 3, 8, 9, 64, 100])
+def test_ordered_mean_and_abs_sum_agree(W):
+    """The C statements of the stated-order fp32 mean and of the error scale against the numpy
+    ones, bit for bit, on a region with padding between two payload segments."""
+    S = 5000
+    parts = np.stack([normal_bf16(13, W, 1, w, S, 1e-3) for w in range(W)])
+    parts[:, 7] = 0x7F00                        # large magnitudes: cancellation and rounding at work
+    parts[W // 2, 7] = 0xFF00
+    segs = [(0, 0, 16, 2000), (1, 0, 2500, 2400)]
+    a, b = D.shard_reduce_f32_ordered(parts, segs), OC.shard_reduce_f32_ordered(parts, segs)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.array_equal(D.shard_reduce_abs_sum(parts), OC.shard_reduce_abs_sum(parts))
+    x, y = D.shard_reduce(parts, segs), OC.shard_reduce(parts, segs)
+    assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+
+
 def test_thread_count_does_not_change_results():
     bits = normal_bf16(4, 0, 2, 0, 384 * 512, 0.02).reshape(384, 512)
     default = OC.num_threads()

@@ -324,3 +324,37 @@ def test_fused_reduce_quantise_is_the_composition_and_stays_near_the_mean():
         for _, _, d, n in segs:
             pay[d:d + n] = True
         assert np.all(codes[~pay] == 0) and np.all(mean[~pay] == 0)
+
+
+def test_fused_reduce_quantise_against_the_definition_alone():
+    """The fused function's scales and codes held against the float64 mean with no summation order
+    assumed (the check the GPU tests apply at full size), on the toy unit and on a unit with row
+    blocks, a 1-D tensor and ragged edges; and the check does catch a planted mistake (a dropped
+    partial, a sum in place of the mean, a scale from the wrong block)."""
+    from fused_check import order_free_fused_check
+    from workloads import gen_partial, normal_bf16
+    wl, pl = toy_plan()
+    ragged = [P.TensorSpec(300, 384, P.BLOCK_128x128), P.TensorSpec(1000, 0, P.BLOCK_1x128),
+              P.TensorSpec(257, 136, P.BLOCK_128x128), P.TensorSpec(64, 200, P.BLOCK_1x128)]
+    pr = P.make_plan(ragged, 3)
+    for plan, W, draw in ((pl, wl.world, lambda w, S: gen_partial(wl, 4, w, S)),
+                          (pr, 3, lambda w, S: normal_bf16(8, 3, 1, w, S, 1e-3))):
+        for k in range(plan.m):
+            parts = np.stack([draw(w, plan.S) for w in range(W)])
+            codes, scales, _ = F.reduce_quant_shard(plan, k, parts)
+            get = lambda a, b: np.ascontiguousarray(parts[:, a:b])
+            n = order_free_fused_check(plan, plan.specs, k, get, codes, scales, "oracle")
+            assert n == sum(s[3] for s in plan.rank_segments(k))
+            if n == 0:
+                continue
+            # planted mistakes must be caught
+            dropped = parts.copy()
+            dropped[W - 1] = 0
+            c2, s2, _ = F.reduce_quant_shard(plan, k, dropped)
+            with pytest.raises(AssertionError):
+                order_free_fused_check(plan, plan.specs, k, get, c2, s2, "dropped partial")
+            with pytest.raises(AssertionError):
+                order_free_fused_check(plan, plan.specs, k, get, codes, scales * np.float32(W), "sum, not mean")
+            if scales.size > 2:
+                with pytest.raises(AssertionError):
+                    order_free_fused_check(plan, plan.specs, k, get, codes, np.roll(scales, 1), "scales shifted")
