@@ -61,7 +61,10 @@ enum {
   RS_ORDER_DEFAULT = 0,     /* the order of the descriptor array */
   RS_ORDER_BLOCK_SIZE = 1,  /* stable sort by g_t, ascending */
   RS_ORDER_SHAPE = 2,       /* stable sort by (element count, rows, cols), ascending */
-  RS_ORDER_BEST = 3         /* all three; the smallest S wins, the earlier order on ties */
+  RS_ORDER_BEST = 3,        /* all three; the smallest S wins, the earlier order on ties */
+  RS_UNITS_LISTING = 256    /* flag, OR-ed into an order: search only the candidate units of Algorithm
+                               1's listing (the running LCM over the ascending distinct block sizes,
+                               g_coll first) instead of the wider set rs_plan_create describes */
 };
 
 typedef struct rs_tensor_desc {
@@ -108,8 +111,9 @@ const char* rs_strerror(int code);
  * rs_plan_destroy.  Errors: RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM. */
 int rs_plan_create(const rs_tensor_desc* descs, int n, int world, int align_bytes,
                    int min_itemsize, int tensor_align_elems, rs_plan** out);
-/* The same with a choice of tensor order (RS_ORDER_*).  Tensors keep the caller's indices in
- * every query and pointer table; only their positions in the buffer change. */
+/* The same with a choice of tensor order (RS_ORDER_*, optionally | RS_UNITS_LISTING for the
+ * algorithm exactly as listed).  Tensors keep the caller's indices in every query and pointer
+ * table; only their positions in the buffer change. */
 int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int align_bytes,
                            int min_itemsize, int tensor_align_elems, int order, rs_plan** out);
 /* The buffer of a group placed RaggedShard(r_t): every block of tensor t on device roots[t]

@@ -198,8 +198,12 @@ def dp_segments(tensors: Sequence[Tuple[int, int]], offsets: Sequence[int], S: i
 # Outer search of Algorithm 1
 # --------------------------------------------------------------------------------------
 
-def candidate_units(tensors: Sequence[Tuple[int, int]], g_coll: int) -> List[int]:
-    """The units whose multiples are searched.  Algorithm 1's listing and the text around it
+UNITS_ALL, UNITS_LISTING = 0, 1
+
+
+def candidate_units(tensors: Sequence[Tuple[int, int]], g_coll: int, units: int = UNITS_ALL) -> List[int]:
+    """The units whose multiples are searched.  units = UNITS_LISTING keeps to Algorithm 1 as
+    listed (the first family below, g_coll included); the default takes all three.  Algorithm 1's listing and the text around it
     describe two different families; both are taken (every result passes CheckValidShard, so
     more candidates can only lower S*):
       * the listing: g_coll, then the running LCM over the distinct block sizes, ascending;
@@ -208,22 +212,24 @@ def candidate_units(tensors: Sequence[Tuple[int, int]], g_coll: int) -> List[int
         largest first (equal counts keep the list order) - one unit per prefix;
       * and, since the set of tensors that contain a whole shard may be neither kind of prefix,
         the smallest such sets as well: lcm(g_coll, g) for every distinct block size on its own."""
-    units = [g_coll]
+    found = [g_coll]
     g = g_coll
     for gp in sorted({g_t for _, g_t in tensors}):
         g = lcm(g, gp)
-        if g not in units:
-            units.append(g)
+        if g not in found:
+            found.append(g)
+    if units == UNITS_LISTING:
+        return found
     g = g_coll
     for _, gp in sorted(tensors, key=lambda eg: -eg[0]):     # sorted() is stable
         g = lcm(g, gp)
-        if g not in units:
-            units.append(g)
+        if g not in found:
+            found.append(g)
     for gp in sorted({g_t for _, g_t in tensors}):
         g = lcm(g_coll, gp)
-        if g not in units:
-            units.append(g)
-    return units
+        if g not in found:
+            found.append(g)
+    return found
 
 
 def min_feasible_multiple(tensors, m: int, c: int, A: int, start: StartFn = smallest_start) -> int:
@@ -241,14 +247,14 @@ def min_feasible_multiple(tensors, m: int, c: int, A: int, start: StartFn = smal
 
 
 def plan_shard_size(tensors: Sequence[Tuple[int, int]], m: int, g_coll: int, A: int,
-                    start: StartFn = smallest_start) -> int:
+                    start: StartFn = smallest_start, units: int = UNITS_ALL) -> int:
     """S* of Algorithm 1 for the given tensor order."""
     if m <= 0 or g_coll <= 0 or A <= 0 or g_coll % A != 0 or not tensors:
         raise ValueError("bad plan arguments")
     total = sum(ceil_div(e, A) * A for e, _ in tensors)
     cap = ceil_div(total, g_coll) * g_coll     # one-shard size; larger units cannot win
     best = None
-    for c in candidate_units(tensors, g_coll):
+    for c in candidate_units(tensors, g_coll, units):
         if c > cap:
             continue
         s = min_feasible_multiple(tensors, m, c, A, start)
@@ -378,19 +384,19 @@ def tensor_order(specs: Sequence[TensorSpec], order: int) -> List[int]:
 
 def make_plan(specs: Sequence[TensorSpec], m: int, align_bytes: int = 16, min_itemsize: int = 1,
               tensor_align: Optional[int] = None, start: StartFn = smallest_start,
-              order: int = ORDER_DEFAULT) -> Plan:
+              order: int = ORDER_DEFAULT, units: int = UNITS_ALL) -> Plan:
     """plan(): S* by Algorithm 1, then the canonical (earliest-start) layout at S*."""
     if align_bytes % min_itemsize != 0:
         raise ValueError("alignment must be a multiple of the item size")
     g_coll = align_bytes // min_itemsize
     A = g_coll if tensor_align is None else tensor_align
     if order == ORDER_BEST:
-        plans = [make_plan(specs, m, align_bytes, min_itemsize, tensor_align, start, o)
+        plans = [make_plan(specs, m, align_bytes, min_itemsize, tensor_align, start, o, units)
                  for o in (ORDER_DEFAULT, ORDER_BLOCK_SIZE, ORDER_SHAPE)]
         return min(plans, key=lambda p: p.S)                              # min() keeps the first of equals
     perm = tensor_order(specs, order)
     tensors = [(specs[t].e, specs[t].g) for t in perm]
-    S = plan_shard_size(tensors, m, g_coll, A, start)
+    S = plan_shard_size(tensors, m, g_coll, A, start, units)
     placed = greedy_layout(tensors, S, A, start)
     assert placed is not None and placed[-1] + tensors[-1][0] <= m * S
     offsets = [0] * len(specs)

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libraggedsh
 
 RS_BLOCK_1x128, RS_BLOCK_128x128, RS_BLOCK_WHOLE, RS_BLOCK_EXPLICIT, RS_BLOCK_32x32 = 0, 1, 2, 3, 4
 RS_ORDER_DEFAULT, RS_ORDER_BLOCK_SIZE, RS_ORDER_SHAPE, RS_ORDER_BEST = 0, 1, 2, 3
+RS_UNITS_LISTING = 256
 RS_OK, RS_EINVAL, RS_EOVERFLOW, RS_ENOMEM, RS_EALIGN, RS_EUNSUPPORTED, RS_EHIP, RS_ENOTUPLOADED, RS_ETOOBIG = (
     0, -1, -2, -3, -4, -5, -6, -7, -8)
 RS_NOALLOC_MAX_TENSORS = 4096

@@ -156,6 +156,8 @@ int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int al
                            int min_itemsize, int tensor_align_elems, int order, rs_plan** out) {
   if (!out) return RS_EINVAL;
   *out = nullptr;
+  const bool listing_only = (order & RS_UNITS_LISTING) != 0;
+  order &= ~RS_UNITS_LISTING;
   if (order < RS_ORDER_DEFAULT || order > RS_ORDER_BEST) return RS_EINVAL;
   try {
     std::vector<rs::TensorHost> listed;
@@ -178,7 +180,7 @@ int rs_plan_create_ordered(const rs_tensor_desc* descs, int n, int world, int al
       p->world = world;
       p->g_coll = g_coll;
       p->A = A;
-      rc = rs::solve_shard_size(p->t, p->world, p->g_coll, p->A, &p->S);
+      rc = rs::solve_shard_size(p->t, p->world, p->g_coll, p->A, listing_only, &p->S);
       if (rc != RS_OK) return rc;
       if (!best || p->S < best->S) best = std::move(p);
     }

@@ -170,7 +170,7 @@ void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int3
 // whole shard), one unit per prefix; and every distinct block size on its own.  Every candidate
 // S passes the exact check, so more candidates can only lower S*.
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
-                     int64_t* S_out) {
+                     bool listing_only, int64_t* S_out) {
   i128 total = 0;
   for (const TensorHost& h : t) total += round_up(h.e, A);
   if (total >= kLimit) return RS_EOVERFLOW;
@@ -193,6 +193,7 @@ int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_
   std::sort(sizes.begin(), sizes.end());
   sizes.erase(std::unique(sizes.begin(), sizes.end()), sizes.end());
   add_family(sizes);
+  if (!listing_only) {
   std::vector<size_t> by_count(t.size());
   for (size_t i = 0; i < t.size(); ++i) by_count[i] = i;
   std::stable_sort(by_count.begin(), by_count.end(),
@@ -203,6 +204,7 @@ int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_
   // the set of tensors that contain a whole shard may be neither kind of prefix: the smallest
   // such sets as well, every distinct block size on its own
   for (int64_t g : sizes) add_family(std::vector<int64_t>{g});
+  }
 
   int64_t best = -1;
   for (int64_t c : units) {

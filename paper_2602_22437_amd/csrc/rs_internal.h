@@ -125,8 +125,9 @@ int64_t smallest_feasible_start(int64_t p, int64_t e, int64_t g, int64_t S, int6
 bool check_valid_shard(const std::vector<TensorHost>& t, int64_t world, int64_t S, int64_t A,
                        std::vector<int64_t>* starts);
 int describe_tensors(const rs_tensor_desc* descs, int n, std::vector<TensorHost>* out);
+// listing_only: candidate units restricted to Algorithm 1's listing (plus g_coll)
 int solve_shard_size(const std::vector<TensorHost>& t, int64_t world, int64_t g_coll, int64_t A,
-                     int64_t* S_out);
+                     bool listing_only, int64_t* S_out);
 void order_tensors(const std::vector<TensorHost>& t, int order, std::vector<int32_t>* perm);
 int shard_dim_granularity(const int64_t* shape, int ndim, int dim, int64_t g_user, int64_t* g_out);
 void select_roots(const std::vector<TensorHost>& t, int world, int32_t* roots, double* loads);

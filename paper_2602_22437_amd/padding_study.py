@@ -6,6 +6,7 @@ multiples costs least, and reports the padding overhead of the plan against the 
 sweep on synthetic units shaped like the two models the section uses.
 
     python -m paper_2602_22437_amd.padding_study [--model deepseek|gpt_oss|gpt_oss_fused] [--order 0..3]
+                                                 [--units all|listing|both]
     python -m paper_2602_22437_amd.padding_study --pick 480 544        # the FSDP sizes of a range with least padding
 """
 from __future__ import annotations
@@ -46,7 +47,8 @@ def moe_unit(model: str, rows_per_block: int) -> List[Tuple[int, int, int, int]]
 
 def sweep(model: str, worlds: Sequence[int], granularities: Sequence[int] = (1, 16, 128),
           order: int = B.RS_ORDER_DEFAULT) -> Dict[int, Dict[int, Tuple[float, float]]]:
-    """{rows_per_block: {world: (padding / payload, planner seconds)}}"""
+    """{rows_per_block: {world: (padding / payload, planner seconds)}}; `order` may carry
+    B.RS_UNITS_LISTING to keep the search to the candidate units of Algorithm 1 as listed."""
     out: Dict[int, Dict[int, Tuple[float, float]]] = {}
     for g in granularities:
         unit = moe_unit(model, g)
@@ -77,6 +79,8 @@ def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--model", default="deepseek", choices=["deepseek", "gpt_oss", "gpt_oss_fused"])
     ap.add_argument("--order", type=int, default=B.RS_ORDER_DEFAULT)
+    ap.add_argument("--units", default="both", choices=["all", "listing", "both"],
+                    help="candidate units of the search: Algorithm 1 as listed, the library's wider set, or both")
     ap.add_argument("--worlds", default="8,16,32,64,96,128,192,256,384,512,768,1024")
     ap.add_argument("--pick", type=int, nargs=2, metavar=("LO", "HI"),
                     help="rank the FSDP sizes of [LO, HI] by padding overhead instead of sweeping --worlds")
@@ -90,12 +94,16 @@ def main() -> None:
                   + f"  ... worst {ranked[-1][1]} ({100 * ranked[-1][0]:.2f}%)")
         return
     worlds = [int(x) for x in args.worlds.split(",")]
-    res = sweep(args.model, worlds, order=args.order)
+    variants = {"all": [("the library's search", 0)], "listing": [("Algorithm 1 as listed", B.RS_UNITS_LISTING)],
+                "both": [("Algorithm 1 as listed", B.RS_UNITS_LISTING), ("the library's wider search", 0)]}[args.units]
     print(f"padding overhead (padding / parameter elements), {args.model}-shaped MoE unit, bf16, 16-byte units")
-    print("FSDP size " + "".join(f"{w:>9d}" for w in worlds))
-    for g, row in res.items():
-        print(f"{g:>4d}x rows " + "".join(f"{100 * row[w][0]:8.2f}%" for w in worlds))
-    print("planner s  " + "".join(f"{max(res[g][w][1] for g in res):9.3f}" for w in worlds))
+    for label, flag in variants:
+        res = sweep(args.model, worlds, order=args.order | flag)
+        print(f"-- candidate units: {label}")
+        print("FSDP size " + "".join(f"{w:>9d}" for w in worlds))
+        for g, row in res.items():
+            print(f"{g:>4d}x rows " + "".join(f"{100 * row[w][0]:8.2f}%" for w in worlds))
+        print("planner s  " + "".join(f"{max(res[g][w][1] for g in res):9.3f}" for w in worlds))
 
 
 if __name__ == "__main__":

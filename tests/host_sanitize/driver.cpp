@@ -102,7 +102,9 @@ int main(int argc, char** argv) {
       rs::select_roots(t, int(world), lpt.data(), loads.data());
       for (int i = 0; i < n; ++i) REQUIRE(t[size_t(i)].cols == 0 ? lpt[size_t(i)] == -1 : (lpt[size_t(i)] >= 0 && lpt[size_t(i)] < world));
     } else {
-      REQUIRE(rs::solve_shard_size(t, world, g_coll, A, &S) == RS_OK);
+      REQUIRE(rs::solve_shard_size(t, world, g_coll, A, false, &S) == RS_OK);
+      int64_t S_listing = 0;   // Algorithm 1 as listed searches a subset of the units: never better
+      REQUIRE(rs::solve_shard_size(t, world, g_coll, A, true, &S_listing) == RS_OK && S_listing >= S);
       REQUIRE(rs::check_valid_shard(t, world, S, A, &starts));
     }
     REQUIRE(S > 0 && S % g_coll == 0);

@@ -92,6 +92,45 @@ def test_random_units_match_oracle():
             B.rs_plan_destroy(plan)
 
 
+def test_listing_only_units_match_oracle_and_never_beat_the_wider_search():
+    """RS_UNITS_LISTING keeps the candidate units to Algorithm 1 as listed (running LCM over the
+    ascending distinct block sizes, g_coll first): library == oracle on random units and on the
+    configurations; the result is valid, never below the wider search's, and sometimes above it."""
+    rnd = random.Random(22)
+    worse = 0
+    for _ in range(300):
+        tensors, world, align, item, A = random_unit(rnd)
+        specs = [P.TensorSpec(*t) for t in tensors]
+        for order in (B.RS_ORDER_DEFAULT, B.RS_ORDER_BEST):
+            want = P.make_plan(specs, world, align, item, tensor_align=A or None, order=order, units=P.UNITS_LISTING)
+            full = P.make_plan(specs, world, align, item, tensor_align=A or None, order=order)
+            plan = B.rs_plan_create_ordered(tensors, world, align, item, A, order | B.RS_UNITS_LISTING)
+            try:
+                assert B.rs_plan_shard_elems(plan) == want.S, (tensors, world, align, item, A, order)
+                assert B.rs_plan_offsets(plan) == want.offsets
+                assert want.S >= full.S
+                worse += want.S > full.S
+                perm = want.buffer_order()
+                tens = [(specs[t].e, specs[t].g) for t in perm]
+                assert P.layout_violations(tens, [want.offsets[t] for t in perm], world, want.S, want.A) == []
+            finally:
+                B.rs_plan_destroy(plan)
+    assert worse > 0          # the listing's family alone does miss the optimum now and then
+    for idx in sorted(WORKLOADS):      # the five configurations get the same S either way
+        wl = WORKLOADS[idx]
+        desc = [(t.rows, t.cols, t.mode) for t in wl.tensors]
+        a = B.rs_plan_create_ordered(desc, wl.world, wl.align_bytes, wl.min_itemsize, 0, B.RS_UNITS_LISTING)
+        b = B.rs_plan_create(desc, wl.world, wl.align_bytes, wl.min_itemsize)
+        try:
+            assert B.rs_plan_shard_elems(a) == B.rs_plan_shard_elems(b)
+            assert B.rs_plan_offsets(a) == B.rs_plan_offsets(b)
+        finally:
+            B.rs_plan_destroy(a)
+            B.rs_plan_destroy(b)
+    with pytest.raises(B.RaggedShardError):
+        B.rs_plan_create_ordered([(8, 0, 0)], 2, 16, 1, 0, 4 | B.RS_UNITS_LISTING)
+
+
 def test_check_valid_shard_matches_oracle():
     rnd = random.Random(22)
     for _ in range(300):
