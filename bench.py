@@ -447,6 +447,48 @@ def bench_config(wl, args, torch, B):
             B.rs_tensor_table_destroy(d.pop("dst32_tab"))
             del d["dst32"]
     if not args.no_extras:
+        # the unpack on regions gathered over a 2-D mesh (two groups; this group's regions are
+        # every other S elements of a buffer twice the size)
+        if quant:
+            wide = torch.empty(2 * total, dtype=torch.uint8, device="cuda")
+            wide.view(2 * W, S)[0::2].copy_(U[0]["codes"].view(W, S))
+            ms = timed(lambda i=0: B.rs_unpack_strided(plan, wide, 2 * S, U[0]["scales"], U[0]["dst_tab"], stream), 8)
+            kernels["unpack_strided"] = entry(ms, E + 4 * nb + 2 * E,
+                                              "dequant_unpack of one of two groups of a mesh-gathered code buffer; not in the step")
+        else:
+            wide = torch.empty(2 * total, dtype=torch.bfloat16, device="cuda")
+            wide.view(2 * W, S)[0::2].copy_(U[0]["dbuf"].view(W, S))
+            ms = timed(lambda i=0: B.rs_unpack_bf16_strided(plan, wide, 2 * S, U[0]["dst_tab"], stream), 8)
+            kernels["unpack_bf16_strided"] = entry(ms, 4 * E, "unpack_bf16 of one of two groups of a mesh-gathered "
+                                                              "buffer; not in the step")
+        del wide
+        if wl.index == 3:
+            # Algorithm 2's data path on these shapes: the balanced buffer P (128-row granularity) to
+            # the rooted buffer Q (every matrix whole on the device SelectRoot gives it) and back,
+            # one group copy each way
+            from workloads import MODE_128x128, MODE_1x128
+            pdesc = [(t.rows, t.cols, MODE_128x128 if t.cols else MODE_1x128) for t in wl.tensors]
+            pplan = B.rs_plan_create(pdesc, W, wl.align_bytes, wl.min_itemsize)
+            B.rs_plan_upload(pplan, 0)
+            roots, _ = B.rs_select_roots(desc, W)
+            roots = [r if r >= 0 else 0 for r in roots]
+            qplan = B.rs_plan_create_rooted(desc, W, roots, wl.align_bytes, wl.min_itemsize)
+            qoff = B.rs_plan_offsets(qplan)
+            ptotal, qtotal = B.rs_plan_total_elems(pplan), B.rs_plan_total_elems(qplan)
+            pbuf = torch.empty(ptotal, dtype=torch.bfloat16, device="cuda").normal_(0, wl.sigma, generator=gen)
+            qbuf = torch.zeros(qtotal, dtype=torch.bfloat16, device="cuda")
+            views = [qbuf[o:o + t.numel] for o, t in zip(qoff, wl.tensors)]
+            vtab = B.rs_tensor_table_create(pplan, views)
+            ms = timed(lambda i=0: B.rs_unpack_bf16(pplan, pbuf, vtab, stream), 16)
+            kernels["redistribute_to_roots"] = entry(
+                ms, 4 * E, f"P -> Q: balanced buffer ({ptotal} elem) into views of the rooted one ({qtotal} elem), "
+                           "one unpack_bf16 launch; not in the step")
+            ms = timed(lambda i=0: B.rs_pack(pplan, vtab, pbuf, stream), 16)
+            kernels["redistribute_from_roots"] = entry(ms, 2 * E + 2 * ptotal, "Q -> P: one ragged_pack launch; not in the step")
+            B.rs_tensor_table_destroy(vtab)
+            B.rs_plan_destroy(pplan)
+            B.rs_plan_destroy(qplan)
+            del pbuf, qbuf, views
         # group-level operators (widening beyond the four timed kernels)
         group_bytes = {"pack_scaled": 2 * E + 2 * total, "group_add": 6 * E, "group_scale": 4 * E,
                        "group_zero": 2 * total}

@@ -309,6 +309,17 @@ int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
 int rs_unpack_f32(const rs_plan* plan, const uint8_t* codes, const float* scales,
                   const rs_tensor_table* dst, void* stream);
 
+/* The same two on a code buffer gathered over a 2-D device mesh (Section 4, the stride metadata of
+ * StridedRaggedShard; see rs_unpack_bf16_strided): rank k's S code bytes start at byte
+ * k * region_stride.  With the parameter split over G devices of the other mesh dimension, part g is
+ * read with codes + g * S, region_stride = G * S, the scale array of part g (every part has its own,
+ * in the plan's order) and a tensor table over the g-th slices of the full tensors.
+ * region_stride >= S (RS_EINVAL), a multiple of 16 (RS_EALIGN). */
+int rs_unpack_strided(const rs_plan* plan, const uint8_t* codes, int64_t region_stride,
+                      const float* scales, const rs_tensor_table* dst, void* stream);
+int rs_unpack_f32_strided(const rs_plan* plan, const uint8_t* codes, int64_t region_stride,
+                          const float* scales, const rs_tensor_table* dst, void* stream);
+
 /* ---- block-wise 8-bit optimiser state on the local shard (Section 6.3, "8-bit Adam") ---------
  * The two Adam moments of rank's shard are held as 8-bit codes in blocks that never cross a
  * rank boundary, so a rank updates and re-quantises its state with no communication.

@@ -217,6 +217,24 @@ def reduce_quant_shard(plan: Plan, k: int, partials: np.ndarray) -> Tuple[np.nda
     return codes, scales, mean
 
 
+def gather_strided_codes(plan: Plan, buf: np.ndarray, starts) -> np.ndarray:
+    """The logical code buffer (m * S) of one group of a buffer gathered over a 2-D device mesh:
+    logical position x lives at buf[starts[x // S] + x % S] (Section 4, the stride metadata of
+    StridedRaggedShard; starts as dbuffer.strided_region_starts gives them)."""
+    S = plan.S
+    out = np.empty(plan.m * S, dtype=np.uint8)
+    for k in range(plan.m):
+        out[k * S:(k + 1) * S] = buf[starts[k]:starts[k] + S]
+    return out
+
+
+def dequant_unpack_strided(plan: Plan, buf: np.ndarray, starts, scales: np.ndarray, f32: bool = False) -> List[np.ndarray]:
+    """dequant_unpack of one group's regions of a mesh-gathered code buffer: the reshuffle on
+    materialise, with the group's own scale array."""
+    logical = gather_strided_codes(plan, buf, starts)
+    return dequant_unpack_f32(plan, logical, scales) if f32 else dequant_unpack(plan, logical, scales)
+
+
 def dequant_unpack_f32(plan: Plan, codes: np.ndarray, scales: np.ndarray) -> List[np.ndarray]:
     """Per-parameter fp32 values from the gathered codes (m*S) and all scales."""
     out = []

@@ -31,7 +31,7 @@ EXPORTS = [
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
     "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize",
     "rs_reduce_rows", "rs_pack_noalloc", "rs_partials_batch_create", "rs_partials_batch_destroy",
-    "rs_reduce_batch",
+    "rs_reduce_batch", "rs_unpack_strided", "rs_unpack_f32_strided",
 ]
 
 
@@ -115,6 +115,8 @@ _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_reduce_quantize.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P, _P, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
 _lib.rs_unpack_f32.argtypes = [_P, _P, _P, _P, _P]
+_lib.rs_unpack_strided.argtypes = [_P, _P, C.c_int64, _P, _P, _P]
+_lib.rs_unpack_f32_strided.argtypes = [_P, _P, C.c_int64, _P, _P, _P]
 _lib.rs_shard_batch_create.argtypes = [_P, C.c_int, C.c_int, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P),
                                        C.POINTER(_P)]
 _lib.rs_shard_batch_destroy.argtypes = [_P]
@@ -509,6 +511,16 @@ def rs_adam8_step(plan, rank: int, hyper, grad, master, param_bf16, m_codes, v_c
 
 def rs_unpack_f32(plan, codes, scales, dst_table, stream=None) -> None:
     _check(_lib.rs_unpack_f32(plan, _ptr(codes), _ptr(scales), dst_table, _stream(stream)), "rs_unpack_f32")
+
+
+def rs_unpack_strided(plan, codes, region_stride: int, scales, dst_table, stream=None) -> None:
+    _check(_lib.rs_unpack_strided(plan, _ptr(codes), int(region_stride), _ptr(scales), dst_table, _stream(stream)),
+           "rs_unpack_strided")
+
+
+def rs_unpack_f32_strided(plan, codes, region_stride: int, scales, dst_table, stream=None) -> None:
+    _check(_lib.rs_unpack_f32_strided(plan, _ptr(codes), int(region_stride), _ptr(scales), dst_table,
+                                      _stream(stream)), "rs_unpack_f32_strided")
 
 
 def rs_copy_probe(dst, src, nbytes: int, stream=None) -> None:

@@ -830,31 +830,42 @@ int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* st
                                 static_cast<hipStream_t>(stream));
 }
 
-int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
-              const rs_tensor_table* dst, void* stream) {
+// shared body of the four dequant_unpack entry points
+static int dequant_unpack(bool f32_out, const rs_plan* plan, const uint8_t* codes, int64_t region_stride,
+                          const float* scales, const rs_tensor_table* dst, void* stream) {
   int rc = check_device(plan);
   if (rc == RS_OK) rc = check_table(plan, dst);
   if (rc != RS_OK) return rc;
   if (!plan->all_quant) return RS_EUNSUPPORTED;
-  if (!codes || !scales) return RS_EINVAL;
-  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3)) return RS_EALIGN;
-  return rs::launch_dequant_unpack(false, plan->dev, int(plan->t.size()), plan->host.n_payload_gran,
+  if (!codes || !scales || region_stride < plan->S) return RS_EINVAL;
+  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3) || region_stride % 16 != 0 ||
+      (f32_out && (dst->low_bits & 3)))
+    return RS_EALIGN;
+  return rs::launch_dequant_unpack(f32_out, plan->dev, int(plan->t.size()), plan->host.n_payload_gran,
                                    codes, scales, dst->ptrs, plan->S, plan->host.granules_per_rank,
-                                   static_cast<hipStream_t>(stream));
+                                   region_stride, static_cast<hipStream_t>(stream));
+}
+
+int rs_unpack(const rs_plan* plan, const uint8_t* codes, const float* scales,
+              const rs_tensor_table* dst, void* stream) {
+  return dequant_unpack(false, plan, codes, plan ? plan->S : 0, scales, dst, stream);
 }
 
 int rs_unpack_f32(const rs_plan* plan, const uint8_t* codes, const float* scales,
                   const rs_tensor_table* dst, void* stream) {
-  int rc = check_device(plan);
-  if (rc == RS_OK) rc = check_table(plan, dst);
-  if (rc != RS_OK) return rc;
-  if (!plan->all_quant) return RS_EUNSUPPORTED;
-  if (!codes || !scales) return RS_EINVAL;
-  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3) || (dst->low_bits & 3))
-    return RS_EALIGN;
-  return rs::launch_dequant_unpack(true, plan->dev, int(plan->t.size()), plan->host.n_payload_gran,
-                                   codes, scales, dst->ptrs, plan->S, plan->host.granules_per_rank,
-                                   static_cast<hipStream_t>(stream));
+  return dequant_unpack(true, plan, codes, plan ? plan->S : 0, scales, dst, stream);
+}
+
+int rs_unpack_strided(const rs_plan* plan, const uint8_t* codes, int64_t region_stride,
+                      const float* scales, const rs_tensor_table* dst, void* stream) {
+  if (region_stride <= 0) return RS_EINVAL;
+  return dequant_unpack(false, plan, codes, region_stride, scales, dst, stream);
+}
+
+int rs_unpack_f32_strided(const rs_plan* plan, const uint8_t* codes, int64_t region_stride,
+                          const float* scales, const rs_tensor_table* dst, void* stream) {
+  if (region_stride <= 0) return RS_EINVAL;
+  return dequant_unpack(true, plan, codes, region_stride, scales, dst, stream);
 }
 
 int rs_copy_probe(void* dst, const void* src, int64_t bytes, void* stream) {

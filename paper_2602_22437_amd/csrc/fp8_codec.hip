@@ -256,7 +256,8 @@ template <bool kF32>
 __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
     const TensorDev* __restrict__ T, int n, const GranRef* __restrict__ granules,
     const uint8_t* __restrict__ codes,
-    const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr) {
+    const float* __restrict__ scales, void* const* __restrict__ ptrs, int64_t S, int64_t gpr,
+    int64_t region_stride) {
   // one 8-byte read: the granule and its first tensor (a payload granule: t0 < n)
   const long long packed = reinterpret_cast<const long long*>(granules)[blockIdx.x];
   const int t0 = int32_t(packed >> 32);
@@ -266,7 +267,9 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
   const unsigned gid = unsigned(packed);             // granule ids and gpr fit 31 bits
   const unsigned k = gid / unsigned(gpr);
   const int64_t i0 = int64_t(gid - k * unsigned(gpr)) * kGranule;
-  const int64_t d0 = k * S + i0;
+  const int64_t d0 = k * S + i0;            // logical buffer position: what the tables speak of
+  // where the granule's codes live: rank regions are region_stride bytes apart (S in a plain buffer)
+  const uint8_t* __restrict__ const src = codes + k * region_stride + i0;
   const int len = int(min(int64_t(kGranule), S - i0));
   // A lane converts kGroup codes per access so that its store is one 16-byte vector and a
   // wavefront's stores are contiguous: 8 codes -> 8 bf16, or 4 codes -> 4 fp32.
@@ -302,9 +305,9 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
         on[h] = lo < len;
         if (!on[h]) continue;
         if (kF32)
-          c[h] = u32x2{__builtin_nontemporal_load(reinterpret_cast<const unsigned*>(codes + d0 + lo)), 0};
+          c[h] = u32x2{__builtin_nontemporal_load(reinterpret_cast<const unsigned*>(src + lo)), 0};
         else
-          c[h] = ld8(codes + d0 + lo);
+          c[h] = ld8(src + lo);
         int64_t sidx;
         if (contig) {
           sidx = (first + lo) >> 7;            // blocks are consecutive runs of 128 elements
@@ -350,7 +353,7 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
       const int64_t row = i / t.cols;
       const int64_t col = i - row * t.cols;
       const float scale = scales[t.scale_base + scale_index(t, row, col)];
-      const auto f = __builtin_amdgcn_cvt_pk_f32_fp8(int(codes[pos]), false);
+      const auto f = __builtin_amdgcn_cvt_pk_f32_fp8(int(src[lo + q]), false);
       if (kF32)
         reinterpret_cast<float*>(ptrs[s])[i] = f[0] * scale;
       else
@@ -378,16 +381,16 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
 
 int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
-                          int64_t gpr, hipStream_t st) {
+                          int64_t gpr, int64_t region_stride, hipStream_t st) {
   if (n_payload_gran == 0) return RS_OK;
   if (n_payload_gran < 0 || n_payload_gran > 0x7fffffffLL) return RS_EOVERFLOW;
   const dim3 g{unsigned(n_payload_gran)}, b{unsigned(kDequantThreads)};
   if (f32_out)
     dequant_unpack_kernel<true><<<g, b, 0, st>>>(dev.tensors, n, dev.payload_gran,
-                                                 codes, scales, ptrs, S, gpr);
+                                                 codes, scales, ptrs, S, gpr, region_stride);
   else
     dequant_unpack_kernel<false><<<g, b, 0, st>>>(dev.tensors, n, dev.payload_gran,
-                                                  codes, scales, ptrs, S, gpr);
+                                                  codes, scales, ptrs, S, gpr, region_stride);
   return launched();
 }
 

@@ -35,7 +35,7 @@ int launch_reduce_quant(const DeviceTables& dev, int64_t item_off, int64_t item_
                         hipStream_t st);
 int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
-                          int64_t gpr, hipStream_t st);
+                          int64_t gpr, int64_t region_stride, hipStream_t st);
 // fp32 constants of one 8-bit Adam step
 struct Adam8Consts {
   float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, step_size, bc2_sqrt, decay;

@@ -249,6 +249,52 @@ def test_strided_regions_of_a_2d_mesh(groups, gap):
         u.close()
 
 
+@pytest.mark.parametrize("groups,gap", [(1, 0), (3, 0), (2, 48)])
+def test_strided_fp8_unpack_of_a_2d_mesh(groups, gap):
+    """rs_unpack_strided / rs_unpack_f32_strided: FP8 codes gathered over a (world x groups) mesh,
+    every group with its own scale array; `groups` launches materialise the full tensors in bf16
+    and in fp32 with no intermediate copy, bit for bit what the oracle's reshuffle gives."""
+    from oracle import fp8 as OF
+    tensors = [(257, 136, MODE_128x128), (300, 0, MODE_1x128), (128, 384, MODE_128x128), (33, 8, MODE_1x128)]
+    W = 4
+    u = Unit(tensors, W)
+    try:
+        S = u.S
+        stride = groups * S + gap
+        sizes = [s.e for s in u.specs]
+        nb = u.oracle.scale_bases()[-1]
+        rng = np.random.default_rng(80 + groups)
+        gathered = rng.integers(0, 0x7F, size=W * stride, dtype=np.uint8) | (
+            rng.integers(0, 2, size=W * stride, dtype=np.uint8) << 7)
+        d_codes = torch.from_numpy(gathered).cuda()
+        full16 = [torch.full((groups * e,), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.bfloat16) for e in sizes]
+        full32 = [torch.full((groups * e,), float("nan"), dtype=torch.float32, device="cuda") for e in sizes]
+        for g in range(groups):
+            scales = (rng.random(nb).astype(np.float32) + np.float32(0.25)) * np.float32(2e-3)
+            d_scales = torch.from_numpy(scales).cuda()
+            starts = [k * stride + g * S for k in range(W)]
+            say(f"unpack_strided: group {g} of {groups}, stride {stride}")
+            v16 = [f[g * e:(g + 1) * e] for f, e in zip(full16, sizes)]
+            v32 = [f[g * e:(g + 1) * e] for f, e in zip(full32, sizes)]
+            B.rs_unpack_strided(u.plan, d_codes[g * S:], stride, d_scales, u.table(v16))
+            B.rs_unpack_f32_strided(u.plan, d_codes[g * S:], stride, d_scales, u.table(v32))
+            torch.cuda.synchronize()
+            want16 = OF.dequant_unpack_strided(u.oracle, gathered, starts, scales)
+            want32 = OF.dequant_unpack_strided(u.oracle, gathered, starts, scales, f32=True)
+            for i in range(len(sizes)):
+                first_diff(bits_of(v16[i]), want16[i], f"strided fp8 unpack tensor {i} group {g}")
+                assert np.array_equal(v32[i].cpu().numpy().view(np.uint32), want32[i].view(np.uint32)), (i, g)
+        P = C.c_void_p
+        tab = u.tables[0]
+        sc = torch.zeros(nb, dtype=torch.float32, device="cuda")
+        assert B.raw_call("rs_unpack_strided", P(u.plan), P(d_codes.data_ptr()), C.c_int64(S - 16), P(sc.data_ptr()),
+                          P(tab), P(0)) == B.RS_EINVAL
+        assert B.raw_call("rs_unpack_f32_strided", P(u.plan), P(d_codes.data_ptr()), C.c_int64(S + 8), P(sc.data_ptr()),
+                          P(tab), P(0)) == B.RS_EALIGN
+    finally:
+        u.close()
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_units_group_ops(seed):
     """Random units (any block mode, odd pitches, element-aligned starts, reordered buffers)."""

@@ -358,3 +358,35 @@ def test_fused_reduce_quantise_against_the_definition_alone():
             if scales.size > 2:
                 with pytest.raises(AssertionError):
                     order_free_fused_check(plan, plan.specs, k, get, codes, np.roll(scales, 1), "scales shifted")
+
+
+def test_strided_dequant_unpack_against_reshape_and_per_element_gather():
+    """FP8 codes gathered over a (m x groups) mesh, FSDP rank outermost: one group's logical code
+    buffer is a strided slice (numpy reshape as the independent formulation), its unpack is the
+    plain dequant_unpack of that slice, and single elements follow the address rule by hand."""
+    from oracle.dbuffer import strided_region_starts
+    wl, pl = toy_plan()
+    m, S, groups = pl.m, pl.S, 3
+    rng = np.random.default_rng(12)
+    gathered = rng.integers(0, 0x7F, size=m * groups * S, dtype=np.uint8) | (
+        rng.integers(0, 2, size=m * groups * S, dtype=np.uint8) << 7)           # any code but NaN
+    nb = pl.scale_bases()[-1]
+    tab = F.decode_table()
+    for grp in range(groups):
+        scales = (rng.random(nb).astype(np.float32) + np.float32(0.5)) * np.float32(1e-3)
+        starts = strided_region_starts(m, S, groups, grp)
+        logical = gathered.reshape(m, groups, S)[:, grp, :].reshape(-1)
+        assert np.array_equal(F.gather_strided_codes(pl, gathered, starts), logical)
+        for f32 in (False, True):
+            got = F.dequant_unpack_strided(pl, gathered, starts, scales, f32=f32)
+            want = F.dequant_unpack_f32(pl, logical, scales) if f32 else F.dequant_unpack(pl, logical, scales)
+            for a, b in zip(got, want):
+                assert np.array_equal(a, b)
+        # by hand on tensor 0 (256 x 384, 128x128 tiles): element (row, col) of the fp32 form
+        got = F.dequant_unpack_strided(pl, gathered, starts, scales, f32=True)
+        l, C = pl.offsets[0], 384
+        for row, col in ((0, 0), (127, 383), (128, 5), (255, 200)):
+            x = l + row * C + col
+            code = gathered[((x // S) * groups + grp) * S + x % S]
+            blk = pl.scale_bases()[0] + (row // 128) * 3 + col // 128
+            assert got[0][row * C + col] == tab[code] * scales[blk]
