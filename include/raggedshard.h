@@ -314,7 +314,7 @@ int rs_unpack_f32(const rs_plan* plan, const uint8_t* codes, const float* scales
  * k * region_stride.  With the parameter split over G devices of the other mesh dimension, part g is
  * read with codes + g * S, region_stride = G * S, the scale array of part g (every part has its own,
  * in the plan's order) and a tensor table over the g-th slices of the full tensors.
- * region_stride >= S (RS_EINVAL), a multiple of 16 (RS_EALIGN). */
+ * region_stride >= S (RS_EINVAL), a multiple of 8 (RS_EALIGN). */
 int rs_unpack_strided(const rs_plan* plan, const uint8_t* codes, int64_t region_stride,
                       const float* scales, const rs_tensor_table* dst, void* stream);
 int rs_unpack_f32_strided(const rs_plan* plan, const uint8_t* codes, int64_t region_stride,

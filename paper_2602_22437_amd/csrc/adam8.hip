@@ -67,7 +67,11 @@ __device__ __forceinline__ StateSlot state_slot(const TensorDev& t, const Item& 
   return s;
 }
 
-__device__ __forceinline__ float quant_step(float absmax, float levels) { return absmax / levels; }
+// step = absmax / levels (levels 127 or 255), correctly rounded, by the shared-divisor quotient
+// with the constant's reciprocal
+__device__ __forceinline__ float quant_step(float absmax, float levels) {
+  return exact_quotient(absmax, levels == 127.0f ? 1.0 / 127.0 : 1.0 / 255.0);
+}
 
 // Reciprocal of a block's quantisation step for exact_quotient; an all-zero block (absmax 0,
 // step 0) gets 0, which turns every code of the block into 0.
@@ -188,7 +192,7 @@ __device__ __forceinline__ void adam8_item(const TensorDev& t, const Item& it,
       const float t3 = c.beta2 * v_old, t4 = c.one_minus_beta2 * gg;
       v[i][j] = t3 + t4;
       const float w1 = __uint_as_float(wq[j]) * c.decay;
-      const float root = exact_quotient(__builtin_sqrtf(v[i][j]), c.bc2_sqrt_rcp);
+      const float root = exact_quotient(exact_sqrt(v[i][j]), c.bc2_sqrt_rcp);
       const float denom = root + c.eps;
       const float upd = c.step_size * (m[i][j] / denom);
       wn[j] = w1 - upd;

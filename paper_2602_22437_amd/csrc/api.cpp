@@ -838,7 +838,7 @@ static int dequant_unpack(bool f32_out, const rs_plan* plan, const uint8_t* code
   if (rc != RS_OK) return rc;
   if (!plan->all_quant) return RS_EUNSUPPORTED;
   if (!codes || !scales || region_stride < plan->S) return RS_EINVAL;
-  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3) || region_stride % 16 != 0 ||
+  if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3) || region_stride % 8 != 0 ||
       (f32_out && (dst->low_bits & 3)))
     return RS_EALIGN;
   return rs::launch_dequant_unpack(f32_out, plan->dev, int(plan->t.size()), plan->host.n_payload_gran,

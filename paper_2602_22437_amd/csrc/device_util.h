@@ -84,6 +84,25 @@ __device__ __forceinline__ float bf16_hi(unsigned packed) { return __uint_as_flo
 __device__ __forceinline__ double shared_reciprocal(float b) { return 1.0 / double(b); }
 __device__ __forceinline__ float exact_quotient(float x, double rd) { return float(double(x) * rd); }
 
+// Correctly rounded fp32 square root of x >= 0 from the hardware's 1-ulp estimate s: the true root
+// rounds to s - 1 ulp exactly when x <= s * (s - 1 ulp) (the product stands for the square of the
+// midpoint; x - s * (s - 1 ulp) is a whole multiple of ulp(s)^2, so the quarter-ulp^2 between the
+// two cannot matter), to s + 1 ulp when x > s * (s + 1 ulp), both residuals exact in one FMA each.
+// Zero comes out as zero (the lower neighbour is a NaN pattern, its test false).  Valid for zero
+// and for x in [2^-100, 2^100); outside, the estimate's own input scaling would be needed and the
+// compiler's sequence is taken instead (a branch uniform across the wavefront, all but never taken).
+__device__ __forceinline__ float exact_sqrt(float x) {
+  const unsigned e = (__float_as_uint(x) >> 23) & 0xffu;
+  const bool in_range = (x == 0.0f) | ((e >= 27u) & (e < 227u));
+  if (__builtin_amdgcn_ballot_w64(!in_range) != 0) return __builtin_sqrtf(x);
+  const float s = __builtin_amdgcn_sqrtf(x);
+  const float dn = __uint_as_float(__float_as_uint(s) - 1u), up = __uint_as_float(__float_as_uint(s) + 1u);
+  const float t_dn = __builtin_fmaf(-dn, s, x), t_up = __builtin_fmaf(-up, s, x);
+  float r = t_dn <= 0.0f ? dn : s;
+  r = t_up > 0.0f ? up : r;
+  return r;
+}
+
 // status of the launch just enqueued
 static inline int launched() { return hipGetLastError() == hipSuccess ? RS_OK : RS_EHIP; }
 

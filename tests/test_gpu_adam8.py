@@ -25,7 +25,7 @@ def diff(got, want, what):
         raise AssertionError(f"{what}: {bad.size} differ, first at {bad[:6]}: got {got[bad[:6]]} want {want[bad[:6]]}")
 
 
-def run_steps(u: Unit, rank: int, seed: int, hypers, label, grad_sigma=1e-3, with_param=True):
+def run_steps(u: Unit, rank: int, seed: int, hypers, label, grad_sigma=1e-3, with_param=True, wild=False):
     """Zero state, then one step per entry of `hypers`, each compared with the oracle."""
     S = u.S
     rng = np.random.default_rng(seed)
@@ -51,6 +51,8 @@ def run_steps(u: Unit, rank: int, seed: int, hypers, label, grad_sigma=1e-3, wit
         g = (rng.standard_normal(S) * grad_sigma).astype(np.float32)
         if i == 1:
             g[pay & (rng.random(S) < 0.01)] = 0.0
+        if wild:       # magnitudes from 1e-30 to 1e+15 side by side: tiny, subnormal and huge second moments
+            g = (g * np.float32(1e3) * (np.float32(10.0) ** rng.integers(-30, 16, size=S).astype(np.float32))).astype(np.float32)
         g[~pay] = np.nan                                  # the kernel must not look at padding
         say(f"adam8 {label}: rank={rank} step={h.step} S={S} blocks={nb}")
         B.rs_adam8_step(u.plan, rank, (h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step),
@@ -68,7 +70,7 @@ def run_steps(u: Unit, rank: int, seed: int, hypers, label, grad_sigma=1e-3, wit
         assert d_am.cpu().numpy()[nb] == 7.0 and d_av.cpu().numpy()[nb] == 7.0
     # padding untouched in every array
     assert np.all(w[~pay] == W_SENTINEL) and np.all(mc[~pay] == M_SENTINEL) and np.all(vc[~pay] == V_SENTINEL)
-    if nb:
+    if nb and not wild:
         assert am.max() > 0 and av.max() > 0 and np.abs(mc[pay]).max() == 127 and vc[pay].max() == 255
 
 
@@ -101,6 +103,19 @@ def test_adam8_units_every_rank(case):
         assert B.rs_plan_state_bases(u.plan) == OA.state_bases(u.oracle)
         for k in range(world):
             run_steps(u, k, 100 * case + k, hypers(3), f"unit{case}")
+    finally:
+        u.close()
+
+
+@pytest.mark.parametrize("case", [0, 1, 5])
+def test_adam8_gradients_of_wildly_different_magnitudes(case):
+    """Gradients from 1e-30 to 1e+15 in one shard: second moments that are zero, subnormal, tiny and
+    huge, quotients far below one code step - every output still bit for bit the oracle's."""
+    tensors, world, A = UNITS[case]
+    u = Unit(tensors, world, 16, 1, A)
+    try:
+        for k in range(world):
+            run_steps(u, k, 4000 + 10 * case + k, hypers(3), f"wild{case}", wild=True)
     finally:
         u.close()
 

@@ -289,7 +289,7 @@ def test_strided_fp8_unpack_of_a_2d_mesh(groups, gap):
         sc = torch.zeros(nb, dtype=torch.float32, device="cuda")
         assert B.raw_call("rs_unpack_strided", P(u.plan), P(d_codes.data_ptr()), C.c_int64(S - 16), P(sc.data_ptr()),
                           P(tab), P(0)) == B.RS_EINVAL
-        assert B.raw_call("rs_unpack_f32_strided", P(u.plan), P(d_codes.data_ptr()), C.c_int64(S + 8), P(sc.data_ptr()),
+        assert B.raw_call("rs_unpack_f32_strided", P(u.plan), P(d_codes.data_ptr()), C.c_int64(S + 4), P(sc.data_ptr()),
                           P(tab), P(0)) == B.RS_EALIGN
     finally:
         u.close()
