@@ -295,7 +295,22 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
       if (col0 < 0) { col0 += t.cols; --row0; }
       if (col0 >= t.cols) { col0 -= t.cols; ++row0; }
       const unsigned C = unsigned(t.cols);
-      const bool contig = (t.flags & kFlagContig) && !(t.flags & kFlagTile);
+      const bool tile = (t.flags & kFlagTile) != 0;
+      const bool contig = (t.flags & kFlagContig) && !tile;
+      // scale of the granule's first element, the same for the whole workgroup: scalar arithmetic
+      const int64_t row0u = (int64_t(__builtin_amdgcn_readfirstlane(int(row0 >> 32))) << 32) |
+                            unsigned(__builtin_amdgcn_readfirstlane(int(row0)));
+      const float* __restrict__ const sc0 =
+          scales + t.scale_base + (contig ? (first >> 7) : (tile ? (row0u >> 7) : row0u) * t.nbc);
+      const unsigned row_in_tile = tile ? unsigned(row0u) & 127u : 0u;
+      // this lane's first group: rows past row0 and column, by one 32-bit division; the following
+      // parts are kStep elements further on, which is at most one row when rows are that long
+      unsigned cc = unsigned(col0) + unsigned(lane), dr = 0;
+      if (!contig) {
+        dr = cc / C;
+        cc -= dr * C;
+      }
+      const bool long_rows = C >= unsigned(kStep);
       u32x2 c[kParts];
       float sc[kParts];
       bool on[kParts];
@@ -303,20 +318,31 @@ __global__ __launch_bounds__(kDequantThreads) void dequant_unpack_kernel(
       for (int h = 0; h < kParts; ++h) {
         const int lo = h * kStep + lane;
         on[h] = lo < len;
-        if (!on[h]) continue;
-        if (kF32)
-          c[h] = u32x2{__builtin_nontemporal_load(reinterpret_cast<const unsigned*>(src + lo)), 0};
-        else
-          c[h] = ld8(src + lo);
-        int64_t sidx;
-        if (contig) {
-          sidx = (first + lo) >> 7;            // blocks are consecutive runs of 128 elements
-        } else {
-          const unsigned cc = unsigned(col0) + unsigned(lo);
-          const unsigned dr = cc / C;
-          sidx = scale_index(t, row0 + dr, cc - dr * C);
+        if (on[h]) {
+          if (kF32)
+            c[h] = u32x2{__builtin_nontemporal_load(reinterpret_cast<const unsigned*>(src + lo)), 0};
+          else
+            c[h] = ld8(src + lo);
+          unsigned sidx;
+          if (contig)
+            sidx = ((unsigned(first) & 127u) + unsigned(lo)) >> 7;   // consecutive runs of 128 elements
+          else
+            sidx = (tile ? ((row_in_tile + dr) >> 7) : dr) * unsigned(t.nbc) + (cc >> 7);
+          sc[h] = sc0[sidx];
         }
-        sc[h] = scales[t.scale_base + sidx];
+        if (!contig && h + 1 < kParts) {     // on to the next part
+          if (long_rows) {
+            cc += kStep;
+            if (cc >= C) {
+              cc -= C;
+              ++dr;
+            }
+          } else {
+            const unsigned c2 = cc + kStep, k2 = c2 / C;
+            dr += k2;
+            cc = c2 - k2 * C;
+          }
+        }
       }
 #pragma unroll
       for (int h = 0; h < kParts; ++h) {

@@ -54,16 +54,20 @@ class Unit:
         self.S = self.oracle.S
         self.total = self.oracle.total
         self.tables = []
+        self.keep = []
 
     def table(self, dev_tensors):
+        dev_tensors = list(dev_tensors)
         t = B.rs_tensor_table_create(self.plan, dev_tensors)
         self.tables.append(t)
+        self.keep.append(dev_tensors)   # the table holds bare addresses: the tensors must outlive it
         return t
 
     def close(self):
         for t in self.tables:
             B.rs_tensor_table_destroy(t)
         self.tables = []
+        self.keep = []
         if self.plan:
             B.rs_plan_destroy(self.plan)
             self.plan = None
