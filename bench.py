@@ -432,6 +432,11 @@ def bench_config(wl, args, torch, B):
                                                        None, stream), reps)
         kernels["reduce_quantize"] = entry(
             rq_ms, rq_bytes, "shard_reduce + block_quant in one launch (codes and scales out, no fp32 mean); not in the step")
+        if rbatch and qshards == units:
+            rqb_ms = timed(lambda i=0: B.rs_reduce_quantize_batch(plan, rbatch, batch, False, stream), 8)
+            kernels["reduce_quantize_batch"] = entry(
+                rqb_ms, units * rq_bytes,
+                f"the same over rank {rank}'s region of all {units} units in one launch; not in the step")
         for d in U:   # the timed path's codes come from the packed parameters: restore them
             B.rs_quantize(plan, rank, d["shard"], d["shard_codes"], d["shard_scales"], stream)
         # gathered FP8 unit straight into fp32 master copies (first 4 units: 4 bytes per element)

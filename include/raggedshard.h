@@ -297,6 +297,16 @@ int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* st
 int rs_reduce_quantize(const rs_plan* plan, int rank, const void* partials, int64_t row_stride,
                        uint8_t* codes, float* scales, float* mean_out, void* stream);
 
+/* The same for rank `rank`'s region of `count` units that share this plan, in one launch (the
+ * group-level fusion of Section 5 again: a unit's shard holds too few blocks to occupy the GPU).
+ * in: the units' partial buffers and row stride (rs_partials_batch_create); out: their code and
+ * scale buffers (rs_shard_batch_create; its shard pointers are not read).  Both must have been
+ * made for this plan with the same rank and count, else RS_EINVAL.  write_means != 0: the fp32
+ * mean of unit u is also written to the partials batch's outs[u] (0 on padding); otherwise
+ * those buffers are left alone.  Equal to rs_reduce_quantize on every unit, bit for bit. */
+int rs_reduce_quantize_batch(const rs_plan* plan, const rs_partials_batch* in,
+                             const rs_shard_batch* out, int write_means, void* stream);
+
 /* ---- dequant_unpack: gathered FP8 unit -> per-parameter bf16 --------------------------------
  * dst_t[i] = bf16_rne( value(codes[l_t + i]) * scales[block of i] ).
  * codes: device, world*S uint8, 16-byte aligned; scales: device, all of the unit's scales. */

@@ -29,7 +29,7 @@ EXPORTS = [
     "rs_plan_num_state_blocks", "rs_plan_state_bases", "rs_plan_state_range", "rs_adam8_step",
     "rs_adam8_batch_create", "rs_adam8_batch_destroy", "rs_adam8_step_batch", "rs_unpack_f32",
     "rs_state_quantize", "rs_state_dequantize", "rs_pack_strided", "rs_unpack_bf16_strided",
-    "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize",
+    "rs_plan_create_rooted", "rs_select_roots", "rs_shard_dim_granularity", "rs_reduce_quantize", "rs_reduce_quantize_batch",
     "rs_reduce_rows", "rs_pack_noalloc", "rs_partials_batch_create", "rs_partials_batch_destroy",
     "rs_reduce_batch", "rs_unpack_strided", "rs_unpack_f32_strided",
 ]
@@ -113,6 +113,7 @@ _lib.rs_partials_batch_destroy.restype = None
 _lib.rs_reduce_batch.argtypes = [_P, _P, _P]
 _lib.rs_quantize.argtypes = [_P, C.c_int, _P, _P, _P, _P]
 _lib.rs_reduce_quantize.argtypes = [_P, C.c_int, _P, C.c_int64, _P, _P, _P, _P]
+_lib.rs_reduce_quantize_batch.argtypes = [_P, _P, _P, C.c_int, _P]
 _lib.rs_unpack.argtypes = [_P, _P, _P, _P, _P]
 _lib.rs_unpack_f32.argtypes = [_P, _P, _P, _P, _P]
 _lib.rs_unpack_strided.argtypes = [_P, _P, C.c_int64, _P, _P, _P]
@@ -406,6 +407,11 @@ def rs_reduce_quantize(plan, rank: int, partials, row_stride: int, codes, scales
     _check(_lib.rs_reduce_quantize(plan, int(rank), _ptr(partials), int(row_stride), _ptr(codes),
                                    _ptr(scales), None if mean_out is None else _ptr(mean_out),
                                    _stream(stream)), "rs_reduce_quantize")
+
+
+def rs_reduce_quantize_batch(plan, partials_batch, shard_batch, write_means: bool = False, stream=None) -> None:
+    _check(_lib.rs_reduce_quantize_batch(plan, partials_batch, shard_batch, int(bool(write_means)),
+                                         _stream(stream)), "rs_reduce_quantize_batch")
 
 
 def rs_shard_batch_create(plan, rank: int, shards: Sequence, codes: Sequence, scales: Sequence) -> int:

@@ -135,7 +135,7 @@ void finish_plan(rs_plan* p, const std::vector<int64_t>& starts) {
 
 extern "C" {
 
-int rs_version(void) { return 160; }
+int rs_version(void) { return 170; }
 
 const char* rs_strerror(int code) {
   switch (code) {
@@ -616,9 +616,26 @@ int rs_reduce_quantize(const rs_plan* plan, int rank, const void* partials, int6
     return RS_EALIGN;
   const std::vector<int64_t>& ib = plan->host.item_begin;
   return rs::launch_reduce_quant(plan->dev, ib[size_t(rank)], ib[size_t(rank) + 1] - ib[size_t(rank)],
-                                 partials, row_stride, codes, scales, mean_out,
-                                 int64_t(rank) * plan->S, plan->scale_begin[size_t(rank)],
+                                 partials, row_stride, codes, scales, mean_out, nullptr, nullptr, 0,
+                                 false, int64_t(rank) * plan->S, plan->scale_begin[size_t(rank)],
                                  int(plan->world), static_cast<hipStream_t>(stream));
+}
+
+int rs_reduce_quantize_batch(const rs_plan* plan, const rs_partials_batch* in,
+                             const rs_shard_batch* out, int write_means, void* stream) {
+  const int rc = check_device(plan);
+  if (rc != RS_OK) return rc;
+  if (!plan->all_quant) return RS_EUNSUPPORTED;
+  if (!in || !out || in->owner != plan || out->owner != plan || !in->ptrs || !out->ptrs ||
+      in->rank != out->rank || in->count != out->count)
+    return RS_EINVAL;
+  const int rank = in->rank;
+  const std::vector<int64_t>& ib = plan->host.item_begin;
+  return rs::launch_reduce_quant(plan->dev, ib[size_t(rank)], ib[size_t(rank) + 1] - ib[size_t(rank)],
+                                 nullptr, in->row_stride, nullptr, nullptr, nullptr, in->ptrs,
+                                 out->ptrs, in->count, write_means != 0, int64_t(rank) * plan->S,
+                                 plan->scale_begin[size_t(rank)], int(plan->world),
+                                 static_cast<hipStream_t>(stream));
 }
 
 // checks the hyper-parameters and derives the step's fp32 constants: each is evaluated in

@@ -36,12 +36,29 @@ __device__ __forceinline__ unsigned quant4(float a, float b, float c, float e, d
 
 __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
     const TensorDev* __restrict__ T, const QItem* __restrict__ items, int64_t item_off,
-    int64_t item_count, const uint16_t* __restrict__ P, int64_t row_stride,
-    uint8_t* __restrict__ codes, float* __restrict__ scales, float* __restrict__ mean_out,
-    int64_t elem_base, int64_t scale_off, int W, float inv_w) {
+    int64_t item_count, const uint16_t* __restrict__ P_one, int64_t row_stride,
+    uint8_t* __restrict__ codes_one, float* __restrict__ scales_one, float* __restrict__ mean_one,
+    void* const* __restrict__ batch_in, void* const* __restrict__ batch_out, int batch_count,
+    int write_means, int64_t elem_base, int64_t scale_off, int W, float inv_w) {
   __shared__ unsigned wave_max_lds[kQuantThreads / 64];
-  const int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
-  if (idx >= item_count) return;
+  const uint16_t* __restrict__ P = P_one;
+  uint8_t* __restrict__ codes = codes_one;
+  float* __restrict__ scales = scales_one;
+  float* __restrict__ mean_out = mean_one;
+  int64_t idx = xcd_chunked(blockIdx.x, kXcdChunk);
+  if (batch_in) {
+    // the units' item ranges end to end in one flat grid; batch_in = [partials | means],
+    // batch_out = [shards (unused) | codes | scales], batch_count pointers each
+    const int64_t u = unsigned(idx) / unsigned(item_count);   // both below 2^31
+    if (u >= batch_count) return;
+    idx -= u * item_count;
+    P = static_cast<const uint16_t*>(batch_in[u]);
+    mean_out = write_means ? static_cast<float*>(batch_in[batch_count + u]) : nullptr;
+    codes = static_cast<uint8_t*>(batch_out[batch_count + u]);
+    scales = static_cast<float*>(batch_out[2 * batch_count + u]);
+  } else if (idx >= item_count) {
+    return;
+  }
   const QItem it = items[item_off + idx];
   const int tid = threadIdx.x;
   if (it.tensor < 0) {   // padding of the region: zero codes, zero mean
@@ -136,13 +153,18 @@ __global__ __launch_bounds__(kQuantThreads) void reduce_quant_kernel(
 
 int launch_reduce_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count,
                         const void* partials, int64_t row_stride, uint8_t* codes, float* scales,
-                        float* mean_out, int64_t elem_base, int64_t scale_off, int world,
-                        hipStream_t st) {
-  if (item_count == 0) return RS_OK;
-  if (item_count < 0 || item_count > 0x7fffff00LL) return RS_EOVERFLOW;
-  reduce_quant_kernel<<<dim3(unsigned(xcd_grid(item_count))), dim3(kQuantThreads), 0, st>>>(
+                        float* mean_out, void* const* batch_in, void* const* batch_out,
+                        int batch_count, bool write_means, int64_t elem_base, int64_t scale_off,
+                        int world, hipStream_t st) {
+  if (item_count == 0 || (batch_in && batch_count == 0)) return RS_OK;
+  if (item_count < 0 || item_count > 0x7fffffffLL || batch_count < 0 || batch_count > 65535)
+    return RS_EOVERFLOW;
+  const int64_t work = item_count * (batch_in ? batch_count : 1);
+  if (work > 0x7fffff00LL) return RS_EOVERFLOW;
+  reduce_quant_kernel<<<dim3(unsigned(xcd_grid(work))), dim3(kQuantThreads), 0, st>>>(
       dev.tensors, dev.items, item_off, item_count, static_cast<const uint16_t*>(partials), row_stride,
-      codes, scales, mean_out, elem_base, scale_off, world, 1.0f / float(world));
+      codes, scales, mean_out, batch_in, batch_out, batch_count, write_means ? 1 : 0, elem_base,
+      scale_off, world, 1.0f / float(world));
   return launched();
 }
 

@@ -31,8 +31,9 @@ int launch_block_quant(const DeviceTables& dev, int64_t item_off, int64_t item_c
 // shard_reduce and block_quant in one pass over the rank's quantisation items; mean_out may be null
 int launch_reduce_quant(const DeviceTables& dev, int64_t item_off, int64_t item_count,
                         const void* partials, int64_t row_stride, uint8_t* codes, float* scales,
-                        float* mean_out, int64_t elem_base, int64_t scale_off, int world,
-                        hipStream_t st);
+                        float* mean_out, void* const* batch_in, void* const* batch_out,
+                        int batch_count, bool write_means, int64_t elem_base, int64_t scale_off,
+                        int world, hipStream_t st);
 int launch_dequant_unpack(bool f32_out, const DeviceTables& dev, int n, int64_t n_payload_gran,
                           const uint8_t* codes, const float* scales, void* const* ptrs, int64_t S,
                           int64_t gpr, int64_t region_stride, hipStream_t st);

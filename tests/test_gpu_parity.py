@@ -846,3 +846,62 @@ def test_random_units_all_ops(seed):
         check_dequant_unpack(u, c, s, wc, ws, f"random{seed}")
     finally:
         u.close()
+
+
+@pytest.mark.parametrize("write_means", [False, True])
+def test_reduce_quantize_batch_equals_per_unit(write_means):
+    """rs_reduce_quantize_batch over several units that share a plan: codes, scales and (when
+    asked for) means of every unit equal the oracle's and rs_reduce_quantize's, bit for bit;
+    without write_means the mean buffers are left untouched.  Ragged tensors and padding included."""
+    W, n_units = 5, 4
+    tensors = [(300, 384, MODE_128x128), (1000, 0, MODE_1x128), (257, 130, MODE_128x128), (64, 256, MODE_1x128),
+               (77, 24, MODE_1x128)]
+    u = Unit(tensors, W)
+    try:
+        stride = u.S + 16
+        for rank in (0, 2, W - 1):
+            lo, hi = u.oracle.scale_range(rank)
+            hosts, devs, means, codes, scales, shards = [], [], [], [], [], []
+            for unit in range(n_units):
+                parts = np.stack([normal_bf16(23, unit, 1, 100 * rank + w, u.S, 1e-3 * (unit + 1)) for w in range(W)])
+                padded = np.full((W, stride), 0x7fc0, dtype=np.uint16)     # NaN between the rows
+                padded[:, :u.S] = parts
+                hosts.append(parts)
+                devs.append(to_dev_bf16(padded.reshape(-1)))
+                means.append(torch.full((u.S,), float("nan"), dtype=torch.float32, device="cuda"))
+                codes.append(torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda"))
+                scales.append(torch.full((max(hi - lo, 1),), float("nan"), dtype=torch.float32, device="cuda"))
+                shards.append(torch.zeros(u.S, dtype=torch.bfloat16, device="cuda"))   # required by the batch, not read
+            say(f"reduce_quantize_batch rank {rank}: {n_units} units, write_means={write_means}")
+            pin = B.rs_partials_batch_create(u.plan, rank, devs, stride, means)
+            pout = B.rs_shard_batch_create(u.plan, rank, shards, codes, scales)
+            B.rs_reduce_quantize_batch(u.plan, pin, pout, write_means)
+            torch.cuda.synchronize()
+            for unit in range(n_units):
+                want_c, want_s, want_mean = OF.reduce_quant_shard(u.oracle, rank, hosts[unit])
+                one_c = torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda")
+                one_s = torch.full((max(hi - lo, 1),), float("nan"), dtype=torch.float32, device="cuda")
+                B.rs_reduce_quantize(u.plan, rank, devs[unit], stride, one_c, one_s)
+                torch.cuda.synchronize()
+                got_c, got_s = codes[unit].cpu().numpy(), scales[unit].cpu().numpy()[:hi - lo]
+                assert np.array_equal(got_c, want_c), f"unit {unit} codes"
+                assert np.array_equal(got_s.view(np.uint32), want_s.view(np.uint32)), f"unit {unit} scales"
+                assert np.array_equal(got_c, one_c.cpu().numpy())
+                assert np.array_equal(got_s.view(np.uint32), one_s.cpu().numpy()[:hi - lo].view(np.uint32))
+                got_m = means[unit].cpu().numpy()
+                if write_means:
+                    assert np.array_equal(got_m.view(np.uint32), want_mean.view(np.uint32)), f"unit {unit} mean"
+                else:
+                    assert np.all(np.isnan(got_m)), "mean buffers must not be written"
+            # batches made for another rank or count are refused
+            other = B.rs_shard_batch_create(u.plan, (rank + 1) % W, shards, codes, scales)
+            fewer = B.rs_shard_batch_create(u.plan, rank, shards[:2], codes[:2], scales[:2])
+            for bad in (other, fewer):
+                with pytest.raises(B.RaggedShardError) as e:
+                    B.rs_reduce_quantize_batch(u.plan, pin, bad)
+                assert e.value.code == B.RS_EINVAL
+                B.rs_shard_batch_destroy(bad)
+            B.rs_partials_batch_destroy(pin)
+            B.rs_shard_batch_destroy(pout)
+    finally:
+        u.close()
