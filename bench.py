@@ -92,7 +92,7 @@ CPU_SAMPLE = {
     2: ([0, 2, 1], 1 << 19),                   # norm, wk, wq
     3: ([0, 2, 1], 1 << 20),
     4: ([4, 1, 6], 1 << 18),                   # router, wk, expert 0 down
-    5: ([0, 768], 1 << 15),                    # a routed expert's gate (128x128) and the shared gate (1x128 rows)
+    5: ([0, 1, 2, 3, 4, 5, 768, 769], 1 << 16),   # two routed experts (128x128) and two shared matrices (1x128 rows)
 }
 
 

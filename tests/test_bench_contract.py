@@ -52,6 +52,32 @@ def test_cpu_baseline_leg_reports_what_the_contract_asks():
     assert set(out["per_op_GBps"]) == {"ragged_pack", "shard_reduce", "block_quant", "dequant_unpack"}
 
 
+def test_traffic_figures_come_from_the_committed_counter_summaries(tmp_path):
+    """roofline.traffic is read from profiles/pmc_hbm_traffic_bench_config<N>_*.md: every
+    configuration with FP8 blocks lists the step's four kernels there, the figures are within a few
+    per cent of the algorithmic bytes of the launch the bench times, and a table written by hand
+    parses to the numbers in it."""
+    for idx in (2, 3, 4, 5):
+        wl = WORKLOADS[idx]
+        got = bench.pmc_traffic(idx)
+        step = ["ragged_pack", "shard_reduce", "block_quant", "dequant_unpack"] if idx != 3 else \
+               ["ragged_pack", "shard_reduce", "unpack_bf16"]
+        assert set(step) <= set(got), (idx, sorted(got))
+        specs = [OP.TensorSpec(t.rows, t.cols, t.mode) for t in wl.tensors]
+        plan = OP.make_plan(specs, wl.world, wl.align_bytes, wl.min_itemsize)
+        payload_r = sum(s[3] for s in plan.rank_segments(wl.rank))
+        pack = 2 * plan.payload + 2 * wl.world * plan.S
+        assert 0.95 * pack <= got["ragged_pack"] <= 1.05 * pack, (idx, got["ragged_pack"], pack)
+        one_reduce = 2 * wl.world * payload_r + 4 * plan.S
+        ratio = got["shard_reduce"] / one_reduce          # a whole number of units per launch
+        assert abs(ratio - round(ratio)) <= 0.05 * round(ratio) and round(ratio) >= 1, (idx, ratio)
+    assert bench.pmc_traffic(1) == {} and bench.pmc_traffic(2, str(tmp_path)) == {}
+    (tmp_path / "pmc_hbm_traffic_bench_config9_x.md").write_text(
+        "# title\n\n| operation | kernel | fetch MB | write MB | total MB | algorithmic MB |\n"
+        "|---|---|---|---|---|---|\n| a_b | k<1> | 1.5 | 2.25 | 3.75 | 3.7 |\n| c | k | x | y | n/a | 1 |\n\ntext | with | bars\n")
+    assert bench.pmc_traffic(9, str(tmp_path)) == {"a_b": 3.75e6}
+
+
 @pytest.mark.gpu
 def test_short_run_prints_one_json_line_with_roofline(capsys, monkeypatch):
     monkeypatch.setattr(sys, "argv", ["bench.py", "--workload", "1", "--steps", "2", "--warmup", "1", "--no-cpu"])
