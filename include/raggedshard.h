@@ -289,7 +289,10 @@ int rs_quantize_batch(const rs_plan* plan, const rs_shard_batch* batch, void* st
  *   mean[i] = rs_reduce's out[i], bit for bit (same summation order);
  *   per block: amax = max|mean|, scale = amax/448 (fp32), code = E4M3 RNE of
  *   clamp(mean/scale, +-448) with a correctly rounded fp32 division; a block whose scale is 0
- *   (all zero, or amax below 2^-140) gives scale 0 and codes 0x00.  Padding codes are 0x00.
+ *   (all zero, or amax so small that amax/448 rounds to 0 in fp32, which needs amax below 2^-140)
+ *   gives scale 0 and codes 0x00.  Padding codes are 0x00.
+ * The fp32 mean is quantised as it is, with no rounding to bf16 in between: the codes are in
+ * general NOT those of rs_reduce -> bf16 -> rs_quantize, which rounds twice.
  * partials, row_stride: as for rs_reduce.  codes: device, S uint8, 16-byte aligned; scales:
  * device, the rank's slice [lo, hi).  mean_out: NULL, or device S fp32, 16-byte aligned, which
  * then also receives the mean (0 on padding).  RS_EUNSUPPORTED if the plan holds a tensor
