@@ -81,7 +81,18 @@ __device__ __forceinline__ float bf16_hi(unsigned packed) { return __uint_as_flo
 // midpoint, and its conversion to fp32 rounds it as y would be rounded.  No range restrictions
 // (doubles neither over- nor underflow on fp32 inputs), -0 stays -0, and three full-rate
 // operations per element instead of the twelve or so of the IEEE division sequence.
-__device__ __forceinline__ double shared_reciprocal(float b) { return 1.0 / double(b); }
+// rd need not be the correctly rounded reciprocal: the argument above leaves room for a relative
+// error of 2^-50 in it.  The hardware estimate refined by two Newton steps is within 2^-52 for
+// any estimate good to 2^-13 or better (the error squares in each step), at 5 operations instead
+// of the twenty or so of a double-precision division.  b is a non-negative fp32 number: as a
+// double it is zero or normal, and so is its reciprocal.  b == 0 gives +inf as the division would.
+__device__ __forceinline__ double shared_reciprocal(float b) {
+  const double d = double(b);
+  double r = __builtin_amdgcn_rcp(d);
+  r = __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);
+  r = __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);
+  return b == 0.0f ? __builtin_inf() : r;
+}
 __device__ __forceinline__ float exact_quotient(float x, double rd) { return float(double(x) * rd); }
 
 // Correctly rounded fp32 square root of x >= 0 from the hardware's 1-ulp estimate s: the true root
@@ -89,12 +100,14 @@ __device__ __forceinline__ float exact_quotient(float x, double rd) { return flo
 // midpoint; x - s * (s - 1 ulp) is a whole multiple of ulp(s)^2, so the quarter-ulp^2 between the
 // two cannot matter), to s + 1 ulp when x > s * (s + 1 ulp), both residuals exact in one FMA each.
 // Zero comes out as zero (the lower neighbour is a NaN pattern, its test false).  Valid for zero
-// and for x in [2^-100, 2^100); outside, the estimate's own input scaling would be needed and the
-// compiler's sequence is taken instead (a branch uniform across the wavefront, all but never taken).
+// and for x >= 2^-100 (the residuals are multiples of ulp(s)^2 >= 2^-146, exactly representable;
+// the products inside the FMAs are exact, so large x cannot overflow them); below, the
+// estimate's own input scaling would be needed and the compiler's sequence is taken instead (a
+// branch uniform across the wavefront, all but never taken).
 __device__ __forceinline__ float exact_sqrt(float x) {
-  const unsigned e = (__float_as_uint(x) >> 23) & 0xffu;
-  const bool in_range = (x == 0.0f) | ((e >= 27u) & (e < 227u));
-  if (__builtin_amdgcn_ballot_w64(!in_range) != 0) return __builtin_sqrtf(x);
+  // out of range: 0 < x < 2^-100, as one unsigned comparison of the bit pattern
+  const bool low = (__float_as_uint(x) - 1u) < ((27u << 23) - 1u);
+  if (__builtin_amdgcn_ballot_w64(low) != 0) return __builtin_sqrtf(x);
   const float s = __builtin_amdgcn_sqrtf(x);
   const float dn = __uint_as_float(__float_as_uint(s) - 1u), up = __uint_as_float(__float_as_uint(s) + 1u);
   const float t_dn = __builtin_fmaf(-dn, s, x), t_up = __builtin_fmaf(-up, s, x);
