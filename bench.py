@@ -89,10 +89,10 @@ def pmc_traffic(config_index, profiles_dir=None):
 # tensors of the sample (indices into the configuration's list) and the columns of the reduce sample
 CPU_SAMPLE = {
     1: ([0, 1, 2, 3, 4, 5], None),             # the whole toy unit
-    2: ([0, 2, 1], 1 << 19),                   # norm, wk, wq
+    2: ([0, 1, 2, 3, 4, 5, 6, 7, 8], 1 << 20),  # the whole unit
     3: ([0, 2, 1], 1 << 20),
     4: ([4, 1, 6], 1 << 18),                   # router, wk, expert 0 down
-    5: ([0, 1, 2, 3, 4, 5, 768, 769], 1 << 16),   # two routed experts (128x128) and two shared matrices (1x128 rows)
+    5: ([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 768, 769], 1 << 16),   # four routed experts (128x128), two shared matrices (1x128 rows)
 }
 
 
