@@ -168,8 +168,8 @@ def test_config2_dequant_unpack(cfg2):
 def test_config2_batched_launches_as_the_bench_launches_them(cfg2):
     """The launch shapes bench.py times on config 2 besides the per-unit ones: rank 0's shard of
     32 units in ONE block_quant launch, the same for the 8-bit Adam step, and rank 0's region of
-    32 units in ONE reduce launch; every unit's outputs against the oracle (quantise, reduce) or
-    against the per-unit launch (Adam)."""
+    32 units in ONE reduce launch and in ONE fused reduce + quantise launch; every unit's outputs
+    against the oracle (quantise, reduce) or against the per-unit launch (fused, Adam)."""
     from workloads import normal_bf16
     u, wl = cfg2.unit, WORKLOADS[2]
     rank, n_units, S = wl.rank, wl.units, cfg2.unit.S
@@ -218,7 +218,28 @@ def test_config2_batched_launches_as_the_bench_launches_them(cfg2):
             err = np.abs(got.astype(np.float64) - OC.shard_reduce(sub, segs))
             assert np.all(err <= REDUCE_TOL * OC.shard_reduce_abs_sum(sub)), f"unit {unit}"
             assert np.array_equal(got.view(np.uint32), OC.shard_reduce_f32_ordered(sub, segs).view(np.uint32))
-    del parts, outs
+    # the fused reduce + quantise over the same 32 regions in one launch: every unit equal to
+    # its own rs_reduce_quantize (which the test above holds against the oracle at this size),
+    # means equal to the reduce's
+    say("config 2: reduce_quantize_batch")
+    f_codes = [torch.full((S,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(n_units)]
+    f_scales = [torch.full((hi - lo,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_units)]
+    f_means = [torch.full((S,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_units)]
+    pin = B.rs_partials_batch_create(u.plan, rank, parts, S, f_means)
+    pout = B.rs_shard_batch_create(u.plan, rank, f_means, f_codes, f_scales)   # shard pointers are not read
+    B.rs_reduce_quantize_batch(u.plan, pin, pout, True)
+    torch.cuda.synchronize()
+    B.rs_partials_batch_destroy(pin)
+    B.rs_shard_batch_destroy(pout)
+    one_c = torch.empty(S, dtype=torch.uint8, device="cuda")
+    one_s = torch.empty(hi - lo, dtype=torch.float32, device="cuda")
+    for unit in range(n_units):
+        B.rs_reduce_quantize(u.plan, rank, parts[unit], S, one_c, one_s)
+        torch.cuda.synchronize()
+        assert torch.equal(f_codes[unit], one_c), f"unit {unit}: fused batch codes"
+        assert torch.equal(f_scales[unit].view(torch.int32), one_s.view(torch.int32)), f"unit {unit}: fused batch scales"
+        assert torch.equal(f_means[unit].view(torch.int32), outs[unit].view(torch.int32)), f"unit {unit}: fused batch mean"
+    del parts, outs, f_codes, f_scales, f_means
 
     slo, shi = B.rs_plan_state_range(u.plan, rank)
     gen.manual_seed(99)
@@ -495,6 +516,38 @@ def test_moe_unit_padding_and_rank_launch(idx):
     torch.cuda.synchronize()
     assert torch.equal(c_r, st.codes[k * u.S:(k + 1) * u.S])
     assert torch.equal(s_r[:hi - lo].view(torch.int32), st.scales[lo:hi].view(torch.int32))
+    # the launch bench.py times in the step: rank k's shard of all the layers it holds, one launch.
+    # Shard 0 is the unit's own (already held against the oracle through st.codes), the others are
+    # fresh draws with +0 on the region's padding; every shard must equal its own rs_quantize.
+    import bench
+    n_sh = bench.QUANT_SHARDS[idx]
+    say(f"config {idx}: quantize_batch over rank {k}'s shard of {n_sh} units")
+    pay = torch.zeros(u.S, dtype=torch.bool, device="cuda")
+    for _, _, d, n in u.oracle.rank_segments(k):
+        pay[d:d + n] = True
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4242 + idx)
+    shards = [st.dbuf[k * u.S:(k + 1) * u.S]]
+    for _ in range(n_sh - 1):
+        x = torch.empty(u.S, dtype=torch.bfloat16, device="cuda").normal_(0, wl.sigma, generator=gen)
+        shards.append(torch.where(pay, x, torch.zeros_like(x)))
+    codes = [torch.full((u.S,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(n_sh)]
+    scales = [torch.full((max(1, hi - lo),), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_sh)]
+    batch = B.rs_shard_batch_create(u.plan, k, shards, codes, scales)
+    B.rs_quantize_batch(u.plan, batch)
+    torch.cuda.synchronize()
+    B.rs_shard_batch_destroy(batch)
+    assert torch.equal(codes[0], c_r) and torch.equal(scales[0].view(torch.int32), s_r.view(torch.int32))
+    for i in range(1, n_sh):
+        B.rs_quantize(u.plan, k, shards[i], c_r, s_r)
+        torch.cuda.synchronize()
+        assert torch.equal(codes[i], c_r), f"shard {i}: batch != rs_quantize"
+        assert torch.equal(scales[i].view(torch.int32), s_r.view(torch.int32)), f"shard {i} scales"
+    # one of the fresh shards through the oracle as well (whole shard)
+    oc, os_ = OF.block_quant_shard(u.oracle, k, bits_of(shards[n_sh - 1]))
+    assert np.array_equal(codes[n_sh - 1].cpu().numpy(), oc)
+    assert np.array_equal(scales[n_sh - 1].cpu().numpy()[:hi - lo].view(np.uint32), os_.view(np.uint32))
+    del shards, codes, scales
     # the tensors that touch a rank boundary among the first 8 ranks, the rank of interest, and the
     # ends of the unit lie in the chunks above; name them so a reader can see they are covered
     touching = sorted({t for kk in range(1, 9) for t, (s, l) in enumerate(zip(u.specs, u.oracle.offsets))
